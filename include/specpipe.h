@@ -1,0 +1,235 @@
+/*
+ * specpipe.h -- C ABI of the SpecPipe stage library for AMD MI355X (gfx950).
+ *
+ * One pipeline stage of SpecPipe (arXiv 2504.04104): the stage's decoder layers
+ * run on newly inserted nodes of the dynamic speculative token tree
+ * ("node-wise computation", Sec. 3.3.2, Algorithm 1 lines 1-3), and pruning
+ * propagation compacts the tree tables and the KV cache once a token has been
+ * verified (Sec. 3.2 "to-subtree pruning", Sec. 3.3.2, Algorithm 1 lines 5-7).
+ *
+ * Numbering.  The paper's tree has the last verified token as root tau_1.  Here
+ * that root is the last token of the committed context ("prefix"), and only the
+ * speculative tokens are numbered: node k of a request is the paper's
+ * tau_(k+2); parent -1 means "child of the root".  Parents always have a
+ * smaller index than their children.  depth(k) = 0 for children of the root.
+ * A request's committed context has prefix_len tokens (root included) and its
+ * tree has n_live nodes; node k's K/V rows live in cache slot
+ * slot_base + prefix_len + k, and it stands for sequence position
+ * prefix_len + depth(k) (each tree level is one future position, Sec. 3.2).
+ *
+ * Memory.  Every device byte is owned by the caller: weights, the KV slab, the
+ * table arena and the workspace are passed in as device pointers and must stay
+ * valid until sp_stage_destroy().  The library allocates no device memory and
+ * creates no streams.  All device work of a call is enqueued on the stream
+ * passed to it, in call order; calls return without waiting for the GPU unless
+ * stated.  Host arrays passed in are read before the call returns.
+ *
+ * KV slab layout (element type = config dtype), index order slowest to fastest:
+ *     [layer][K=0|V=1][kv_head][slot][d_head]
+ * with `kv_slots` slots per head.  K rows are stored rotated (post-RoPE).  A
+ * request owns the slot range [slot_base, slot_base + capacity).  One K or V
+ * row of one token is n_kv_heads * d_head elements, i.e. 2*8*128*2 B = 4096 B
+ * per token per layer for the 70B shape in bf16 (Sec. 4.5, Table 1).
+ *
+ * Weights: every matrix is [out_features][in_features] row-major (y = x W^T), in
+ * the config dtype.  wqkv stacks the query rows, then the key rows, then the
+ * value rows; wgu stacks the gate rows, then the up rows.
+ *
+ * Errors: every call returns SP_OK (0) or a negative sp_status; on error the
+ * state is unchanged.  A handle is not thread-safe.
+ */
+#ifndef SPECPIPE_H
+#define SPECPIPE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define SP_VERSION 1
+#define SP_MAX_TREE_NODES 256   /* live speculative nodes per request            */
+#define SP_MAX_BATCH_REQ 64     /* requests per sp_stage_forward / *_batch call   */
+#define SP_ANC_WORDS 4          /* 64-bit words of one ancestor-bitmask row       */
+
+typedef struct sp_stage sp_stage;
+typedef void* sp_stream;        /* a hipStream_t; NULL = the default stream */
+
+typedef enum sp_status {
+  SP_OK = 0,
+  SP_E_INVALID = -1,      /* null pointer, bad size, bad config                       */
+  SP_E_CAPACITY = -2,     /* tree, slot range, batch or workspace too small           */
+  SP_E_BAD_PARENT = -3,   /* parent not in {-1} U [0, index of the child)             */
+  SP_E_BAD_REQ = -4,      /* request id out of range or not initialised               */
+  SP_E_BAD_NODE = -5,     /* node index outside the live tree                         */
+  SP_E_ORDER = -6,        /* forward of a node whose parent has not been forwarded    */
+  SP_E_PENDING = -7,      /* a prune awaits sp_kv_compact (or none does)              */
+  SP_E_HIP = -8,          /* a HIP runtime call failed; see sp_last_hip_error()       */
+  SP_E_UNSUPPORTED = -9   /* shape or dtype the kernels do not cover                  */
+} sp_status;
+
+typedef enum sp_dtype { SP_F32 = 0, SP_BF16 = 1 } sp_dtype;
+typedef enum sp_prune_mode { SP_ACCEPT = 0, SP_DROP = 1 } sp_prune_mode;
+
+/* sp_config.flags */
+#define SP_FLAG_SIMPLE_KERNELS 1u   /* use the plain (non-MFMA) kernels for every step */
+
+typedef struct sp_config {
+  int32_t n_layers;
+  int32_t d_model;
+  int32_t n_q_heads;
+  int32_t n_kv_heads;      /* divides n_q_heads; query head h reads KV head h / (n_q/n_kv) */
+  int32_t d_head;          /* even, multiple of 8, <= 256 */
+  int32_t d_ff;
+  float rms_eps;
+  float rope_theta;        /* angle of pair t at position p: p * theta^(-2t/d_head); pairs (t, t+d_head/2) */
+  int32_t dtype;           /* sp_dtype: storage type of weights, hidden rows and KV */
+  int32_t max_requests;
+  int32_t max_tree_nodes;  /* <= SP_MAX_TREE_NODES */
+  int32_t max_batch_nodes; /* most rows (sum of n_nodes) one sp_stage_forward call may carry */
+  int64_t kv_slots;        /* slots per (layer, K|V, head) plane of the slab */
+  uint32_t flags;
+} sp_config;
+
+/* Device pointers of one layer's weights. */
+typedef struct sp_layer_weights {
+  const void* wqkv;    /* [(n_q + 2 n_kv) * d_head][d_model] */
+  const void* wo;      /* [d_model][n_q * d_head]            */
+  const void* wgu;     /* [2 * d_ff][d_model]: gate, then up */
+  const void* wd;      /* [d_model][d_ff]                    */
+  const void* norm1;   /* [d_model] gain of the attention RMSNorm */
+  const void* norm2;   /* [d_model] gain of the FFN RMSNorm       */
+} sp_layer_weights;
+
+typedef struct sp_sizes {
+  size_t kv_bytes;         /* KV slab */
+  size_t tables_bytes;     /* per-request tree tables and prune maps */
+  size_t workspace_bytes;  /* activations and partial results of one forward call */
+  size_t kv_plane_bytes;   /* bytes between consecutive kv_heads   */
+  size_t kv_row_bytes;     /* bytes of one (slot, head) row = d_head * element size */
+} sp_sizes;
+
+typedef struct sp_buffers {
+  void* kv;        size_t kv_bytes;
+  void* tables;    size_t tables_bytes;
+  void* workspace; size_t workspace_bytes;
+} sp_buffers;
+
+/* Host copy of one request's tables, for tests and debugging (Sec. 3.2: I, P and M;
+ * M is held as one ancestor bitmask per node: bit j of anc[i] is M[i][j]). */
+typedef struct sp_tree_view {
+  int32_t prefix_len;
+  int32_t n_live;
+  int32_t parent[SP_MAX_TREE_NODES];
+  int32_t depth[SP_MAX_TREE_NODES];
+  int32_t token[SP_MAX_TREE_NODES];
+  float prob[SP_MAX_TREE_NODES];
+  uint64_t anc[SP_MAX_TREE_NODES][SP_ANC_WORDS];
+} sp_tree_view;
+
+/* ---- set-up ---------------------------------------------------------------- */
+
+/* Buffer sizes a stage of this config needs.  Pure host arithmetic. */
+int sp_stage_query_sizes(const sp_config* cfg, sp_sizes* out);
+
+/* Builds a stage.  `layers` is a host array of n_layers entries holding device
+ * pointers.  Buffers must be at least as large as sp_stage_query_sizes() says and
+ * 256-byte aligned.  The tables buffer is initialised on `stream`. */
+int sp_stage_create(const sp_config* cfg, const sp_layer_weights* layers, const sp_buffers* buffers,
+                    sp_stream stream, sp_stage** out);
+void sp_stage_destroy(sp_stage* stage);
+
+/* Declares request `req`: it owns slots [slot_base, slot_base+capacity) of every
+ * plane, of which the first prefix_len (>= 1: the root) already hold the rotated K
+ * and V of the committed context for every layer.  Its tree becomes empty.  May be
+ * called again to reset a request. */
+int sp_request_init(sp_stage* stage, int32_t req, int64_t slot_base, int32_t capacity,
+                    int32_t prefix_len, sp_stream stream);
+
+/* ---- the hot path ------------------------------------------------------------ */
+
+/* Layer appending (Sec. 3.2): appends n_new nodes to request `req`.  parents[k] is
+ * -1, a live node, or one of this call's earlier nodes.  The new nodes get indices
+ * n_live .. n_live+n_new-1 in argument order (*first_index_out = old n_live); pass
+ * them sorted by parent order to keep the paper's level-by-level indexing.  tokens
+ * (I) and probs (P) are carried, compacted and returned but never interpreted; NULL
+ * stores zeros.  Errors: SP_E_CAPACITY (tree or slot range full), SP_E_BAD_PARENT,
+ * SP_E_BAD_REQ, SP_E_PENDING. */
+int sp_tree_insert(sp_stage* stage, int32_t req, int32_t n_new, const int32_t* parents /*host*/,
+                   const int32_t* tokens /*host, nullable*/, const float* probs /*host, nullable*/,
+                   int32_t* first_index_out /*host, nullable*/, sp_stream stream);
+
+/* Node-wise computation (Algorithm 1 lines 1-3): runs every layer of the stage on
+ * nodes [first_node[i], first_node[i]+n_nodes[i]) of request req_ids[i], i < n_req,
+ * under the tree mask: a node attends to its request's committed context and to
+ * itself and its ancestors.  x_in / x_out: device, [sum n_nodes][d_model] in the
+ * config dtype, rows ordered by (position in req_ids, node index); they may alias.
+ * The nodes' K and V rows are written to the slab.  A node's parent must have been
+ * forwarded before or be part of this call (SP_E_ORDER).  A request may appear once. */
+int sp_stage_forward(sp_stage* stage, int32_t n_req, const int32_t* req_ids /*host*/,
+                     const int32_t* first_node /*host*/, const int32_t* n_nodes /*host*/,
+                     const void* x_in /*device*/, void* x_out /*device*/, sp_stream stream);
+
+/* Pruning propagation, table part (Sec. 3.2, Algorithm 1 lines 5 and 7).
+ * SP_ACCEPT(node): the verified token is `node`.  The path root..node joins the
+ *   committed context (prefix_len grows by depth(node)+1 = *n_commit_out); the strict
+ *   descendants of `node` stay as the tree, re-indexed by rank; children of `node`
+ *   get parent -1; depths shrink by n_commit.
+ * SP_DROP(node): `node` and its descendants leave the tree; nothing is committed.
+ * Computes the keep flags from the mask column, their prefix sums, and the compacted
+ * tables on the device, and leaves the old->new map there for sp_kv_compact, which
+ * must be the next call for this request.  Outputs are computed on the host mirror. */
+int sp_tree_prune(sp_stage* stage, int32_t req, int32_t mode, int32_t node,
+                  int32_t* n_live_out /*host, nullable*/, int32_t* n_commit_out /*host, nullable*/,
+                  sp_stream stream);
+
+/* Pruning propagation, cache part (Algorithm 1 line 6): K and V rows of the kept
+ * nodes -- for SP_ACCEPT the mask is row(node) OR col(node), so the committed path
+ * comes first -- move, in order, to the slots right after the old committed context,
+ * for every layer.  If x_rows != NULL it holds n_rows hidden rows [n_rows][d_model]
+ * (device) of nodes row_nodes[] (host; indices from before the prune, ascending):
+ * rows whose node is outside col(node) (resp. inside the dropped subtree) are
+ * removed in place (Algorithm 1 line 5).  *n_rows_out = surviving rows;
+ * row_nodes_out[i] = new index of the node of surviving row i (-1 for the accepted
+ * node itself, which is now the root).  Clears the pending state. */
+int sp_kv_compact(sp_stage* stage, int32_t req, void* x_rows /*device, nullable*/, int32_t n_rows,
+                  const int32_t* row_nodes /*host*/, int32_t* n_rows_out /*host, nullable*/,
+                  int32_t* row_nodes_out /*host, nullable*/, sp_stream stream);
+
+/* The same two steps for several requests in one launch each (dynamic batching,
+ * Sec. 4 "Implementation").  Entries with modes[i] < 0 are skipped. */
+int sp_tree_prune_batch(sp_stage* stage, int32_t n, const int32_t* req_ids, const int32_t* modes,
+                        const int32_t* nodes, int32_t* n_live_out /*nullable*/,
+                        int32_t* n_commit_out /*nullable*/, sp_stream stream);
+int sp_kv_compact_batch(sp_stage* stage, int32_t n, const int32_t* req_ids, sp_stream stream);
+
+/* ---- inspection ------------------------------------------------------------- */
+
+/* Copies a request's device tables to the host.  Waits for `stream`. */
+int sp_tree_read(sp_stage* stage, int32_t req, sp_tree_view* out /*host*/, sp_stream stream);
+
+/* Host mirror of a request's counters; no GPU access. */
+int sp_request_info(const sp_stage* stage, int32_t req, int32_t* prefix_len, int32_t* n_live,
+                    int32_t* n_forwarded);
+
+/* Per-kernel timing.  After sp_profile_begin(kind), every launch of that kernel
+ * kind is bracketed by HIP events on its stream (at most max_launches of them);
+ * sp_profile_end waits for the last event and returns the launch count and the sum
+ * of their durations. */
+typedef enum sp_kernel_kind {
+  SP_K_NONE = 0, SP_K_GEMM_QKV = 1, SP_K_GEMM_O = 2, SP_K_GEMM_GATEUP = 3, SP_K_GEMM_DOWN = 4,
+  SP_K_ATTENTION = 5, SP_K_ATTENTION_MERGE = 6, SP_K_KV_COMPACT = 7, SP_K_TREE_PRUNE = 8,
+  SP_K_TREE_INSERT = 9, SP_K_NORM = 10, SP_K_ROPE_KV = 11, SP_K_KIND_COUNT = 12
+} sp_kernel_kind;
+int sp_profile_begin(sp_stage* stage, int32_t kind, int32_t max_launches);
+int sp_profile_end(sp_stage* stage, int32_t* n_launches, float* total_ms);
+
+const char* sp_strerror(int status);
+int sp_version(void);
+int sp_last_hip_error(const sp_stage* stage);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SPECPIPE_H */

@@ -1,0 +1,591 @@
+// Host side of the SpecPipe stage library: argument checks against a host mirror of
+// the tree, workspace carving, and the per-layer launch sequence.  No device memory
+// is allocated here and nothing waits for the GPU except sp_tree_read and
+// sp_profile_end.
+#include <cmath>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "../../include/specpipe.h"
+#include "sp_launch.h"
+
+static_assert(SP_T == SP_MAX_TREE_NODES, "tree capacity");
+static_assert(SP_W == SP_ANC_WORDS, "mask words");
+static_assert(SP_BATCH == SP_MAX_BATCH_REQ, "batch capacity");
+
+namespace {
+
+struct HostReq {
+  bool active = false;
+  long long base = 0;
+  int cap = 0, P = 0, T = 0;
+  short parent[SP_T];
+  unsigned char fwd[SP_T];      // node's K/V rows exist at this stage
+  bool pending = false;         // a prune awaits its cache compaction
+  int pend_mode = 0, pend_node = 0;
+  short pend_tab_new[SP_T];     // old node -> new index, -1 gone
+};
+
+inline size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
+
+struct Workspace {
+  RowInfo* rows = nullptr;
+  float* cs = nullptr;
+  float* h = nullptr;
+  void* xn = nullptr;
+  void* qbuf = nullptr;
+  void* attn = nullptr;
+  void* act = nullptr;
+  float* part = nullptr;
+  float* attn_part = nullptr;
+  size_t part_floats = 0;
+  size_t attn_units = 0;
+  size_t total = 0;
+};
+
+inline int elt_bytes(int dtype) { return dtype == SP_BF16 ? 2 : 4; }
+
+// Lays the workspace out from `base` (may be null: sizes only).
+Workspace carve(const sp_config& c, char* base) {
+  Workspace w;
+  const size_t MB = align_up((size_t)c.max_batch_nodes, 16);
+  const size_t eb = elt_bytes(c.dtype);
+  const size_t dq = (size_t)c.n_q_heads * c.d_head, dkv = (size_t)c.n_kv_heads * c.d_head;
+  const size_t nqkv = dq + 2 * dkv;
+  size_t off = 0;
+  auto take = [&](size_t bytes) { char* p = base ? base + off : nullptr; off += align_up(bytes); return (void*)p; };
+  w.rows = (RowInfo*)take(MB * sizeof(RowInfo));
+  w.cs = (float*)take(MB * c.d_head * sizeof(float));
+  w.h = (float*)take(MB * c.d_model * sizeof(float));
+  w.xn = take(MB * c.d_model * eb);
+  w.qbuf = take(MB * dq * eb);
+  w.attn = take(MB * dq * eb);
+  w.act = take(MB * (size_t)c.d_ff * eb);
+  // partial sums of the split projections, or the unfused gate/up output
+  const size_t part_rows = MB > 1024 ? MB : 1024;
+  const size_t nmax = nqkv > (size_t)c.d_model ? nqkv : (size_t)c.d_model;
+  size_t pf = part_rows * nmax;
+  const size_t gu = MB * 2 * (size_t)c.d_ff;
+  if (gu > pf) pf = gu;
+  w.part_floats = pf;
+  w.part = (float*)take(pf * sizeof(float));
+  // split-KV attention partials: (max, sum, d_head outputs) per (row, head, chunk)
+  w.attn_units = (MB > 64 ? MB : 64) * (size_t)c.n_q_heads * 32;
+  w.attn_part = (float*)take(w.attn_units * (size_t)(c.d_head + 2) * sizeof(float));
+  w.total = off;
+  return w;
+}
+
+int check_config(const sp_config* c) {
+  if (!c) return SP_E_INVALID;
+  if (c->n_layers < 1 || c->d_model < 8 || c->n_q_heads < 1 || c->n_kv_heads < 1 || c->d_ff < 8) return SP_E_INVALID;
+  if (c->n_q_heads % c->n_kv_heads) return SP_E_INVALID;
+  if (c->dtype != SP_F32 && c->dtype != SP_BF16) return SP_E_INVALID;
+  if (c->max_requests < 1 || c->max_tree_nodes < 1 || c->max_tree_nodes > SP_MAX_TREE_NODES) return SP_E_INVALID;
+  if (c->max_batch_nodes < 1 || c->kv_slots < 1) return SP_E_INVALID;
+  if (c->d_model % 8 || c->d_ff % 8) return SP_E_UNSUPPORTED;
+  if (c->d_head != 64 && c->d_head != 128) return SP_E_UNSUPPORTED;
+  if (!(c->rms_eps > 0.f) || !(c->rope_theta > 1.f)) return SP_E_INVALID;
+  return SP_OK;
+}
+
+}  // namespace
+
+struct sp_stage {
+  sp_config cfg;
+  std::vector<sp_layer_weights> W;
+  sp_buffers buf;
+  sp_sizes sizes;
+  ReqMeta* d_meta = nullptr;
+  ReqTables* d_tables = nullptr;
+  Workspace ws;
+  KvGeom geom;
+  std::vector<HostReq> reqs;
+  bool fast = false;           // bf16 MFMA kernels in use
+  int last_hip = 0;
+  // profiling
+  int prof_kind = 0, prof_max = 0, prof_n = 0;
+  std::vector<hipEvent_t> prof_ev;
+};
+
+namespace {
+
+inline int hip_fail(sp_stage* s, hipError_t e) {
+  s->last_hip = (int)e;
+  return SP_E_HIP;
+}
+
+// Brackets a launch with events when its kind is being profiled.
+struct ProfScope {
+  sp_stage* s;
+  hipStream_t st;
+  bool on;
+  ProfScope(sp_stage* s_, int kind, hipStream_t st_) : s(s_), st(st_) {
+    on = (s->prof_kind == kind && s->prof_n < s->prof_max);
+    if (on) hipEventRecord(s->prof_ev[2 * s->prof_n], st);
+  }
+  ~ProfScope() {
+    if (on) { hipEventRecord(s->prof_ev[2 * s->prof_n + 1], st); ++s->prof_n; }
+  }
+};
+
+size_t tables_meta_bytes(const sp_config& c) { return align_up((size_t)c.max_requests * sizeof(ReqMeta)); }
+
+HostReq* get_req(sp_stage* s, int req) {
+  if (!s || req < 0 || req >= (int)s->reqs.size() || !s->reqs[req].active) return nullptr;
+  return &s->reqs[req];
+}
+
+// Host mirror of a prune: same result as the device kernel, computed from the
+// parent list instead of the bitmask.  Fills tab_new and returns counts.
+void mirror_prune(HostReq& r, int mode, int node, int* n_tab, int* n_commit) {
+  bool in_col[SP_T];
+  for (int i = 0; i < r.T; ++i)
+    in_col[i] = (i == node) || (r.parent[i] >= 0 && in_col[r.parent[i]]);
+  int commit = 0;
+  if (mode == SP_ACCEPT) for (int j = node; j >= 0; j = r.parent[j]) ++commit;
+  short parent_new[SP_T];
+  unsigned char fwd_new[SP_T];
+  int k = 0;
+  for (int i = 0; i < r.T; ++i) {
+    const bool keep = (mode == SP_ACCEPT) ? (in_col[i] && i != node) : !in_col[i];
+    r.pend_tab_new[i] = keep ? (short)k : (short)-1;
+    if (keep) {
+      const int p = r.parent[i];
+      parent_new[k] = (p >= 0 && r.pend_tab_new[p] >= 0) ? r.pend_tab_new[p] : (short)-1;
+      fwd_new[k] = r.fwd[i];
+      ++k;
+    }
+  }
+  for (int i = r.T; i < SP_T; ++i) r.pend_tab_new[i] = -1;
+  std::memcpy(r.parent, parent_new, sizeof(short) * k);
+  std::memcpy(r.fwd, fwd_new, k);
+  r.T = k;
+  r.P += commit;
+  *n_tab = k;
+  *n_commit = commit;
+}
+
+}  // namespace
+
+extern "C" {
+
+int sp_version(void) { return SP_VERSION; }
+
+const char* sp_strerror(int status) {
+  switch (status) {
+    case SP_OK: return "ok";
+    case SP_E_INVALID: return "invalid argument";
+    case SP_E_CAPACITY: return "capacity exceeded";
+    case SP_E_BAD_PARENT: return "bad parent index";
+    case SP_E_BAD_REQ: return "bad or uninitialised request";
+    case SP_E_BAD_NODE: return "bad node index";
+    case SP_E_ORDER: return "parent not forwarded yet";
+    case SP_E_PENDING: return "prune/compact out of order";
+    case SP_E_HIP: return "HIP runtime error";
+    case SP_E_UNSUPPORTED: return "unsupported shape or dtype";
+    default: return "unknown status";
+  }
+}
+
+int sp_last_hip_error(const sp_stage* stage) { return stage ? stage->last_hip : 0; }
+
+int sp_stage_query_sizes(const sp_config* cfg, sp_sizes* out) {
+  int rc = check_config(cfg);
+  if (rc != SP_OK) return rc;
+  if (!out) return SP_E_INVALID;
+  const size_t row = (size_t)cfg->d_head * elt_bytes(cfg->dtype);
+  out->kv_row_bytes = row;
+  out->kv_plane_bytes = (size_t)cfg->kv_slots * row;
+  out->kv_bytes = (size_t)cfg->n_layers * 2 * cfg->n_kv_heads * out->kv_plane_bytes;
+  out->tables_bytes = tables_meta_bytes(*cfg) + align_up((size_t)cfg->max_requests * sizeof(ReqTables));
+  out->workspace_bytes = carve(*cfg, nullptr).total;
+  return SP_OK;
+}
+
+int sp_stage_create(const sp_config* cfg, const sp_layer_weights* layers, const sp_buffers* buffers,
+                    sp_stream stream, sp_stage** out) {
+  int rc = check_config(cfg);
+  if (rc != SP_OK) return rc;
+  if (!layers || !buffers || !out) return SP_E_INVALID;
+  sp_sizes sz;
+  sp_stage_query_sizes(cfg, &sz);
+  if (!buffers->kv || !buffers->tables || !buffers->workspace) return SP_E_INVALID;
+  if (buffers->kv_bytes < sz.kv_bytes || buffers->tables_bytes < sz.tables_bytes ||
+      buffers->workspace_bytes < sz.workspace_bytes)
+    return SP_E_CAPACITY;
+  if (((uintptr_t)buffers->kv | (uintptr_t)buffers->tables | (uintptr_t)buffers->workspace) & 255) return SP_E_INVALID;
+  for (int l = 0; l < cfg->n_layers; ++l) {
+    const sp_layer_weights& w = layers[l];
+    if (!w.wqkv || !w.wo || !w.wgu || !w.wd || !w.norm1 || !w.norm2) return SP_E_INVALID;
+    if (((uintptr_t)w.wqkv | (uintptr_t)w.wo | (uintptr_t)w.wgu | (uintptr_t)w.wd) & 15) return SP_E_INVALID;
+  }
+  sp_stage* s = new (std::nothrow) sp_stage();
+  if (!s) return SP_E_INVALID;
+  s->cfg = *cfg;
+  s->W.assign(layers, layers + cfg->n_layers);
+  s->buf = *buffers;
+  s->sizes = sz;
+  s->d_meta = (ReqMeta*)buffers->tables;
+  s->d_tables = (ReqTables*)((char*)buffers->tables + tables_meta_bytes(*cfg));
+  s->ws = carve(*cfg, (char*)buffers->workspace);
+  s->geom.kv = (char*)buffers->kv;
+  s->geom.plane_bytes = sz.kv_plane_bytes;
+  s->geom.row_bytes = (int)sz.kv_row_bytes;
+  s->geom.n_layers = cfg->n_layers;
+  s->geom.n_kv_heads = cfg->n_kv_heads;
+  s->reqs.resize(cfg->max_requests);
+  // The MFMA kernels cover bf16 with d_head 128 and dimensions that fill their tiles.
+  s->fast = cfg->dtype == SP_BF16 && !(cfg->flags & SP_FLAG_SIMPLE_KERNELS) && cfg->d_head == 128 &&
+            cfg->d_model % 256 == 0 && cfg->d_ff % 256 == 0 &&
+            (cfg->n_q_heads * cfg->d_head) % 256 == 0;
+  hipError_t e = sp_launch_tables_clear(s->d_meta, s->d_tables, cfg->max_requests, (hipStream_t)stream);
+  if (e != hipSuccess) { delete s; return SP_E_HIP; }
+  *out = s;
+  return SP_OK;
+}
+
+void sp_stage_destroy(sp_stage* stage) {
+  if (!stage) return;
+  for (hipEvent_t ev : stage->prof_ev) hipEventDestroy(ev);
+  delete stage;
+}
+
+int sp_request_init(sp_stage* s, int32_t req, int64_t slot_base, int32_t capacity, int32_t prefix_len,
+                    sp_stream stream) {
+  if (!s) return SP_E_INVALID;
+  if (req < 0 || req >= (int)s->reqs.size()) return SP_E_BAD_REQ;
+  if (slot_base < 0 || capacity < 1 || prefix_len < 1) return SP_E_INVALID;
+  if (prefix_len > capacity || slot_base + capacity > s->cfg.kv_slots) return SP_E_CAPACITY;
+  hipError_t e = sp_launch_request_init(s->d_meta, s->d_tables, req, slot_base, capacity, prefix_len,
+                                        (hipStream_t)stream);
+  if (e != hipSuccess) return hip_fail(s, e);
+  HostReq& r = s->reqs[req];
+  r.active = true; r.base = slot_base; r.cap = capacity; r.P = prefix_len; r.T = 0; r.pending = false;
+  return SP_OK;
+}
+
+int sp_request_info(const sp_stage* s, int32_t req, int32_t* prefix_len, int32_t* n_live, int32_t* n_forwarded) {
+  if (!s) return SP_E_INVALID;
+  if (req < 0 || req >= (int)s->reqs.size() || !s->reqs[req].active) return SP_E_BAD_REQ;
+  const HostReq& r = s->reqs[req];
+  if (prefix_len) *prefix_len = r.P;
+  if (n_live) *n_live = r.T;
+  if (n_forwarded) { int f = 0; for (int i = 0; i < r.T; ++i) f += r.fwd[i]; *n_forwarded = f; }
+  return SP_OK;
+}
+
+int sp_tree_insert(sp_stage* s, int32_t req, int32_t n_new, const int32_t* parents, const int32_t* tokens,
+                   const float* probs, int32_t* first_index_out, sp_stream stream) {
+  if (!s) return SP_E_INVALID;
+  HostReq* r = get_req(s, req);
+  if (!r) return SP_E_BAD_REQ;
+  if (n_new < 0 || (n_new > 0 && !parents)) return SP_E_INVALID;
+  if (r->pending) return SP_E_PENDING;
+  if (r->T + n_new > s->cfg.max_tree_nodes || r->P + r->T + n_new > r->cap) return SP_E_CAPACITY;
+  for (int k = 0; k < n_new; ++k)
+    if (parents[k] < -1 || parents[k] >= r->T + k) return SP_E_BAD_PARENT;
+  if (first_index_out) *first_index_out = r->T;
+  if (n_new == 0) return SP_OK;
+  InsertArgs a;
+  for (int k = 0; k < n_new; ++k) {
+    a.parent[k] = (short)parents[k];
+    a.token[k] = tokens ? tokens[k] : 0;
+    a.prob[k] = probs ? probs[k] : 0.f;
+  }
+  hipError_t e;
+  {
+    ProfScope scope(s, SP_K_TREE_INSERT, (hipStream_t)stream);
+    e = sp_launch_tree_insert(s->d_meta, s->d_tables, req, n_new, a, s->geom, r->base + r->P + r->T,
+                              (hipStream_t)stream);
+  }
+  if (e != hipSuccess) return hip_fail(s, e);
+  for (int k = 0; k < n_new; ++k) { r->parent[r->T + k] = (short)parents[k]; r->fwd[r->T + k] = 0; }
+  r->T += n_new;
+  return SP_OK;
+}
+
+int sp_stage_forward(sp_stage* s, int32_t n_req, const int32_t* req_ids, const int32_t* first_node,
+                     const int32_t* n_nodes, const void* x_in, void* x_out, sp_stream stream) {
+  if (!s || !req_ids || !first_node || !n_nodes) return SP_E_INVALID;
+  if (n_req < 0 || n_req > SP_MAX_BATCH_REQ) return SP_E_CAPACITY;
+  const sp_config& c = s->cfg;
+  hipStream_t st = (hipStream_t)stream;
+  FwdBatch b;
+  b.n_req = 0;
+  int rows = 0;
+  for (int i = 0; i < n_req; ++i) {
+    HostReq* r = get_req(s, req_ids[i]);
+    if (!r) return SP_E_BAD_REQ;
+    if (r->pending) return SP_E_PENDING;
+    for (int j = 0; j < i; ++j) if (req_ids[j] == req_ids[i]) return SP_E_INVALID;
+    if (n_nodes[i] < 0) return SP_E_INVALID;
+    if (n_nodes[i] == 0) continue;
+    if (first_node[i] < 0 || first_node[i] + n_nodes[i] > r->T) return SP_E_BAD_NODE;
+    for (int k = first_node[i]; k < first_node[i] + n_nodes[i]; ++k) {
+      const int p = r->parent[k];
+      if (p >= 0 && !r->fwd[p] && p < first_node[i]) return SP_E_ORDER;
+    }
+    b.req[b.n_req] = req_ids[i]; b.first[b.n_req] = first_node[i]; b.n[b.n_req] = n_nodes[i]; b.row0[b.n_req] = rows;
+    ++b.n_req;
+    rows += n_nodes[i];
+  }
+  if (rows > c.max_batch_nodes) return SP_E_CAPACITY;
+  if (rows == 0) return SP_OK;
+  if (!x_in || !x_out) return SP_E_INVALID;
+  b.n_rows = rows;
+  const int M = rows, d = c.d_model, F = c.d_ff, dh = c.d_head, nq = c.n_q_heads, nkv = c.n_kv_heads;
+  const int dq = nq * dh, nqkv = (nq + 2 * nkv) * dh;
+  const int dt = c.dtype;
+  Workspace& w = s->ws;
+  hipError_t e;
+#define SP_TRY(call) do { e = (call); if (e != hipSuccess) return hip_fail(s, e); } while (0)
+
+  SP_TRY(sp_launch_prep_rows(b, s->d_meta, s->d_tables, w.rows, w.cs, dh, c.rope_theta, st));
+  SP_TRY(sp_launch_load_rows(dt, x_in, w.h, (size_t)M * d, st));
+
+  AttnPlan plan;
+  if (s->fast) {
+    // Split every request's cache range into chunks so that the grid fills the chip
+    // and the partial results fit the workspace.
+    plan.n_seg = b.n_req;
+    const int g = nq / nkv;
+    int maxq = 0;
+    for (int i = 0; i < b.n_req; ++i) if (b.n[i] * g > maxq) maxq = b.n[i] * g;
+    plan.qt = maxq <= 16 ? 1 : 2;
+    const int qrows_per_wave = 16 * plan.qt;
+    int chunk_len = 128;
+    for (;;) {
+      size_t units = 0; int items = 0;
+      for (int i = 0; i < b.n_req; ++i) {
+        const HostReq& r = s->reqs[b.req[i]];
+        const int span = r.P + r.T;
+        const int chunks = (span + chunk_len - 1) / chunk_len;
+        const int qblocks = (b.n[i] * g + qrows_per_wave - 1) / qrows_per_wave;
+        plan.seg_item0[i] = items; plan.seg_chunks[i] = chunks; plan.seg_qblocks[i] = qblocks;
+        plan.seg_row0[i] = b.row0[i]; plan.seg_rows[i] = b.n[i]; plan.seg_P[i] = r.P;
+        plan.seg_unit0[i] = (int)units;
+        items += chunks * qblocks;
+        units += (size_t)chunks * b.n[i] * nq;
+      }
+      plan.seg_item0[b.n_req] = items;
+      plan.total_items = items;
+      plan.units_total = (int)units;
+      plan.chunk_len = chunk_len;
+      if (units <= w.attn_units && (size_t)items * nkv <= 16384) break;
+      chunk_len *= 2;
+      if (chunk_len > (1 << 20)) return SP_E_CAPACITY;
+    }
+  }
+
+  int S_prev = 0;                                   // split count of the previous layer's down projection
+  const size_t strideD = (size_t)M * d, strideQ = (size_t)M * nqkv;
+  for (int l = 0; l < c.n_layers; ++l) {
+    const sp_layer_weights& L = s->W[l];
+    { ProfScope p(s, SP_K_NORM, st);
+      SP_TRY(sp_launch_add_norm(dt, w.h, l ? w.part : nullptr, S_prev, strideD, L.norm1, w.xn, M, d, c.rms_eps, st)); }
+    int S = 1;
+    { ProfScope p(s, SP_K_GEMM_QKV, st);
+      if (s->fast) SP_TRY(sp_launch_gemm_bf16((const bf16_t*)w.xn, (const bf16_t*)L.wqkv, w.part, M, nqkv, d, 16, w.part_floats, &S, st));
+      else SP_TRY(sp_launch_gemm_simple(dt, w.xn, L.wqkv, w.part, M, nqkv, d, st)); }
+    { ProfScope p(s, SP_K_ROPE_KV, st);
+      SP_TRY(sp_launch_rope_kv(dt, w.part, S, strideQ, w.rows, w.cs, w.qbuf, s->geom, l, M, nq, nkv, dh, st)); }
+    if (s->fast) {
+      ProfScope p(s, SP_K_ATTENTION, st);
+      SP_TRY(sp_launch_attn_bf16((const bf16_t*)w.qbuf, w.rows, s->d_tables, s->geom, l, plan, w.attn_part,
+                                 (bf16_t*)w.attn, M, nq, nkv, dh, st));
+    } else {
+      ProfScope p(s, SP_K_ATTENTION, st);
+      SP_TRY(sp_launch_attn_simple(dt, w.qbuf, w.rows, s->d_tables, s->geom, l, w.attn, M, nq, nkv, dh, st));
+    }
+    { ProfScope p(s, SP_K_GEMM_O, st);
+      S = 1;
+      if (s->fast) SP_TRY(sp_launch_gemm_bf16((const bf16_t*)w.attn, (const bf16_t*)L.wo, w.part, M, d, dq, 16, w.part_floats, &S, st));
+      else SP_TRY(sp_launch_gemm_simple(dt, w.attn, L.wo, w.part, M, d, dq, st)); }
+    { ProfScope p(s, SP_K_NORM, st);
+      SP_TRY(sp_launch_add_norm(dt, w.h, w.part, S, strideD, L.norm2, w.xn, M, d, c.rms_eps, st)); }
+    { ProfScope p(s, SP_K_GEMM_GATEUP, st);
+      if (s->fast) {
+        SP_TRY(sp_launch_gemm_gateup_bf16((const bf16_t*)w.xn, (const bf16_t*)L.wgu, (bf16_t*)w.act, M, F, d, st));
+      } else {
+        SP_TRY(sp_launch_gemm_simple(dt, w.xn, L.wgu, w.part, M, 2 * F, d, st));
+        SP_TRY(sp_launch_silu_mul(dt, w.part, w.act, M, F, st));
+      } }
+    { ProfScope p(s, SP_K_GEMM_DOWN, st);
+      S = 1;
+      if (s->fast) SP_TRY(sp_launch_gemm_bf16((const bf16_t*)w.act, (const bf16_t*)L.wd, w.part, M, d, F, 16, w.part_floats, &S, st));
+      else SP_TRY(sp_launch_gemm_simple(dt, w.act, L.wd, w.part, M, d, F, st)); }
+    S_prev = S;
+  }
+  SP_TRY(sp_launch_finish(dt, w.h, w.part, S_prev, strideD, x_out, M, d, st));
+#undef SP_TRY
+  for (int i = 0; i < b.n_req; ++i) {
+    HostReq& r = s->reqs[b.req[i]];
+    for (int k = b.first[i]; k < b.first[i] + b.n[i]; ++k) r.fwd[k] = 1;
+  }
+  return SP_OK;
+}
+
+int sp_tree_prune_batch(sp_stage* s, int32_t n, const int32_t* req_ids, const int32_t* modes, const int32_t* nodes,
+                        int32_t* n_live_out, int32_t* n_commit_out, sp_stream stream) {
+  if (!s || !req_ids || !modes || !nodes) return SP_E_INVALID;
+  if (n < 0 || n > SP_MAX_BATCH_REQ) return SP_E_CAPACITY;
+  PruneBatch b;
+  b.n = n;
+  bool any = false;
+  for (int i = 0; i < n; ++i) {
+    b.req[i] = req_ids[i]; b.mode[i] = modes[i]; b.node[i] = nodes[i];
+    if (modes[i] < 0) continue;
+    HostReq* r = get_req(s, req_ids[i]);
+    if (!r) return SP_E_BAD_REQ;
+    if (modes[i] != SP_ACCEPT && modes[i] != SP_DROP) return SP_E_INVALID;
+    if (r->pending) return SP_E_PENDING;
+    if (nodes[i] < 0 || nodes[i] >= r->T) return SP_E_BAD_NODE;
+    for (int j = 0; j < i; ++j) if (modes[j] >= 0 && req_ids[j] == req_ids[i]) return SP_E_INVALID;
+    any = true;
+  }
+  if (any) {
+    hipError_t e = sp_launch_tree_prune(s->d_meta, s->d_tables, b, (hipStream_t)stream);
+    if (e != hipSuccess) return hip_fail(s, e);
+  }
+  for (int i = 0; i < n; ++i) {
+    int live = 0, commit = 0;
+    if (modes[i] >= 0) {
+      HostReq& r = s->reqs[req_ids[i]];
+      r.pend_mode = modes[i]; r.pend_node = nodes[i];
+      mirror_prune(r, modes[i], nodes[i], &live, &commit);
+      r.pending = true;
+    } else if (HostReq* r = get_req(s, req_ids[i])) {
+      live = r->T;
+    }
+    if (n_live_out) n_live_out[i] = live;
+    if (n_commit_out) n_commit_out[i] = commit;
+  }
+  return SP_OK;
+}
+
+int sp_tree_prune(sp_stage* s, int32_t req, int32_t mode, int32_t node, int32_t* n_live_out, int32_t* n_commit_out,
+                  sp_stream stream) {
+  if (mode < 0) return SP_E_INVALID;
+  if (!s) return SP_E_INVALID;
+  ProfScope scope(s, SP_K_TREE_PRUNE, (hipStream_t)stream);
+  return sp_tree_prune_batch(s, 1, &req, &mode, &node, n_live_out, n_commit_out, stream);
+}
+
+int sp_kv_compact_batch(sp_stage* s, int32_t n, const int32_t* req_ids, sp_stream stream) {
+  if (!s || !req_ids) return SP_E_INVALID;
+  if (n < 0 || n > SP_MAX_BATCH_REQ) return SP_E_CAPACITY;
+  PruneBatch b;
+  b.n = n;
+  for (int i = 0; i < n; ++i) {
+    HostReq* r = get_req(s, req_ids[i]);
+    if (!r) return SP_E_BAD_REQ;
+    if (!r->pending) return SP_E_PENDING;
+    for (int j = 0; j < i; ++j) if (req_ids[j] == req_ids[i]) return SP_E_INVALID;
+    b.req[i] = req_ids[i]; b.mode[i] = r->pend_mode; b.node[i] = r->pend_node;
+  }
+  if (n == 0) return SP_OK;
+  {
+    ProfScope scope(s, SP_K_KV_COMPACT, (hipStream_t)stream);
+    hipError_t e = sp_launch_kv_compact(s->d_meta, s->d_tables, b, s->geom, (hipStream_t)stream);
+    if (e != hipSuccess) return hip_fail(s, e);
+  }
+  for (int i = 0; i < n; ++i) s->reqs[req_ids[i]].pending = false;
+  return SP_OK;
+}
+
+int sp_kv_compact(sp_stage* s, int32_t req, void* x_rows, int32_t n_rows, const int32_t* row_nodes,
+                  int32_t* n_rows_out, int32_t* row_nodes_out, sp_stream stream) {
+  if (!s) return SP_E_INVALID;
+  HostReq* r = get_req(s, req);
+  if (!r) return SP_E_BAD_REQ;
+  if (!r->pending) return SP_E_PENDING;
+  RowList list;
+  list.n_keep = 0;
+  list.first_moved = 0;
+  if (x_rows) {
+    if (n_rows < 0 || n_rows > SP_T || (n_rows > 0 && !row_nodes)) return SP_E_INVALID;
+    bool moved = false;
+    for (int i = 0; i < n_rows; ++i) {
+      const int node = row_nodes[i];
+      if (node < 0 || node >= SP_T) return SP_E_BAD_NODE;
+      if (i > 0 && node <= row_nodes[i - 1]) return SP_E_INVALID;
+      int nn;
+      bool keep;
+      if (r->pend_mode == SP_ACCEPT && node == r->pend_node) { keep = true; nn = -1; }
+      else { nn = r->pend_tab_new[node]; keep = nn >= 0; }
+      if (keep) {
+        if (!moved && i != list.n_keep) { moved = true; list.first_moved = list.n_keep; }
+        list.src[list.n_keep] = (short)i;
+        if (row_nodes_out) row_nodes_out[list.n_keep] = nn;
+        ++list.n_keep;
+      }
+    }
+    if (!moved) list.first_moved = list.n_keep;
+  }
+  int rc = sp_kv_compact_batch(s, 1, &req, stream);
+  if (rc != SP_OK) return rc;
+  if (x_rows) {
+    if (list.first_moved < list.n_keep) {
+      const size_t rb = (size_t)s->cfg.d_model * elt_bytes(s->cfg.dtype);
+      hipError_t e = sp_launch_rows_compact(x_rows, rb, (int)rb, list, (hipStream_t)stream);
+      if (e != hipSuccess) return hip_fail(s, e);
+    }
+    if (n_rows_out) *n_rows_out = list.n_keep;
+  } else if (n_rows_out) {
+    *n_rows_out = 0;
+  }
+  return SP_OK;
+}
+
+int sp_tree_read(sp_stage* s, int32_t req, sp_tree_view* out, sp_stream stream) {
+  if (!s || !out) return SP_E_INVALID;
+  if (!get_req(s, req)) return SP_E_BAD_REQ;
+  hipStream_t st = (hipStream_t)stream;
+  ReqMeta m;
+  hipError_t e = hipMemcpyAsync(&m, s->d_meta + req, sizeof(ReqMeta), hipMemcpyDeviceToHost, st);
+  if (e != hipSuccess) return hip_fail(s, e);
+  const ReqTables* t = s->d_tables + req;
+  if ((e = hipMemcpyAsync(out->parent, t->parent, sizeof(out->parent), hipMemcpyDeviceToHost, st)) != hipSuccess ||
+      (e = hipMemcpyAsync(out->depth, t->depth, sizeof(out->depth), hipMemcpyDeviceToHost, st)) != hipSuccess ||
+      (e = hipMemcpyAsync(out->token, t->token, sizeof(out->token), hipMemcpyDeviceToHost, st)) != hipSuccess ||
+      (e = hipMemcpyAsync(out->prob, t->prob, sizeof(out->prob), hipMemcpyDeviceToHost, st)) != hipSuccess ||
+      (e = hipMemcpyAsync(out->anc, t->anc, sizeof(out->anc), hipMemcpyDeviceToHost, st)) != hipSuccess)
+    return hip_fail(s, e);
+  if ((e = hipStreamSynchronize(st)) != hipSuccess) return hip_fail(s, e);
+  out->prefix_len = m.P;
+  out->n_live = m.T;
+  return SP_OK;
+}
+
+int sp_profile_begin(sp_stage* s, int32_t kind, int32_t max_launches) {
+  if (!s || kind <= SP_K_NONE || kind >= SP_K_KIND_COUNT || max_launches < 1) return SP_E_INVALID;
+  while ((int)s->prof_ev.size() < 2 * max_launches) {
+    hipEvent_t ev;
+    hipError_t e = hipEventCreate(&ev);
+    if (e != hipSuccess) return hip_fail(s, e);
+    s->prof_ev.push_back(ev);
+  }
+  s->prof_kind = kind; s->prof_max = max_launches; s->prof_n = 0;
+  return SP_OK;
+}
+
+int sp_profile_end(sp_stage* s, int32_t* n_launches, float* total_ms) {
+  if (!s) return SP_E_INVALID;
+  float tot = 0.f;
+  for (int i = 0; i < s->prof_n; ++i) {
+    hipError_t e = hipEventSynchronize(s->prof_ev[2 * i + 1]);
+    if (e != hipSuccess) return hip_fail(s, e);
+    float ms = 0.f;
+    e = hipEventElapsedTime(&ms, s->prof_ev[2 * i], s->prof_ev[2 * i + 1]);
+    if (e != hipSuccess) return hip_fail(s, e);
+    tot += ms;
+  }
+  if (n_launches) *n_launches = s->prof_n;
+  if (total_ms) *total_ms = tot;
+  s->prof_kind = 0; s->prof_n = 0;
+  return SP_OK;
+}
+
+}  // extern "C"

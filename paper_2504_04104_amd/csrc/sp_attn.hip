@@ -1,0 +1,287 @@
+// Tree-masked attention on the matrix cores (Sec. 2.1 attention, Sec. 2.2 and 3.3.2
+// tree mask), bf16, d_head = 128, grouped-query.
+//
+// Work is split over (request, KV head, block of query rows, chunk of cache slots);
+// one wave owns one such item and streams its chunk's K and V rows from HBM once for
+// all of its query rows (the g query heads of the group times the tree nodes).  The
+// committed context is visible to every node; a tree slot is visible to a node iff
+// its bit is set in the node's ancestor mask.  Each wave leaves an un-normalised
+// partial (running max, sum, output) per query row; a second kernel merges the chunks.
+//
+// MFMA use (v_mfma_f32_16x16x32_bf16, D[4*(l/16)+i][l%16]):
+//   S^T = K Q^T : A = 16 slots x 32 d (straight from global, 16 B per lane),
+//                 B = 32 d x 16 query rows (registers, loaded once).
+//   O^T = V^T P^T: B = P^T is exactly the S^T registers of two 16-slot tiles (the
+//                 contraction order over the 32 slots is free, so no shuffle is
+//                 needed); A = V^T needs 8 slots per lane for one d, which is read
+//                 from an LDS copy of the V tile, two d columns per 32-bit read.
+#include "sp_launch.h"
+
+#define DH 128
+#define VS 272            // LDS row stride of the V tile in bytes (256 + 16)
+
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+  return (uint32_t)f32_to_bf16(lo) | ((uint32_t)f32_to_bf16(hi) << 16);
+}
+
+struct AttnArgs {
+  const bf16_t* q;          // [M][n_q][DH]
+  const RowInfo* rows;
+  const ReqTables* tables;
+  KvGeom g;
+  int layer, n_q, n_kv;
+  float* part_o;            // [units][DH]
+  float* part_ml;           // [units][2]
+};
+
+template <int QT>
+__global__ void __launch_bounds__(256) k_attn_bf16(AttnArgs a, AttnPlan plan, int qt_rows) {
+  __shared__ __attribute__((aligned(16))) char s_v[4][32 * VS];
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int item = blockIdx.x * 4 + wave;
+  if (item >= plan.total_items) return;            // whole wave; no block-level barriers below
+  const int kvh = blockIdx.y;
+  int seg = 0;
+  while (seg + 1 < plan.n_seg && item >= plan.seg_item0[seg + 1]) ++seg;
+  const int local = item - plan.seg_item0[seg];
+  const int chunks = plan.seg_chunks[seg];
+  const int qb = local / chunks, ch = local - qb * chunks;
+  const int g = a.n_q / a.n_kv;
+  const int seg_rows = plan.seg_rows[seg], row0 = plan.seg_row0[seg];
+  const int nqrows = seg_rows * g;                 // query rows of this (request, KV head)
+
+  const RowInfo r0 = a.rows[row0];
+  const int P = r0.P, T = r0.T;
+  const int span = P + T;
+  const int c0 = ch * plan.chunk_len;
+  const int c1 = min(c0 + plan.chunk_len, span);
+  const int l15 = lane & 15, kg = lane >> 4;
+
+  // ---- query fragments and ancestor masks of this lane's query row per tile ------
+  u32x4_t qf[QT][4];
+  unsigned long long anc[QT][SP_W];
+  int qrow_ok[QT];
+#pragma unroll
+  for (int t = 0; t < QT; ++t) {
+    const int qi = qb * qt_rows + t * 16 + l15;    // index inside (request, KV head): node_local * g + gq
+    const bool ok = qi < nqrows;
+    qrow_ok[t] = ok;
+    const int nl = ok ? qi / g : 0, gq = ok ? qi - nl * g : 0;
+    const int row = row0 + nl;
+    const bf16_t* qp = a.q + ((size_t)row * a.n_q + (size_t)kvh * g + gq) * DH + kg * 8;
+#pragma unroll
+    for (int s = 0; s < 4; ++s)
+      qf[t][s] = ok ? *reinterpret_cast<const u32x4_t*>(qp + s * 32) : (u32x4_t){0u, 0u, 0u, 0u};
+    const int node = a.rows[row].node;
+#pragma unroll
+    for (int w = 0; w < SP_W; ++w) anc[t][w] = ok ? a.tables[r0.req].anc[node][w] : 0ull;
+  }
+
+  const char* kplane = a.g.kv + ((size_t)(a.layer * 2 + 0) * a.n_kv + kvh) * a.g.plane_bytes + (size_t)r0.base * 256;
+  const char* vplane = a.g.kv + ((size_t)(a.layer * 2 + 1) * a.n_kv + kvh) * a.g.plane_bytes + (size_t)r0.base * 256;
+
+  f32x4_t o[QT][8];
+  float mrun[QT], lrun[QT];
+#pragma unroll
+  for (int t = 0; t < QT; ++t) {
+    mrun[t] = -INFINITY; lrun[t] = 0.f;
+#pragma unroll
+    for (int d = 0; d < 8; ++d) o[t][d] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
+  }
+  const float sc = 0.08838834764831845f * 1.4426950408889634f;   // 1/sqrt(128) * log2(e)
+
+  // Loads of one 32-slot tile: K as MFMA A fragments (row l15 of each 16-slot half, 16 B at
+  // d = s*32 + kg*8), V as plain 16-byte pieces (row i*4+kg, piece l15).  Slots past the
+  // request's data are read from slot 0 (always valid) and masked later.
+#define SP_LOAD_TILE(S0)                                                                           \
+  {                                                                                                \
+    _Pragma("unroll") for (int t2 = 0; t2 < 2; ++t2) {                                             \
+      int slot = (S0) + t2 * 16 + l15;                                                             \
+      slot = slot < span ? slot : 0;                                                               \
+      const char* kp = kplane + (size_t)slot * 256 + kg * 16;                                      \
+      _Pragma("unroll") for (int s = 0; s < 4; ++s)                                                \
+          kreg[t2][s] = *reinterpret_cast<const u32x4_t*>(kp + s * 64);                              \
+    }                                                                                              \
+    _Pragma("unroll") for (int i = 0; i < 8; ++i) {                                                \
+      int slot = (S0) + i * 4 + kg;                                                                \
+      slot = slot < span ? slot : 0;                                                               \
+      vreg[i] = *reinterpret_cast<const u32x4_t*>(vplane + (size_t)slot * 256 + l15 * 16);           \
+    }                                                                                              \
+  }
+
+  u32x4_t kreg[2][4], vreg[8];
+  char* vt = s_v[wave];
+  SP_LOAD_TILE(c0)
+  for (int s0 = c0; s0 < c1; s0 += 32) {
+    // V tile -> LDS, K fragments -> a second register set, then the next tile's loads
+    // are issued so that they fly during this tile's math (the tile after the last one
+    // re-reads slot 0 and is discarded).
+    __builtin_amdgcn_wave_barrier();
+#pragma unroll
+    for (int i = 0; i < 8; ++i) *reinterpret_cast<u32x4_t*>(vt + (i * 4 + kg) * VS + l15 * 16) = vreg[i];
+    u32x4_t kc[2][4];
+#pragma unroll
+    for (int t2 = 0; t2 < 2; ++t2)
+#pragma unroll
+      for (int s = 0; s < 4; ++s) kc[t2][s] = kreg[t2][s];
+    {
+      const int nxt = (s0 + 32 < c1) ? s0 + 32 : span;     // span: every slot clamps to 0
+      SP_LOAD_TILE(nxt)
+    }
+
+    const bool tail = s0 + 32 > P || s0 + 32 > c1;   // tile touches the tree region or the chunk end
+    uint32_t pb[QT][4];
+#pragma unroll
+    for (int t = 0; t < QT; ++t) {
+      f32x4_t sacc[2];
+#pragma unroll
+      for (int t2 = 0; t2 < 2; ++t2) {
+        sacc[t2] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int s = 0; s < 4; ++s)
+          sacc[t2] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(*reinterpret_cast<const bf16x8_t*>(&kc[t2][s]),
+                                                             *reinterpret_cast<const bf16x8_t*>(&qf[t][s]),
+                                                             sacc[t2], 0, 0, 0);
+      }
+      float sv[8];
+#pragma unroll
+      for (int t2 = 0; t2 < 2; ++t2)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) sv[t2 * 4 + i] = sacc[t2][i] * sc;
+      if (tail) {
+        // bits [n0, n0+64) of the row's 256-bit ancestor mask, n0 = first tree index of the tile
+        const int n0 = s0 - P;
+        unsigned long long win = 0ull;
+#pragma unroll
+        for (int w = 0; w < SP_W; ++w) {
+          const int sh = w * 64 - n0;
+          if (sh > -64 && sh < 64) win |= sh >= 0 ? (anc[t][w] << sh) : (anc[t][w] >> (-sh));
+        }
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+          const int off = (j >> 2) * 16 + kg * 4 + (j & 3);
+          const int slot = s0 + off;
+          bool vis = slot < c1;
+          if (slot >= P) vis = vis && (slot - P) < T && ((win >> off) & 1ull);
+          if (!vis) sv[j] = -INFINITY;
+        }
+      }
+      float mx = sv[0];
+#pragma unroll
+      for (int j = 1; j < 8; ++j) mx = fmaxf(mx, sv[j]);
+      mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+      const float mnew = fmaxf(mrun[t], mx);
+      const float msafe = (mnew == -INFINITY) ? 0.f : mnew;
+      const float alpha = exp2f(mrun[t] - msafe);           // 0 when mrun is -inf
+      float ps = 0.f;
+      float pv[8];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) { pv[j] = exp2f(sv[j] - msafe); ps += pv[j]; }
+      lrun[t] = lrun[t] * alpha + ps;
+      mrun[t] = mnew;
+#pragma unroll
+      for (int d = 0; d < 8; ++d) o[t][d] *= alpha;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) pb[t][j] = pack_bf16x2(pv[2 * j], pv[2 * j + 1]);
+    }
+
+    // O^T += V^T P^T.  Lane (l15, kg) of the d-group G pair reads V[slot(kg,j)][G*32 + 2*l15 .. +1].
+    __builtin_amdgcn_wave_barrier();
+#pragma unroll
+    for (int G = 0; G < 4; ++G) {
+      uint32_t w[8];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const int srow = (j >> 2) * 16 + kg * 4 + (j & 3);
+        w[j] = *reinterpret_cast<const uint32_t*>(vt + srow * VS + (G * 32 + 2 * l15) * 2);
+      }
+      u32x4_t alo, ahi;     // low halves: column 2*l15; high halves: column 2*l15+1
+      alo.x = __builtin_amdgcn_perm(w[1], w[0], 0x05040100); ahi.x = __builtin_amdgcn_perm(w[1], w[0], 0x07060302);
+      alo.y = __builtin_amdgcn_perm(w[3], w[2], 0x05040100); ahi.y = __builtin_amdgcn_perm(w[3], w[2], 0x07060302);
+      alo.z = __builtin_amdgcn_perm(w[5], w[4], 0x05040100); ahi.z = __builtin_amdgcn_perm(w[5], w[4], 0x07060302);
+      alo.w = __builtin_amdgcn_perm(w[7], w[6], 0x05040100); ahi.w = __builtin_amdgcn_perm(w[7], w[6], 0x07060302);
+#pragma unroll
+      for (int t = 0; t < QT; ++t) {
+        const bf16x8_t pfrag = *reinterpret_cast<const bf16x8_t*>(&pb[t][0]);
+        o[t][2 * G] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(*reinterpret_cast<const bf16x8_t*>(&alo), pfrag,
+                                                              o[t][2 * G], 0, 0, 0);
+        o[t][2 * G + 1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(*reinterpret_cast<const bf16x8_t*>(&ahi), pfrag,
+                                                                  o[t][2 * G + 1], 0, 0, 0);
+      }
+    }
+  }
+
+  // ---- partial results ------------------------------------------------------------
+  // o[t][2G+h][i] is output column G*32 + 2*(4*kg+i) + h of query row t*16 + l15.
+  const size_t unit0 = (size_t)plan.seg_unit0[seg] + (size_t)ch * seg_rows * a.n_q;
+#pragma unroll
+  for (int t = 0; t < QT; ++t) {
+    float l = lrun[t];
+    l += __shfl_xor(l, 16, 64);
+    l += __shfl_xor(l, 32, 64);
+    if (!qrow_ok[t]) continue;
+    const int qi = qb * qt_rows + t * 16 + l15;
+    const int nl = qi / g, gq = qi - nl * g;
+    const size_t unit = unit0 + (size_t)nl * a.n_q + (size_t)kvh * g + gq;
+    float* po = a.part_o + unit * DH;
+#pragma unroll
+    for (int G = 0; G < 4; ++G) {
+      f32x4_t lo, hi;
+      lo[0] = o[t][2 * G][0]; lo[1] = o[t][2 * G + 1][0]; lo[2] = o[t][2 * G][1]; lo[3] = o[t][2 * G + 1][1];
+      hi[0] = o[t][2 * G][2]; hi[1] = o[t][2 * G + 1][2]; hi[2] = o[t][2 * G][3]; hi[3] = o[t][2 * G + 1][3];
+      *reinterpret_cast<f32x4_t*>(po + G * 32 + 8 * kg) = lo;
+      *reinterpret_cast<f32x4_t*>(po + G * 32 + 8 * kg + 4) = hi;
+    }
+    if (kg == 0) { a.part_ml[unit * 2] = mrun[t]; a.part_ml[unit * 2 + 1] = l; }
+  }
+}
+
+// One wave per (row, query head): combine the chunk partials (log2-domain maxima).
+__global__ void __launch_bounds__(256) k_attn_merge(AttnArgs a, AttnPlan plan, bf16_t* out, int M) {
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int item = blockIdx.x * 4 + wave;
+  if (item >= M * a.n_q) return;
+  const int row = item / a.n_q, head = item - row * a.n_q;
+  const int seg = a.rows[row].seg;
+  const int chunks = plan.seg_chunks[seg], seg_rows = plan.seg_rows[seg];
+  const size_t stride = (size_t)seg_rows * a.n_q;
+  const size_t u0 = (size_t)plan.seg_unit0[seg] + (size_t)(row - plan.seg_row0[seg]) * a.n_q + head;
+  float mx = -INFINITY;
+  for (int c = lane; c < chunks; c += 64) mx = fmaxf(mx, a.part_ml[(u0 + c * stride) * 2]);
+  mx = wave_max(mx);
+  float acc0 = 0.f, acc1 = 0.f, lsum = 0.f;
+  for (int c = 0; c < chunks; ++c) {
+    const size_t u = u0 + c * stride;
+    const float m = a.part_ml[u * 2], l = a.part_ml[u * 2 + 1];
+    if (m == -INFINITY) continue;
+    const float wgt = exp2f(m - mx);
+    lsum += wgt * l;
+    acc0 += wgt * a.part_o[u * DH + lane];
+    acc1 += wgt * a.part_o[u * DH + 64 + lane];
+  }
+  const float inv = 1.f / lsum;
+  bf16_t* po = out + ((size_t)row * a.n_q + head) * DH;
+  po[lane] = f32_to_bf16(acc0 * inv);
+  po[64 + lane] = f32_to_bf16(acc1 * inv);
+}
+
+hipError_t sp_launch_attn_bf16(const bf16_t* q, const RowInfo* rows, const ReqTables* tables, KvGeom g, int layer,
+                               const AttnPlan& plan, float* part, bf16_t* out, int M, int n_q, int n_kv, int d_head,
+                               hipStream_t st) {
+  if (d_head != DH || g.row_bytes != 256) return hipErrorInvalidValue;
+  AttnArgs a;
+  a.q = q; a.rows = rows; a.tables = tables; a.g = g; a.layer = layer; a.n_q = n_q; a.n_kv = n_kv;
+  a.part_o = part;
+  a.part_ml = part + (size_t)plan.units_total * DH;
+  dim3 grid((plan.total_items + 3) / 4, n_kv);
+  switch (plan.qt) {
+    case 1: hipLaunchKernelGGL(k_attn_bf16<1>, grid, dim3(256), 0, st, a, plan, 16); break;
+    case 2: hipLaunchKernelGGL(k_attn_bf16<2>, grid, dim3(256), 0, st, a, plan, 32); break;
+    default: return hipErrorInvalidValue;
+  }
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(k_attn_merge, dim3((M * n_q + 3) / 4), dim3(256), 0, st, a, plan, out, M);
+  return hipGetLastError();
+}

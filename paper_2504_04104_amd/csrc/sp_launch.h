@@ -1,0 +1,73 @@
+// Host-callable launchers of the HIP kernels.  Each enqueues on `st` and returns
+// the launch status; none synchronises.
+#pragma once
+#include "sp_device.h"
+
+struct KvGeom {
+  char* kv;              // slab
+  size_t plane_bytes;    // bytes between consecutive kv heads: kv_slots * row_bytes
+  int row_bytes;         // d_head * element size
+  int n_layers;
+  int n_kv_heads;
+};
+
+// ---- tree tables -------------------------------------------------------------
+hipError_t sp_launch_tables_clear(ReqMeta* meta, ReqTables* tables, int n_req, hipStream_t st);
+hipError_t sp_launch_request_init(ReqMeta* meta, ReqTables* tables, int req, long long base, int cap, int P,
+                                  hipStream_t st);
+// first_slot: cache slot of the first new node (host mirror: base + prefix_len + n_live)
+hipError_t sp_launch_tree_insert(ReqMeta* meta, ReqTables* tables, int req, int n_new, const InsertArgs& a,
+                                 KvGeom g, long long first_slot, hipStream_t st);
+hipError_t sp_launch_tree_prune(ReqMeta* meta, ReqTables* tables, const PruneBatch& b, hipStream_t st);
+hipError_t sp_launch_kv_compact(const ReqMeta* meta, const ReqTables* tables, const PruneBatch& b, KvGeom g,
+                                hipStream_t st);
+hipError_t sp_launch_rows_compact(void* rows, size_t row_stride_bytes, int row_bytes, const RowList& l,
+                                  hipStream_t st);
+
+// ---- elementwise / row kernels --------------------------------------------------
+hipError_t sp_launch_prep_rows(const FwdBatch& b, const ReqMeta* meta, const ReqTables* tables, RowInfo* rows,
+                               float* cs /*[rows][d_head]: cos then sin*/, int d_head, float theta,
+                               hipStream_t st);
+hipError_t sp_launch_load_rows(int dtype, const void* x, float* h, size_t n, hipStream_t st);
+// h += sum_s part[s]; xn = rmsnorm(h) * gain   (part may be null)
+hipError_t sp_launch_add_norm(int dtype, float* h, const float* part, int S, size_t part_stride,
+                              const void* gain, void* xn, int M, int d, float eps, hipStream_t st);
+// q,k rotated, v copied; q -> qbuf [M][n_q*d_head]; k,v -> slab rows
+hipError_t sp_launch_rope_kv(int dtype, const float* part, int S, size_t part_stride, const RowInfo* rows,
+                             const float* cs, void* qbuf, KvGeom g, int layer, int M, int n_q, int n_kv,
+                             int d_head, hipStream_t st);
+hipError_t sp_launch_silu_mul(int dtype, const float* gu, void* act, int M, int F, hipStream_t st);
+hipError_t sp_launch_finish(int dtype, const float* h, const float* part, int S, size_t part_stride, void* out,
+                            int M, int d, hipStream_t st);
+
+// ---- GEMM: out[s][m][n] (f32) = sum over the s-th K slice of X[m][k] * W[n][k] -----
+hipError_t sp_launch_gemm_simple(int dtype, const void* X, const void* W, float* out, int M, int N, int K,
+                                 hipStream_t st);
+// bf16 MFMA kernels.  Returns the split count used in *S_out (partials [S][M][N]).
+hipError_t sp_launch_gemm_bf16(const bf16_t* X, const bf16_t* W, float* out, int M, int N, int K, int max_split,
+                               size_t part_capacity_floats, int* S_out, hipStream_t st);
+// act[m][f] = silu(X Wg^T) * (X Wu^T), W = [gate rows ; up rows]
+hipError_t sp_launch_gemm_gateup_bf16(const bf16_t* X, const bf16_t* W, bf16_t* act, int M, int F, int K,
+                                      hipStream_t st);
+
+// ---- tree attention -------------------------------------------------------------
+hipError_t sp_launch_attn_simple(int dtype, const void* q, const RowInfo* rows, const ReqTables* tables, KvGeom g,
+                                 int layer, void* out, int M, int n_q, int n_kv, int d_head, hipStream_t st);
+
+struct AttnPlan {          // host-made split of a forward call's attention work
+  int n_seg;
+  int chunk_len;           // slots per chunk (multiple of 32)
+  int qt;                  // 16-row query tiles per wave: 1 or 2
+  int units_total;         // partial-result units: sum over segments of chunks * rows * n_q
+  int total_items;         // sum over segments of q_blocks * chunks
+  int seg_item0[SP_BATCH + 1];   // first work item of each segment
+  int seg_chunks[SP_BATCH];
+  int seg_qblocks[SP_BATCH];
+  int seg_unit0[SP_BATCH];
+  int seg_row0[SP_BATCH];
+  int seg_rows[SP_BATCH];
+  int seg_P[SP_BATCH];     // host mirror of the prefix length (sizes the split only)
+};
+hipError_t sp_launch_attn_bf16(const bf16_t* q, const RowInfo* rows, const ReqTables* tables, KvGeom g, int layer,
+                               const AttnPlan& plan, float* part /*workspace*/, bf16_t* out, int M, int n_q,
+                               int n_kv, int d_head, hipStream_t st);

@@ -1,0 +1,292 @@
+// Tree tables on the device: layer appending, prune flags + prefix sums + table
+// compaction, and the in-place row gather that compacts the KV cache and the
+// in-flight hidden rows.  (Sec. 3.2; Sec. 3.3.2 "pruning propagation"; Algorithm 1
+// lines 5-7.)
+#include "sp_launch.h"
+
+// 256-bit rows live in four registers; select the word without indexing memory.
+__device__ __forceinline__ void set_bit(unsigned long long (&b)[SP_W], int idx) {
+#pragma unroll
+  for (int w = 0; w < SP_W; ++w) b[w] |= ((idx >> 6) == w) ? (1ull << (idx & 63)) : 0ull;
+}
+__device__ __forceinline__ bool test_bit(const unsigned long long (&b)[SP_W], int idx) {
+  unsigned long long word = 0ull;
+#pragma unroll
+  for (int w = 0; w < SP_W; ++w) word = ((idx >> 6) == w) ? b[w] : word;
+  return (word >> (idx & 63)) & 1ull;
+}
+
+// -----------------------------------------------------------------------------
+__global__ void k_tables_clear(ReqMeta* meta, ReqTables* tables, int n_req) {
+  int r = blockIdx.x;
+  if (r >= n_req) return;
+  ReqTables& t = tables[r];
+  for (int i = threadIdx.x; i < SP_T; i += blockDim.x) {
+    t.parent[i] = -1; t.depth[i] = 0; t.token[i] = 0; t.prob[i] = 0.f;
+    for (int w = 0; w < SP_W; ++w) t.anc[i][w] = 0ull;
+    t.kv_src[i] = 0; t.tab_new[i] = -1;
+  }
+  if (threadIdx.x == 0) {
+    t.pend_n_kv_keep = 0; t.pend_first_moved = 0; t.pend_P_old = 0; t.pend_T_old = 0;
+    ReqMeta m; m.base = 0; m.cap = 0; m.P = 0; m.T = 0; m.pad = 0;
+    meta[r] = m;
+  }
+}
+
+__global__ void k_request_init(ReqMeta* meta, ReqTables* tables, int req, long long base, int cap, int P) {
+  if (threadIdx.x == 0) {
+    ReqMeta m; m.base = base; m.cap = cap; m.P = P; m.T = 0; m.pad = 0;
+    meta[req] = m;
+    ReqTables& t = tables[req];
+    t.pend_n_kv_keep = 0; t.pend_first_moved = 0; t.pend_P_old = P; t.pend_T_old = 0;
+  }
+}
+
+// Layer appending.  Block 0: thread k owns new node T0+k.  Its ancestor row is its own
+// bit, the bits of the parents it reaches inside this call, and the stored row of the
+// first parent that existed before the call (nothing if it reaches the root).
+// Blocks 1..: one per (layer, K|V, head) plane; they clear the new nodes' cache rows,
+// so that every slot below prefix_len + n_live always holds finite numbers (a masked
+// key still enters the matrix-core product with weight zero).
+__global__ void __launch_bounds__(SP_T) k_tree_insert(ReqMeta* meta, ReqTables* tables, int req, int n_new,
+                                                       InsertArgs a, KvGeom g, long long first_slot) {
+  if (blockIdx.x > 0) {
+    uint4* rows = reinterpret_cast<uint4*>(g.kv + (size_t)(blockIdx.x - 1) * g.plane_bytes +
+                                           (size_t)first_slot * g.row_bytes);
+    const int n16 = n_new * (g.row_bytes >> 4);
+    for (int i = threadIdx.x; i < n16; i += blockDim.x) rows[i] = make_uint4(0u, 0u, 0u, 0u);
+    return;
+  }
+  ReqTables& t = tables[req];
+  const int T0 = meta[req].T;
+  const int k = threadIdx.x;
+  if (k < n_new) {
+    unsigned long long bits[SP_W] = {0ull, 0ull, 0ull, 0ull};
+    const int self = T0 + k;
+    set_bit(bits, self);
+    int cur = a.parent[k];
+    int up = 0;
+    while (cur >= T0) {
+      set_bit(bits, cur);
+      cur = a.parent[cur - T0];
+      ++up;
+    }
+    int dep = up;
+    if (cur >= 0) {
+#pragma unroll
+      for (int w = 0; w < SP_W; ++w) bits[w] |= t.anc[cur][w];
+      dep = t.depth[cur] + up + 1;
+    }
+    t.parent[self] = a.parent[k];
+    t.depth[self] = dep;
+    t.token[self] = a.token[k];
+    t.prob[self] = a.prob[k];
+#pragma unroll
+    for (int w = 0; w < SP_W; ++w) t.anc[self][w] = bits[w];
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) meta[req].T = T0 + n_new;
+}
+
+// Prune flags from the mask column, wave-level prefix sums (ballot + popcount,
+// wave64), compacted tables written in place, and the old->new map for the cache.
+__global__ void __launch_bounds__(SP_T) k_tree_prune(ReqMeta* meta, ReqTables* tables, PruneBatch b) {
+  const int item = blockIdx.x;
+  const int mode = b.mode[item];
+  if (mode < 0) return;
+  const int req = b.req[item];
+  const int r = b.node[item];
+  ReqTables& t = tables[req];
+  const int T = meta[req].T;
+  const int P = meta[req].P;
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+
+  __shared__ unsigned long long s_tab[SP_W], s_kv[SP_W], s_path[SP_W];
+  __shared__ short s_new[SP_T];
+
+  if (tid < SP_W) s_path[tid] = t.anc[r][tid];
+  const bool live = tid < T;
+  unsigned long long my[SP_W] = {0ull, 0ull, 0ull, 0ull};
+  int par = -1, dep = 0, tok = 0;
+  float prb = 0.f;
+  if (live) {
+#pragma unroll
+    for (int w = 0; w < SP_W; ++w) my[w] = t.anc[tid][w];
+    par = t.parent[tid]; dep = t.depth[tid]; tok = t.token[tid]; prb = t.prob[tid];
+  }
+  __syncthreads();
+  const bool in_col = live && test_bit(my, r);                               // tid is r or below r
+  const bool on_path = live && ((s_path[tid >> 6] >> (tid & 63)) & 1ull);   // tid is r or above r
+  bool keep_tab, keep_kv;
+  if (mode == 0) { keep_tab = in_col && tid != r; keep_kv = in_col || on_path; }
+  else           { keep_tab = live && !in_col;    keep_kv = keep_tab; }
+
+  const unsigned long long bt = __ballot(keep_tab), bk = __ballot(keep_kv);
+  if (lane == 0) { s_tab[wave] = bt; s_kv[wave] = bk; }
+  __syncthreads();
+  const unsigned long long below = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
+  int pre_tab = __popcll(bt & below), pre_kv = __popcll(bk & below);
+  int n_tab = 0, n_kv = 0;
+#pragma unroll
+  for (int w = 0; w < SP_W; ++w) {
+    const int ct = __popcll(s_tab[w]), ck = __popcll(s_kv[w]);
+    if (w < wave) { pre_tab += ct; pre_kv += ck; }
+    n_tab += ct; n_kv += ck;
+  }
+  int n_commit = 0;
+  if (mode == 0) {
+#pragma unroll
+    for (int w = 0; w < SP_W; ++w) n_commit += __popcll(s_path[w]);
+  }
+  s_new[tid] = keep_tab ? (short)pre_tab : (short)-1;
+  __syncthreads();     // every thread has read its old entries; the map is complete
+
+  if (keep_tab) {
+    const int np = (par >= 0 && s_new[par] >= 0) ? (int)s_new[par] : -1;
+    unsigned long long nrow[SP_W] = {0ull, 0ull, 0ull, 0ull};
+#pragma unroll
+    for (int w = 0; w < SP_W; ++w) {
+      unsigned long long bits = my[w] & s_tab[w];
+      while (bits) {
+        const int j = __ffsll((long long)bits) - 1;
+        bits &= bits - 1;
+        const int nj = s_new[w * 64 + j];
+        set_bit(nrow, nj);
+      }
+    }
+    t.parent[pre_tab] = np;
+    t.depth[pre_tab] = dep - n_commit;
+    t.token[pre_tab] = tok;
+    t.prob[pre_tab] = prb;
+#pragma unroll
+    for (int w = 0; w < SP_W; ++w) t.anc[pre_tab][w] = nrow[w];
+  }
+  if (keep_kv) t.kv_src[pre_kv] = (short)tid;
+  t.tab_new[tid] = s_new[tid];
+  if (tid == 0) {
+    // rows before the first dropped one keep their slot
+    int first = T;
+#pragma unroll
+    for (int w = SP_W - 1; w >= 0; --w) {
+      unsigned long long live_w = 0ull;
+      const int lo = w * 64;
+      if (T > lo) live_w = (T - lo >= 64) ? ~0ull : ((1ull << (T - lo)) - 1ull);
+      const unsigned long long gone = live_w & ~s_kv[w];
+      if (gone) first = lo + __ffsll((long long)gone) - 1;
+    }
+    t.pend_n_kv_keep = n_kv;
+    t.pend_first_moved = first;
+    t.pend_P_old = P;
+    t.pend_T_old = T;
+    meta[req].P = P + n_commit;
+    meta[req].T = n_tab;
+  }
+}
+
+// -----------------------------------------------------------------------------
+// In-place stable row gather on one "stream" of rows: destination row j takes
+// source row src[j] >= j.  A workgroup owns the stream.  It works through the
+// destinations in ascending batches; inside a batch every source is in registers
+// before the first store.  Later batches only read sources beyond the rows a batch
+// writes (src[j] >= j), so no row is overwritten before it is read.
+template <int R>
+__device__ __forceinline__ void gather_inplace(char* stream, size_t row_stride, int slice_bytes, int first,
+                                               int n_keep, const short* src) {
+  const int U = slice_bytes >> 4;                 // 16-byte units per row slice
+  const int rows_per_pass = blockDim.x / U;
+  const int u = threadIdx.x % U, rr = threadIdx.x / U;
+  const bool active = rr < rows_per_pass;
+  for (int b0 = first; b0 < n_keep; b0 += rows_per_pass * R) {
+    uint4 regs[R];
+#pragma unroll
+    for (int i = 0; i < R; ++i) {
+      const int dst = b0 + i * rows_per_pass + rr;
+      const bool in = active && dst < n_keep;
+      const int s = in ? (int)src[dst] : 0;
+      const bool mv = in && s != dst;
+      // rows that stay (or lanes without a row) read the stream's first bytes and drop them
+      const uint4 v = *reinterpret_cast<const uint4*>(stream + (mv ? (size_t)s * row_stride + (size_t)u * 16 : 0));
+      regs[i] = mv ? v : make_uint4(0u, 0u, 0u, 0u);
+    }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < R; ++i) {
+      const int dst = b0 + i * rows_per_pass + rr;
+      if (active && dst < n_keep) {
+        const int s = src[dst];
+        if (s != dst) *reinterpret_cast<uint4*>(stream + (size_t)dst * row_stride + (size_t)u * 16) = regs[i];
+      }
+    }
+    __syncthreads();
+  }
+}
+
+// grid = (layers * 2 * kv_heads, batch items): one workgroup per (plane, request).
+__global__ void __launch_bounds__(256) k_kv_compact(const ReqMeta* meta, const ReqTables* tables, PruneBatch b,
+                                                     KvGeom g) {
+  const int item = blockIdx.y;
+  if (b.mode[item] < 0) return;
+  const int req = b.req[item];
+  const ReqTables& t = tables[req];
+  __shared__ short s_src[SP_T];
+  const int n_keep = t.pend_n_kv_keep, first = t.pend_first_moved;
+  for (int i = threadIdx.x; i < n_keep; i += blockDim.x) s_src[i] = t.kv_src[i];
+  __syncthreads();
+  if (first >= n_keep) return;
+  const size_t plane = blockIdx.x;      // (layer*2 + kv) * n_kv_heads + head
+  char* stream = g.kv + plane * g.plane_bytes + (size_t)(meta[req].base + t.pend_P_old) * g.row_bytes;
+  gather_inplace<16>(stream, (size_t)g.row_bytes, g.row_bytes, first, n_keep, s_src);
+}
+
+// grid = row_bytes / slice: one workgroup per 256-byte column slice of the rows.
+__global__ void __launch_bounds__(256) k_rows_compact(char* rows, size_t row_stride, int slice_bytes, RowList l) {
+  __shared__ short s_src[SP_T];
+  for (int i = threadIdx.x; i < l.n_keep; i += blockDim.x) s_src[i] = l.src[i];
+  __syncthreads();
+  gather_inplace<16>(rows + (size_t)blockIdx.x * slice_bytes, row_stride, slice_bytes, l.first_moved, l.n_keep,
+                     s_src);
+}
+
+// ---- launchers -------------------------------------------------------------------
+hipError_t sp_launch_tables_clear(ReqMeta* meta, ReqTables* tables, int n_req, hipStream_t st) {
+  hipLaunchKernelGGL(k_tables_clear, dim3(n_req), dim3(256), 0, st, meta, tables, n_req);
+  return hipGetLastError();
+}
+hipError_t sp_launch_request_init(ReqMeta* meta, ReqTables* tables, int req, long long base, int cap, int P,
+                                  hipStream_t st) {
+  hipLaunchKernelGGL(k_request_init, dim3(1), dim3(64), 0, st, meta, tables, req, base, cap, P);
+  return hipGetLastError();
+}
+hipError_t sp_launch_tree_insert(ReqMeta* meta, ReqTables* tables, int req, int n_new, const InsertArgs& a,
+                                 KvGeom g, long long first_slot, hipStream_t st) {
+  hipLaunchKernelGGL(k_tree_insert, dim3(1 + g.n_layers * 2 * g.n_kv_heads), dim3(SP_T), 0, st, meta, tables, req,
+                     n_new, a, g, first_slot);
+  return hipGetLastError();
+}
+hipError_t sp_launch_tree_prune(ReqMeta* meta, ReqTables* tables, const PruneBatch& b, hipStream_t st) {
+  hipLaunchKernelGGL(k_tree_prune, dim3(b.n), dim3(SP_T), 0, st, meta, tables, b);
+  return hipGetLastError();
+}
+hipError_t sp_launch_kv_compact(const ReqMeta* meta, const ReqTables* tables, const PruneBatch& b, KvGeom g,
+                                hipStream_t st) {
+  hipLaunchKernelGGL(k_kv_compact, dim3(g.n_layers * 2 * g.n_kv_heads, b.n), dim3(256), 0, st, meta, tables, b, g);
+  return hipGetLastError();
+}
+hipError_t sp_launch_rows_compact(void* rows, size_t row_stride_bytes, int row_bytes, const RowList& l,
+                                  hipStream_t st) {
+  // slices of 256 bytes; a last narrower slice is handled by a second launch
+  const int slice = 256;
+  const int full = row_bytes / slice;
+  if (full > 0) {
+    hipLaunchKernelGGL(k_rows_compact, dim3(full), dim3(256), 0, st, (char*)rows, row_stride_bytes, slice, l);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  }
+  const int rest = row_bytes - full * slice;      // multiple of 16 by construction (d_model % 8 == 0)
+  if (rest > 0) {
+    hipLaunchKernelGGL(k_rows_compact, dim3(1), dim3(256), 0, st, (char*)rows + (size_t)full * slice,
+                       row_stride_bytes, rest, l);
+    return hipGetLastError();
+  }
+  return hipSuccess;
+}

@@ -1,0 +1,148 @@
+"""Runs the HIP stage and the CPU oracle side by side on the same seeded inputs."""
+from __future__ import annotations
+
+from typing import Dict, List, Optional, Sequence
+
+import numpy as np
+import torch
+
+import workloads as wl
+import paper_2504_04104_amd as sp
+from oracle import StageOracle
+
+
+def rel_err(gpu: np.ndarray, ref: np.ndarray) -> float:
+    """max |gpu - ref| / max |ref| over a tensor."""
+    ref = np.asarray(ref, np.float64)
+    gpu = np.asarray(gpu, np.float64)
+    return float(np.max(np.abs(gpu - ref)) / max(np.max(np.abs(ref)), 1e-30))
+
+
+def to_np(t: torch.Tensor) -> np.ndarray:
+    return t.detach().float().cpu().numpy()
+
+
+def to_dev(a: np.ndarray, stage: sp.Stage) -> torch.Tensor:
+    return torch.from_numpy(np.ascontiguousarray(a)).to(stage.device, stage.tdtype).contiguous()
+
+
+class Pair:
+    """A GPU stage and an oracle stage with identical weights and committed contexts."""
+
+    def __init__(self, shape: wl.ModelShape, seed: int, prefixes: Dict[int, int], *, tree_room: int = 256 + 64,
+                 flags: int = 0, max_batch_nodes: int = 64, oracle: bool = True):
+        self.shape, self.seed = shape, seed
+        self.weights = [wl.layer_weights(shape, seed, l) for l in range(shape.n_layers)]
+        layers = [sp.pack_layer_weights(w, shape.dtype) for w in self.weights]
+        n_req = max(prefixes) + 1
+        self.base: Dict[int, int] = {}
+        self.cap: Dict[int, int] = {}
+        off = 0
+        for r in sorted(prefixes):
+            self.base[r] = off
+            self.cap[r] = prefixes[r] + tree_room
+            off += self.cap[r]
+        self.gpu = sp.Stage(shape, layers, kv_slots=off, max_requests=n_req, max_batch_nodes=max_batch_nodes,
+                            flags=flags)
+        self.ora = StageOracle(shape, self.weights) if oracle else None
+        for r, P in prefixes.items():
+            pk, pv = zip(*[wl.prefix_kv(shape, seed, l, P, req=r) for l in range(shape.n_layers)])
+            for l in range(shape.n_layers):
+                sp.write_prefix(self.gpu, l, self.base[r], pk[l], pv[l])
+            self.gpu.request_init(r, self.base[r], self.cap[r], P)
+            if self.ora is not None:
+                self.ora.request_init(r, pk, pv, self.cap[r])
+
+    # -- the same call on both sides ------------------------------------------------
+    def insert(self, req: int, parents: Sequence[int], tokens=None, probs=None) -> int:
+        first = self.gpu.tree_insert(req, parents, tokens, probs)
+        if self.ora is not None:
+            assert self.ora.tree_insert(req, parents, tokens, probs) == first
+        return first
+
+    def forward(self, reqs: Sequence[int], firsts: Sequence[int], counts: Sequence[int], x: np.ndarray):
+        """x: [sum counts, d] float32 (already rounded to the storage type).  Returns (gpu, oracle)."""
+        y = to_np(self.gpu.stage_forward(reqs, firsts, counts, to_dev(x, self.gpu)))
+        ref = None
+        if self.ora is not None:
+            outs, row = [], 0
+            for r, f, n in zip(reqs, firsts, counts):
+                if n:
+                    outs.append(self.ora.stage_forward(r, f, x[row:row + n]))
+                row += n
+            ref = np.concatenate(outs) if outs else np.zeros_like(x, dtype=np.float64)
+        return y, ref
+
+    def tree_region(self, req: int, P: int, n: int) -> torch.Tensor:
+        """Raw slab rows of tree slots [P, P+n): [layer, K|V, head, n, d_head] (a copy)."""
+        b = self.base[req]
+        return self.gpu.kv_view()[:, :, :, b + P:b + P + n, :].clone()
+
+    def check_tables(self, req: int):
+        v = self.gpu.tree_read(req)
+        st = self.ora.req[req]
+        par, dep, tok, prob, M = st.tree.view()
+        assert v["prefix_len"] == st.P, (v["prefix_len"], st.P)
+        assert v["n_live"] == len(par)
+        assert np.array_equal(v["parent"], par)
+        assert np.array_equal(v["depth"], dep)
+        assert np.array_equal(v["token"], tok)
+        assert np.array_equal(v["prob"].view(np.uint32), prob.view(np.uint32))
+        assert np.array_equal(v["M"], M)
+        assert self.gpu.request_info(req)[:2] == (st.P, len(par))
+
+    def check_kv(self, req: int, tol: float):
+        """Tree-region K/V rows of every layer against the oracle's."""
+        st = self.ora.req[req]
+        n = st.tree.n - 1
+        if n == 0:
+            return
+        g = self.tree_region(req, st.P, n).float().cpu().numpy()
+        for l in range(self.shape.n_layers):
+            K, V = self.ora.tree_kv(req, l)                  # [n, H, d]
+            assert rel_err(g[l, 0].transpose(1, 0, 2), K) <= tol, ("K", l)
+            assert rel_err(g[l, 1].transpose(1, 0, 2), V) <= tol, ("V", l)
+
+    def prune(self, req: int, mode: int, node: int, x_rows: Optional[np.ndarray] = None,
+              row_nodes: Optional[Sequence[int]] = None):
+        """Prune + compact on both sides.  Checks that the cache compaction is the oracle's
+        stable selection applied to the GPU's own bytes, bit for bit, that rows in front of
+        the first dropped slot did not change, and the tables.  Returns surviving hidden rows
+        (gpu, oracle) if x_rows was given."""
+        st = self.ora.req[req]
+        P_old, T_old = st.P, st.tree.n - 1
+        before = self.tree_region(req, P_old, T_old)
+        untouched = self.gpu.kv_view()[:, :, :, self.base[req]:self.base[req] + P_old, :].clone()
+        live, commit = self.gpu.tree_prune(req, mode, node)
+        pr = self.ora.accept(req, node) if mode == sp.SP_ACCEPT else self.ora.drop(req, node)
+        assert commit == pr.n_commit and live == st.tree.n - 1
+        xg = None
+        if x_rows is not None:
+            xg = to_dev(x_rows, self.gpu)
+            n_out, new_nodes = self.gpu.kv_compact(req, xg, row_nodes)
+        else:
+            self.gpu.kv_compact(req)
+        keep = pr.kv_keep[1:]
+        n_keep = int(keep.sum())
+        after = self.tree_region(req, P_old, n_keep)
+        sel = torch.from_numpy(np.nonzero(keep)[0]).to(before.device)
+        expect = before.index_select(3, sel)                # oracle: rows[keep], stable
+        assert expect.shape[3] == n_keep
+        assert torch.equal(after.view(torch.uint8), expect.contiguous().view(torch.uint8))
+        now = self.gpu.kv_view()[:, :, :, self.base[req]:self.base[req] + P_old, :]
+        assert torch.equal(now.contiguous().view(torch.uint8), untouched.view(torch.uint8))
+        self.check_tables(req)
+        if x_rows is not None:
+            ref = self.ora.prune_hidden_rows(x_rows, row_nodes, pr)
+            assert n_out == ref.shape[0]
+            tab_new = np.cumsum(pr.table_keep) - 1           # new oracle index (root = 0)
+            want = [int(tab_new[k + 1]) - 1 if mode == sp.SP_ACCEPT else int(tab_new[k + 1]) - 1
+                    for k in row_nodes if pr.table_keep[k + 1]]
+            assert new_nodes == want, (new_nodes, want)
+            got = to_np(xg[:n_out])
+            assert np.array_equal(got, ref.astype(np.float32))
+            return got, ref
+        return None
+
+    def close(self):
+        self.gpu.close()

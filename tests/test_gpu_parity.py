@@ -1,0 +1,238 @@
+"""HIP path against the CPU oracle, through the C ABI, on seeded inputs.
+
+Bars: bit-exact for tables (parent, depth, token, prob, mask) and for cache/hidden-row
+compaction; hidden states and freshly written K/V rows within max|gpu - oracle| / max|oracle|
+<= 2e-2 for bf16 storage (the oracle computes in float64 from the same bf16-rounded weights,
+inputs and context) and <= 2e-4 for float32 storage (float32 accumulation over up to
+14336 terms against float64)."""
+import numpy as np
+import pytest
+import torch
+
+import workloads as wl
+import paper_2504_04104_amd as sp
+from gpu_harness import Pair, rel_err, to_dev, to_np
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"bf16": 2e-2, "f32": 2e-4}
+
+# small shapes that still span several tiles of every kernel and leave ragged tails
+MINI_BF16 = wl.ModelShape(n_layers=2, d_model=512, n_q_heads=4, n_kv_heads=2, d_head=128, d_ff=768)
+MINI_GQA4 = wl.ModelShape(n_layers=2, d_model=768, n_q_heads=8, n_kv_heads=2, d_head=128, d_ff=1280)
+MINI_F32 = wl.ModelShape(n_layers=2, d_model=256, n_q_heads=4, n_kv_heads=2, d_head=64, d_ff=688,
+                         rms_eps=1e-6, dtype="f32")
+
+
+def say(*a):
+    print(*a, flush=True)
+
+
+# ---------------------------------------------------------------------------------------
+def test_c1_tiny_fp32_forward_drop_compact():
+    """Config 1: 2 layers, d=256, 4 heads of 64, FFN 688, fp32, prefix 128, 16 nodes."""
+    w = wl.CONFIGS["C1"]
+    say("C1", w.shape)
+    pair = Pair(w.shape, w.seed, {0: w.prefix_len})
+    par = wl.tree_uniform_parents(w.seed, w.n_nodes, w.max_levels)
+    x = wl.hidden_rows(w.shape, w.seed, ("c1",), w.n_nodes)
+    pair.insert(0, par, tokens=list(range(100, 116)), probs=[0.5 + i / 64 for i in range(16)])
+    pair.check_tables(0)
+    y, ref = pair.forward([0], [0], [w.n_nodes], x)
+    e = rel_err(y, ref)
+    say("C1 rel err", e)
+    assert e <= TOL["f32"]
+    pair.check_kv(0, TOL["f32"])
+    node = int(wl.rng(w.seed, "c1drop").integers(0, w.n_nodes))
+    pair.prune(0, sp.SP_DROP, node, x_rows=y, row_nodes=list(range(w.n_nodes)))
+    pair.close()
+
+
+@pytest.mark.parametrize("flags", [sp.SP_FLAG_SIMPLE_KERNELS, 0], ids=["simple", "mfma"])
+@pytest.mark.parametrize("shape", [MINI_BF16, MINI_GQA4], ids=["g2", "g4"])
+def test_mini_bf16_forward(shape, flags):
+    """Several attention tiles with a ragged tail (prefix 300), 37 nodes (ragged M), both kernel sets."""
+    say("mini bf16", shape, flags)
+    pair = Pair(shape, 11, {0: 300}, flags=flags)
+    par = wl.tree_branching(11, 37, 3, 7)
+    x = wl.hidden_rows(shape, 11, ("m",), 37)
+    pair.insert(0, par)
+    y, ref = pair.forward([0], [0], [37], x)
+    e = rel_err(y, ref)
+    say("rel err", e)
+    assert e <= TOL["bf16"]
+    pair.check_kv(0, TOL["bf16"])
+    pair.close()
+
+
+def test_mini_f32_gqa_forward_in_pieces():
+    """fp32, grouped heads, nodes forwarded over several calls in ancestor order."""
+    pair = Pair(MINI_F32, 12, {0: 77})
+    par = wl.bfs_sorted(wl.tree_branching(12, 29, 3, 6))[0]
+    x = wl.hidden_rows(MINI_F32, 12, ("p",), 29)
+    cuts = [0, 2, 9, 10, 29]
+    for lo, hi in zip(cuts[:-1], cuts[1:]):
+        pair.insert(0, par[lo:hi])
+        y, ref = pair.forward([0], [lo], [hi - lo], x[lo:hi])
+        assert rel_err(y, ref) <= TOL["f32"]
+    pair.check_tables(0)
+    pair.check_kv(0, TOL["f32"])
+    pair.close()
+
+
+@pytest.mark.parametrize("n", [1, 15, 16, 17, 33, 64, 65, 130])
+def test_row_counts_across_tile_edges(n):
+    """M below, at and above the 16-row MFMA tile and the 64-row block."""
+    shape = MINI_BF16
+    pair = Pair(shape, 13, {0: 129}, max_batch_nodes=160)
+    par = wl.tree_uniform_parents(13, n, 9, name=("t", n))
+    x = wl.hidden_rows(shape, 13, ("r", n), n)
+    pair.insert(0, par)
+    y, ref = pair.forward([0], [0], [n], x)
+    e = rel_err(y, ref)
+    say("n", n, "rel err", e)
+    assert e <= TOL["bf16"]
+    pair.close()
+
+
+def test_tables_only_random_sequences():
+    """Insert / accept / drop sequences up to the 256-node cap: tables bit-exact after every call."""
+    pair = Pair(MINI_F32, 14, {0: 5}, tree_room=4096)
+    g = wl.rng(14, "seq")
+    n_live = 0
+    for step in range(60):
+        room = 256 - n_live
+        k = int(g.integers(0, min(room, 40) + 1))
+        parents = [int(g.integers(-1, n_live + i)) for i in range(k)]
+        toks = [int(g.integers(0, 1 << 20)) for _ in range(k)]
+        prbs = [float(g.random()) for _ in range(k)]
+        pair.insert(0, parents, toks, prbs)
+        n_live += k
+        pair.check_tables(0)
+        if n_live and g.random() < 0.8:
+            node = int(g.integers(0, n_live))
+            mode = sp.SP_ACCEPT if g.random() < 0.5 else sp.SP_DROP
+            pair.prune(0, mode, node)
+            n_live = pair.gpu.request_info(0)[1]
+    # fill to the cap exactly, then prune at the last node
+    pair.insert(0, [-1] * (256 - n_live))
+    pair.check_tables(0)
+    pair.prune(0, sp.SP_DROP, 255)
+    pair.prune(0, sp.SP_ACCEPT, 0)
+    pair.close()
+
+
+def test_streaming_mini():
+    """Config 4 in miniature: per step insert 1-8 nodes, forward only those, prune, compact
+    (cache and in-flight hidden rows); every step checked."""
+    shape = MINI_BF16
+    pair = Pair(shape, 15, {0: 200}, tree_room=700)
+    steps = wl.streaming_schedule(15, 40, max_new=8, cap=256, p_accept=0.7)
+    worst = 0.0
+    for s, st in enumerate(steps):
+        n = len(st.parents)
+        first = pair.insert(0, st.parents)
+        y = None
+        if n:
+            x = wl.hidden_rows(shape, 15, ("s", s), n)
+            y, ref = pair.forward([0], [first], [n], x)
+            worst = max(worst, rel_err(y, ref))
+        if st.prune is not None:
+            if y is not None:
+                pair.prune(0, st.prune.mode, st.prune.node, x_rows=y, row_nodes=list(range(first, first + n)))
+            else:
+                pair.prune(0, st.prune.mode, st.prune.node)
+        pair.check_kv(0, TOL["bf16"])
+    say("streaming worst rel err", worst)
+    assert worst <= TOL["bf16"]
+    pair.close()
+
+
+def test_ragged_batch_mini():
+    """Config 5 in miniature: several requests with their own prefix and tree in one call;
+    block-diagonal masks; batched prune + compaction."""
+    shape = MINI_GQA4
+    reqs = wl.batch_requests(16, n_req=5, p_lo=40, p_hi=333, t_lo=3, t_hi=20, max_levels=5)
+    pair = Pair(shape, 16, {r.req: r.prefix_len for r in reqs}, max_batch_nodes=128)
+    for r in reqs:
+        pair.insert(r.req, r.parents)
+    counts = [len(r.parents) for r in reqs]
+    x = wl.hidden_rows(shape, 16, ("b",), sum(counts))
+    y, ref = pair.forward([r.req for r in reqs], [0] * len(reqs), counts, x)
+    e = rel_err(y, ref)
+    say("batch cold rel err", e)
+    assert e <= TOL["bf16"]
+    sched = wl.batch_schedule(16, reqs, 6, max_new=6, max_levels=5)
+    for s, row in enumerate(sched):
+        # batched prune + compaction
+        ids = [r.req for r in reqs]
+        modes = [st.prune.mode if st.prune else -1 for st in row]
+        nodes = [st.prune.node if st.prune else 0 for st in row]
+        before = {}
+        for r, st in zip(reqs, row):
+            if st.prune:
+                o = pair.ora.req[r.req]
+                before[r.req] = (o.P, o.tree.n - 1, pair.tree_region(r.req, o.P, o.tree.n - 1))
+        live, commit = pair.gpu.tree_prune_batch(ids, modes, nodes)
+        act = [i for i, m in zip(ids, modes) if m >= 0]
+        pair.gpu.kv_compact_batch(act)
+        for i, (r, st) in enumerate(zip(reqs, row)):
+            if not st.prune:
+                continue
+            pr = pair.ora.accept(r.req, st.prune.node) if st.prune.mode == sp.SP_ACCEPT else pair.ora.drop(r.req, st.prune.node)
+            assert commit[i] == pr.n_commit
+            P_old, T_old, reg = before[r.req]
+            keep = pr.kv_keep[1:]
+            sel = torch.from_numpy(np.nonzero(keep)[0]).to(reg.device)
+            after = pair.tree_region(r.req, P_old, int(keep.sum()))
+            assert torch.equal(after.view(torch.uint8), reg.index_select(3, sel).contiguous().view(torch.uint8))
+            pair.check_tables(r.req)
+        firsts, counts, act_ids = [], [], []
+        for r, st in zip(reqs, row):
+            if st.parents:
+                firsts.append(pair.insert(r.req, st.parents))
+                counts.append(len(st.parents))
+                act_ids.append(r.req)
+        if act_ids:
+            x = wl.hidden_rows(shape, 16, ("b", s), sum(counts))
+            y, ref = pair.forward(act_ids, firsts, counts, x)
+            e = rel_err(y, ref)
+            assert e <= TOL["bf16"], (s, e)
+    pair.close()
+
+
+def test_error_codes():
+    pair = Pair(MINI_F32, 17, {0: 10}, tree_room=30, oracle=False)
+    g = pair.gpu
+
+    def status(fn, *a, **k):
+        try:
+            fn(*a, **k)
+        except sp.SpError as e:
+            return e.status
+        return 0
+
+    assert status(g.tree_insert, 3, [-1]) == -4                     # request never initialised
+    assert status(g.tree_insert, 0, [0]) == -3                      # parent does not exist
+    assert status(g.tree_insert, 0, [-1, 2]) == -3                  # parent not before child
+    assert status(g.tree_insert, 0, [-1] * 31) == -2                # slot range full
+    assert g.request_info(0) == (10, 0, 0)                          # nothing changed
+    g.tree_insert(0, [-1, 0, 1])
+    x = torch.zeros(1, MINI_F32.d_model, device=g.device)
+    assert status(g.stage_forward, [0], [2], [1], x) == -6          # parent 1 not forwarded
+    assert status(g.stage_forward, [0], [2], [5], torch.zeros(5, 256, device=g.device)) == -5
+    assert status(g.tree_prune, 0, sp.SP_ACCEPT, 3) == -5
+    assert status(g.kv_compact, 0) == -7                            # nothing pending
+    g.tree_prune(0, sp.SP_DROP, 2)
+    assert status(g.tree_insert, 0, [-1]) == -7                     # compaction pending
+    assert status(g.tree_prune, 0, sp.SP_DROP, 0) == -7
+    g.kv_compact(0)
+    assert g.request_info(0) == (10, 2, 0)
+    # a flushed tree: accept the only chain down to nothing, then hang a new level off the tail
+    g.stage_forward([0], [0], [2], torch.zeros(2, 256, device=g.device))
+    assert g.tree_prune(0, sp.SP_ACCEPT, 1) == (0, 2)
+    g.kv_compact(0)
+    assert g.request_info(0) == (12, 0, 0)
+    assert g.tree_insert(0, [-1, -1]) == 0
+    torch.cuda.synchronize()
+    pair.close()
