@@ -123,10 +123,10 @@ struct ProfScope {
   bool on;
   ProfScope(sp_stage* s_, int kind, hipStream_t st_) : s(s_), st(st_) {
     on = (s->prof_kind == kind && s->prof_n < s->prof_max);
-    if (on) hipEventRecord(s->prof_ev[2 * s->prof_n], st);
+    if (on) (void)hipEventRecord(s->prof_ev[2 * s->prof_n], st);
   }
   ~ProfScope() {
-    if (on) { hipEventRecord(s->prof_ev[2 * s->prof_n + 1], st); ++s->prof_n; }
+    if (on) { (void)hipEventRecord(s->prof_ev[2 * s->prof_n + 1], st); ++s->prof_n; }
   }
 };
 
@@ -248,7 +248,7 @@ int sp_stage_create(const sp_config* cfg, const sp_layer_weights* layers, const 
 
 void sp_stage_destroy(sp_stage* stage) {
   if (!stage) return;
-  for (hipEvent_t ev : stage->prof_ev) hipEventDestroy(ev);
+  for (hipEvent_t ev : stage->prof_ev) (void)hipEventDestroy(ev);
   delete stage;
 }
 
@@ -354,28 +354,39 @@ int sp_stage_forward(sp_stage* s, int32_t n_req, const int32_t* req_ids, const i
     int maxq = 0;
     for (int i = 0; i < b.n_req; ++i) if (b.n[i] * g > maxq) maxq = b.n[i] * g;
     plan.qt = maxq <= 16 ? 1 : 2;
-    const int qrows_per_wave = 16 * plan.qt;
-    int chunk_len = 128;
-    for (;;) {
-      size_t units = 0; int items = 0;
+    const int qrows_per_block = 16 * plan.qt;
+    auto fill = [&](int chunk_len, size_t* units_out) {
+      size_t units = 0; int items = 0, split = 0;
       for (int i = 0; i < b.n_req; ++i) {
         const HostReq& r = s->reqs[b.req[i]];
         const int span = r.P + r.T;
         const int chunks = (span + chunk_len - 1) / chunk_len;
-        const int qblocks = (b.n[i] * g + qrows_per_wave - 1) / qrows_per_wave;
+        const int qblocks = (b.n[i] * g + qrows_per_block - 1) / qrows_per_block;
         plan.seg_item0[i] = items; plan.seg_chunks[i] = chunks; plan.seg_qblocks[i] = qblocks;
-        plan.seg_row0[i] = b.row0[i]; plan.seg_rows[i] = b.n[i]; plan.seg_P[i] = r.P;
+        plan.seg_row0[i] = b.row0[i]; plan.seg_rows[i] = b.n[i]; plan.seg_req[i] = b.req[i];
+        plan.seg_first[i] = b.first[i]; plan.seg_P[i] = r.P; plan.seg_T[i] = r.T; plan.seg_base[i] = r.base;
         plan.seg_unit0[i] = (int)units;
         items += chunks * qblocks;
-        units += (size_t)chunks * b.n[i] * nq;
+        if (chunks > 1) { units += (size_t)chunks * b.n[i] * nq; split = 1; }
       }
       plan.seg_item0[b.n_req] = items;
       plan.total_items = items;
       plan.units_total = (int)units;
       plan.chunk_len = chunk_len;
-      if (units <= w.attn_units && (size_t)items * nkv <= 16384) break;
-      chunk_len *= 2;
+      plan.any_split = split;
+      *units_out = units;
+      return items;
+    };
+    // Whole cache ranges if that already gives every CU a workgroup; otherwise halve the
+    // chunk (down to one 32-slot tile per wave) until it does.  Then grow it again if the
+    // partial results would not fit the workspace.
+    size_t units = 0;
+    int chunk_len = 1 << 20;
+    while (fill(chunk_len, &units) * nkv < 256 && chunk_len > 256) chunk_len >>= 1;
+    while (units > w.attn_units) {
+      chunk_len <<= 1;
       if (chunk_len > (1 << 20)) return SP_E_CAPACITY;
+      fill(chunk_len, &units);
     }
   }
 
@@ -393,7 +404,7 @@ int sp_stage_forward(sp_stage* s, int32_t n_req, const int32_t* req_ids, const i
       SP_TRY(sp_launch_rope_kv(dt, w.part, S, strideQ, w.rows, w.cs, w.qbuf, s->geom, l, M, nq, nkv, dh, st)); }
     if (s->fast) {
       ProfScope p(s, SP_K_ATTENTION, st);
-      SP_TRY(sp_launch_attn_bf16((const bf16_t*)w.qbuf, w.rows, s->d_tables, s->geom, l, plan, w.attn_part,
+      SP_TRY(sp_launch_attn_bf16((const bf16_t*)w.qbuf, s->d_tables, s->geom, l, plan, w.attn_part,
                                  (bf16_t*)w.attn, M, nq, nkv, dh, st));
     } else {
       ProfScope p(s, SP_K_ATTENTION, st);

@@ -1,12 +1,15 @@
 // Tree-masked attention on the matrix cores (Sec. 2.1 attention, Sec. 2.2 and 3.3.2
 // tree mask), bf16, d_head = 128, grouped-query.
 //
-// Work is split over (request, KV head, block of query rows, chunk of cache slots);
-// one wave owns one such item and streams its chunk's K and V rows from HBM once for
-// all of its query rows (the g query heads of the group times the tree nodes).  The
-// committed context is visible to every node; a tree slot is visible to a node iff
-// its bit is set in the node's ancestor mask.  Each wave leaves an un-normalised
-// partial (running max, sum, output) per query row; a second kernel merges the chunks.
+// A workgroup of eight waves owns one (request, KV head, block of query rows, chunk of
+// cache slots).  Its waves cut the chunk into eight runs of 32-slot tiles; each wave
+// streams the K and V rows of its run from HBM exactly once for all query rows of the
+// block (the g query heads of the group times the tree nodes), keeps an online softmax,
+// and the eight states are folded together through LDS.  If the request's whole cache
+// range is one chunk the block's output is final; otherwise an un-normalised partial
+// (running max, sum, output) is left per query row and a second kernel merges the chunks.
+// The committed context is visible to every node; a tree slot is visible to a node iff its
+// bit is set in the node's ancestor mask.
 //
 // MFMA use (v_mfma_f32_16x16x32_bf16, D[4*(l/16)+i][l%16]):
 //   S^T = K Q^T : A = 16 slots x 32 d (straight from global, 16 B per lane),
@@ -19,66 +22,80 @@
 
 #define DH 128
 #define VS 272            // LDS row stride of the V tile in bytes (256 + 16)
-
-__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
-  return (uint32_t)f32_to_bf16(lo) | ((uint32_t)f32_to_bf16(hi) << 16);
-}
+#define AW 8              // waves per workgroup
+#define VT_BYTES (32 * VS)
 
 struct AttnArgs {
   const bf16_t* q;          // [M][n_q][DH]
-  const RowInfo* rows;
   const ReqTables* tables;
   KvGeom g;
   int layer, n_q, n_kv;
   float* part_o;            // [units][DH]
   float* part_ml;           // [units][2]
+  bf16_t* out;              // [M][n_q][DH]
 };
 
 template <int QT>
-__global__ void __launch_bounds__(256) k_attn_bf16(AttnArgs a, AttnPlan plan, int qt_rows) {
-  __shared__ __attribute__((aligned(16))) char s_v[4][32 * VS];
+__global__ void __launch_bounds__(64 * AW) k_attn_bf16(AttnArgs a, AttnPlan plan) {
+  // V tiles of the eight waves; the same bytes later carry the states being folded
+  // (four waves x QT x 8 d-tiles x 64 lanes x 16 B = QT * 32 KB <= 8 * VT_BYTES for QT <= 2).
+  __shared__ __attribute__((aligned(16))) char s_v[AW * VT_BYTES];
+  __shared__ float s_m[AW][QT * 16];
+  __shared__ float s_l[AW][QT * 16];
+  static_assert(4 * QT * 8 * 64 * 16 <= AW * VT_BYTES, "fold buffer");
+
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  const int item = blockIdx.x * 4 + wave;
-  if (item >= plan.total_items) return;            // whole wave; no block-level barriers below
-  const int kvh = blockIdx.y;
+  // KV head fastest: consecutive workgroup ids go round-robin over the 8 XCDs, so all query
+  // blocks and chunks of one KV head share one XCD's L2 and its K/V rows are fetched from HBM once
+  const int kvh = blockIdx.x % a.n_kv;
+  const int item = blockIdx.x / a.n_kv;
   int seg = 0;
   while (seg + 1 < plan.n_seg && item >= plan.seg_item0[seg + 1]) ++seg;
   const int local = item - plan.seg_item0[seg];
   const int chunks = plan.seg_chunks[seg];
   const int qb = local / chunks, ch = local - qb * chunks;
   const int g = a.n_q / a.n_kv;
+  const float inv_g = 1.f / (float)g;              // (qi + 0.5) * inv_g truncates to qi / g for these small integers
   const int seg_rows = plan.seg_rows[seg], row0 = plan.seg_row0[seg];
   const int nqrows = seg_rows * g;                 // query rows of this (request, KV head)
-
-  const RowInfo r0 = a.rows[row0];
-  const int P = r0.P, T = r0.T;
+  const int P = plan.seg_P[seg], T = plan.seg_T[seg];
   const int span = P + T;
   const int c0 = ch * plan.chunk_len;
   const int c1 = min(c0 + plan.chunk_len, span);
+  // this wave's run of 32-slot tiles inside [c0, c1)
+  const int ntiles = (c1 - c0 + 31) >> 5;
+  const int w0 = c0 + 32 * ((wave * ntiles) / AW);
+  const int w1 = min(c0 + 32 * (((wave + 1) * ntiles) / AW), c1);
   const int l15 = lane & 15, kg = lane >> 4;
 
   // ---- query fragments and ancestor masks of this lane's query row per tile ------
   u32x4_t qf[QT][4];
   unsigned long long anc[QT][SP_W];
-  int qrow_ok[QT];
+  bool qrow_ok[QT];
+  const ReqTables* tab = a.tables + plan.seg_req[seg];
 #pragma unroll
   for (int t = 0; t < QT; ++t) {
-    const int qi = qb * qt_rows + t * 16 + l15;    // index inside (request, KV head): node_local * g + gq
+    const int qi = qb * (QT * 16) + t * 16 + l15;  // index inside (request, KV head): node_local * g + gq
     const bool ok = qi < nqrows;
     qrow_ok[t] = ok;
-    const int nl = ok ? qi / g : 0, gq = ok ? qi - nl * g : 0;
-    const int row = row0 + nl;
-    const bf16_t* qp = a.q + ((size_t)row * a.n_q + (size_t)kvh * g + gq) * DH + kg * 8;
+    const int nl = ok ? (int)(((float)qi + 0.5f) * inv_g) : 0, gq = ok ? qi - nl * g : 0;
+    const bf16_t* qp = a.q + ((size_t)(row0 + nl) * a.n_q + (size_t)kvh * g + gq) * DH + kg * 8;
 #pragma unroll
-    for (int s = 0; s < 4; ++s)
-      qf[t][s] = ok ? *reinterpret_cast<const u32x4_t*>(qp + s * 32) : (u32x4_t){0u, 0u, 0u, 0u};
-    const int node = a.rows[row].node;
+    for (int s = 0; s < 4; ++s) {
+      const u32x4_t v = *reinterpret_cast<const u32x4_t*>(qp + s * 32);
+      qf[t][s] = ok ? v : (u32x4_t){0u, 0u, 0u, 0u};
+    }
+    const int node = plan.seg_first[seg] + nl;
 #pragma unroll
-    for (int w = 0; w < SP_W; ++w) anc[t][w] = ok ? a.tables[r0.req].anc[node][w] : 0ull;
+    for (int w = 0; w < SP_W; ++w) {
+      const unsigned long long v = tab->anc[node][w];
+      anc[t][w] = ok ? v : 0ull;
+    }
   }
 
-  const char* kplane = a.g.kv + ((size_t)(a.layer * 2 + 0) * a.n_kv + kvh) * a.g.plane_bytes + (size_t)r0.base * 256;
-  const char* vplane = a.g.kv + ((size_t)(a.layer * 2 + 1) * a.n_kv + kvh) * a.g.plane_bytes + (size_t)r0.base * 256;
+  const size_t base_b = (size_t)plan.seg_base[seg] * 256;
+  const char* kplane = a.g.kv + ((size_t)(a.layer * 2 + 0) * a.n_kv + kvh) * a.g.plane_bytes + base_b;
+  const char* vplane = a.g.kv + ((size_t)(a.layer * 2 + 1) * a.n_kv + kvh) * a.g.plane_bytes + base_b;
 
   f32x4_t o[QT][8];
   float mrun[QT], lrun[QT];
@@ -89,6 +106,11 @@ __global__ void __launch_bounds__(256) k_attn_bf16(AttnArgs a, AttnPlan plan, in
     for (int d = 0; d < 8; ++d) o[t][d] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
   }
   const float sc = 0.08838834764831845f * 1.4426950408889634f;   // 1/sqrt(128) * log2(e)
+  // mrun is the running maximum of the raw scores q.k; negm = -mrun*sc (0 while mrun is -inf),
+  // so that exp2(fma(s, sc, negm)) is the softmax weight
+  float negm[QT];
+#pragma unroll
+  for (int t = 0; t < QT; ++t) negm[t] = 0.f;
 
   // Loads of one 32-slot tile: K as MFMA A fragments (row l15 of each 16-slot half, 16 B at
   // d = s*32 + kg*8), V as plain 16-byte pieces (row i*4+kg, piece l15).  Slots past the
@@ -100,54 +122,52 @@ __global__ void __launch_bounds__(256) k_attn_bf16(AttnArgs a, AttnPlan plan, in
       slot = slot < span ? slot : 0;                                                               \
       const char* kp = kplane + (size_t)slot * 256 + kg * 16;                                      \
       _Pragma("unroll") for (int s = 0; s < 4; ++s)                                                \
-          kreg[t2][s] = *reinterpret_cast<const u32x4_t*>(kp + s * 64);                              \
+          kreg[t2][s] = *reinterpret_cast<const u32x4_t*>(kp + s * 64);                            \
     }                                                                                              \
     _Pragma("unroll") for (int i = 0; i < 8; ++i) {                                                \
       int slot = (S0) + i * 4 + kg;                                                                \
       slot = slot < span ? slot : 0;                                                               \
-      vreg[i] = *reinterpret_cast<const u32x4_t*>(vplane + (size_t)slot * 256 + l15 * 16);           \
+      vreg[i] = *reinterpret_cast<const u32x4_t*>(vplane + (size_t)slot * 256 + l15 * 16);         \
     }                                                                                              \
   }
 
   u32x4_t kreg[2][4], vreg[8];
-  char* vt = s_v[wave];
-  SP_LOAD_TILE(c0)
-  for (int s0 = c0; s0 < c1; s0 += 32) {
-    // V tile -> LDS, K fragments -> a second register set, then the next tile's loads
-    // are issued so that they fly during this tile's math (the tile after the last one
-    // re-reads slot 0 and is discarded).
+  char* vt = s_v + wave * VT_BYTES;
+  SP_LOAD_TILE(w0 < w1 ? w0 : span)
+  for (int s0 = w0; s0 < w1; s0 += 32) {
+    // V tile -> LDS and the K fragments into the score MFMAs; then the next tile's loads
+    // are issued so that they fly during the softmax and the PV product (the tile after
+    // the last one re-reads slot 0 and is discarded).
     __builtin_amdgcn_wave_barrier();
 #pragma unroll
     for (int i = 0; i < 8; ++i) *reinterpret_cast<u32x4_t*>(vt + (i * 4 + kg) * VS + l15 * 16) = vreg[i];
-    u32x4_t kc[2][4];
+    // scores of every query tile first, so that the K registers are free for the next loads
+    f32x4_t sacc[QT][2];
 #pragma unroll
-    for (int t2 = 0; t2 < 2; ++t2)
+    for (int t = 0; t < QT; ++t)
 #pragma unroll
-      for (int s = 0; s < 4; ++s) kc[t2][s] = kreg[t2][s];
+      for (int t2 = 0; t2 < 2; ++t2) {
+        sacc[t][t2] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int s = 0; s < 4; ++s)
+          sacc[t][t2] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(*reinterpret_cast<const bf16x8_t*>(&kreg[t2][s]),
+                                                                *reinterpret_cast<const bf16x8_t*>(&qf[t][s]),
+                                                                sacc[t][t2], 0, 0, 0);
+      }
     {
-      const int nxt = (s0 + 32 < c1) ? s0 + 32 : span;     // span: every slot clamps to 0
+      const int nxt = (s0 + 32 < w1) ? s0 + 32 : span;     // span: every slot clamps to 0
       SP_LOAD_TILE(nxt)
     }
 
-    const bool tail = s0 + 32 > P || s0 + 32 > c1;   // tile touches the tree region or the chunk end
+    const bool tail = s0 + 32 > P || s0 + 32 > w1;   // tile touches the tree region or the run's end
     uint32_t pb[QT][4];
 #pragma unroll
     for (int t = 0; t < QT; ++t) {
-      f32x4_t sacc[2];
-#pragma unroll
-      for (int t2 = 0; t2 < 2; ++t2) {
-        sacc[t2] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int s = 0; s < 4; ++s)
-          sacc[t2] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(*reinterpret_cast<const bf16x8_t*>(&kc[t2][s]),
-                                                             *reinterpret_cast<const bf16x8_t*>(&qf[t][s]),
-                                                             sacc[t2], 0, 0, 0);
-      }
       float sv[8];
 #pragma unroll
       for (int t2 = 0; t2 < 2; ++t2)
 #pragma unroll
-        for (int i = 0; i < 4; ++i) sv[t2 * 4 + i] = sacc[t2][i] * sc;
+        for (int i = 0; i < 4; ++i) sv[t2 * 4 + i] = sacc[t][t2][i];
       if (tail) {
         // bits [n0, n0+64) of the row's 256-bit ancestor mask, n0 = first tree index of the tile
         const int n0 = s0 - P;
@@ -157,31 +177,31 @@ __global__ void __launch_bounds__(256) k_attn_bf16(AttnArgs a, AttnPlan plan, in
           const int sh = w * 64 - n0;
           if (sh > -64 && sh < 64) win |= sh >= 0 ? (anc[t][w] << sh) : (anc[t][w] >> (-sh));
         }
+        const int lim = w1 - s0, pfx = P - s0, tl = span - s0;   // offsets below: in run / committed / live
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
           const int off = (j >> 2) * 16 + kg * 4 + (j & 3);
-          const int slot = s0 + off;
-          bool vis = slot < c1;
-          if (slot >= P) vis = vis && (slot - P) < T && ((win >> off) & 1ull);
-          if (!vis) sv[j] = -INFINITY;
+          const bool vis = (off < lim) & ((off < pfx) | ((off < tl) & (bool)((win >> off) & 1ull)));
+          sv[j] = vis ? sv[j] : -INFINITY;
         }
       }
-      float mx = sv[0];
+      float mx = fmaxf(fmaxf(fmaxf(sv[0], sv[1]), fmaxf(sv[2], sv[3])), fmaxf(fmaxf(sv[4], sv[5]), fmaxf(sv[6], sv[7])));
+      // The running maximum only has to bound the scores, so it is raised (and the
+      // accumulators rescaled) only when some lane of the wave sees a larger score.
+      if (__builtin_amdgcn_ballot_w64(mx > mrun[t])) {
+        mx = quad_rows_max(mx);
+        const float mnew = fmaxf(mrun[t], mx);
+        const float alpha = (mnew == -INFINITY) ? 1.f : __builtin_amdgcn_exp2f((mrun[t] - mnew) * sc);  // 0 from -inf
+        lrun[t] *= alpha;
 #pragma unroll
-      for (int j = 1; j < 8; ++j) mx = fmaxf(mx, sv[j]);
-      mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
-      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-      const float mnew = fmaxf(mrun[t], mx);
-      const float msafe = (mnew == -INFINITY) ? 0.f : mnew;
-      const float alpha = exp2f(mrun[t] - msafe);           // 0 when mrun is -inf
-      float ps = 0.f;
+        for (int d = 0; d < 8; ++d) o[t][d] *= alpha;
+        mrun[t] = mnew;
+        negm[t] = (mnew == -INFINITY) ? 0.f : -mnew * sc;
+      }
       float pv[8];
 #pragma unroll
-      for (int j = 0; j < 8; ++j) { pv[j] = exp2f(sv[j] - msafe); ps += pv[j]; }
-      lrun[t] = lrun[t] * alpha + ps;
-      mrun[t] = mnew;
-#pragma unroll
-      for (int d = 0; d < 8; ++d) o[t][d] *= alpha;
+      for (int j = 0; j < 8; ++j) pv[j] = __builtin_amdgcn_exp2f(__builtin_fmaf(sv[j], sc, negm[t]));
+      lrun[t] += ((pv[0] + pv[1]) + (pv[2] + pv[3])) + ((pv[4] + pv[5]) + (pv[6] + pv[7]));
 #pragma unroll
       for (int j = 0; j < 4; ++j) pb[t][j] = pack_bf16x2(pv[2 * j], pv[2 * j + 1]);
     }
@@ -211,40 +231,100 @@ __global__ void __launch_bounds__(256) k_attn_bf16(AttnArgs a, AttnPlan plan, in
       }
     }
   }
+#undef SP_LOAD_TILE
 
-  // ---- partial results ------------------------------------------------------------
+  // ---- fold the eight wave states (fixed order, so results do not depend on timing) ----
+#pragma unroll
+  for (int t = 0; t < QT; ++t) {
+    lrun[t] = quad_rows_sum(lrun[t]);
+    mrun[t] = mrun[t] * sc;              // to the log2 domain (-inf stays -inf)
+    if (kg == 0) s_m[wave][t * 16 + l15] = mrun[t];
+  }
+  __syncthreads();                       // every wave is done with its V tile; maxima are posted
+  float mall[QT];
+#pragma unroll
+  for (int t = 0; t < QT; ++t) {
+    float m = -INFINITY;
+#pragma unroll
+    for (int w = 0; w < AW; ++w) m = fmaxf(m, s_m[w][t * 16 + l15]);
+    mall[t] = m;
+    const float f = (mrun[t] == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(mrun[t] - m);
+    lrun[t] *= f;
+#pragma unroll
+    for (int d = 0; d < 8; ++d) o[t][d] *= f;
+  }
+  f32x4_t* fold = reinterpret_cast<f32x4_t*>(s_v);
+#pragma unroll
+  for (int half = AW / 2; half >= 1; half >>= 1) {
+    if (wave >= half && wave < 2 * half) {
+#pragma unroll
+      for (int t = 0; t < QT; ++t) {
+#pragma unroll
+        for (int d = 0; d < 8; ++d) fold[(((wave - half) * QT + t) * 8 + d) * 64 + lane] = o[t][d];
+        if (kg == 0) s_l[wave - half][t * 16 + l15] = lrun[t];
+      }
+    }
+    __syncthreads();
+    if (wave < half) {
+#pragma unroll
+      for (int t = 0; t < QT; ++t) {
+#pragma unroll
+        for (int d = 0; d < 8; ++d) o[t][d] += fold[((wave * QT + t) * 8 + d) * 64 + lane];
+        lrun[t] += s_l[wave][t * 16 + l15];
+      }
+    }
+    __syncthreads();
+  }
+  if (wave != 0) return;
+
+  // ---- wave 0 writes the block's result --------------------------------------------
   // o[t][2G+h][i] is output column G*32 + 2*(4*kg+i) + h of query row t*16 + l15.
   const size_t unit0 = (size_t)plan.seg_unit0[seg] + (size_t)ch * seg_rows * a.n_q;
 #pragma unroll
   for (int t = 0; t < QT; ++t) {
-    float l = lrun[t];
-    l += __shfl_xor(l, 16, 64);
-    l += __shfl_xor(l, 32, 64);
     if (!qrow_ok[t]) continue;
-    const int qi = qb * qt_rows + t * 16 + l15;
-    const int nl = qi / g, gq = qi - nl * g;
-    const size_t unit = unit0 + (size_t)nl * a.n_q + (size_t)kvh * g + gq;
-    float* po = a.part_o + unit * DH;
+    const int qi = qb * (QT * 16) + t * 16 + l15;
+    const int nl = (int)(((float)qi + 0.5f) * inv_g), gq = qi - nl * g;
+    const int head = kvh * g + gq;
+    if (chunks == 1) {
+      const float inv = 1.f / lrun[t];
+      bf16_t* po = a.out + ((size_t)(row0 + nl) * a.n_q + head) * DH;
 #pragma unroll
-    for (int G = 0; G < 4; ++G) {
-      f32x4_t lo, hi;
-      lo[0] = o[t][2 * G][0]; lo[1] = o[t][2 * G + 1][0]; lo[2] = o[t][2 * G][1]; lo[3] = o[t][2 * G + 1][1];
-      hi[0] = o[t][2 * G][2]; hi[1] = o[t][2 * G + 1][2]; hi[2] = o[t][2 * G][3]; hi[3] = o[t][2 * G + 1][3];
-      *reinterpret_cast<f32x4_t*>(po + G * 32 + 8 * kg) = lo;
-      *reinterpret_cast<f32x4_t*>(po + G * 32 + 8 * kg + 4) = hi;
+      for (int G = 0; G < 4; ++G) {
+        u32x4_t pk;
+        pk.x = pack_bf16x2(o[t][2 * G][0] * inv, o[t][2 * G + 1][0] * inv);
+        pk.y = pack_bf16x2(o[t][2 * G][1] * inv, o[t][2 * G + 1][1] * inv);
+        pk.z = pack_bf16x2(o[t][2 * G][2] * inv, o[t][2 * G + 1][2] * inv);
+        pk.w = pack_bf16x2(o[t][2 * G][3] * inv, o[t][2 * G + 1][3] * inv);
+        *reinterpret_cast<u32x4_t*>(po + G * 32 + 8 * kg) = pk;
+      }
+    } else {
+      const size_t unit = unit0 + (size_t)nl * a.n_q + head;
+      float* po = a.part_o + unit * DH;
+#pragma unroll
+      for (int G = 0; G < 4; ++G) {
+        f32x4_t lo, hi;
+        lo[0] = o[t][2 * G][0]; lo[1] = o[t][2 * G + 1][0]; lo[2] = o[t][2 * G][1]; lo[3] = o[t][2 * G + 1][1];
+        hi[0] = o[t][2 * G][2]; hi[1] = o[t][2 * G + 1][2]; hi[2] = o[t][2 * G][3]; hi[3] = o[t][2 * G + 1][3];
+        *reinterpret_cast<f32x4_t*>(po + G * 32 + 8 * kg) = lo;
+        *reinterpret_cast<f32x4_t*>(po + G * 32 + 8 * kg + 4) = hi;
+      }
+      if (kg == 0) { a.part_ml[unit * 2] = mall[t]; a.part_ml[unit * 2 + 1] = lrun[t]; }
     }
-    if (kg == 0) { a.part_ml[unit * 2] = mrun[t]; a.part_ml[unit * 2 + 1] = l; }
   }
 }
 
-// One wave per (row, query head): combine the chunk partials (log2-domain maxima).
-__global__ void __launch_bounds__(256) k_attn_merge(AttnArgs a, AttnPlan plan, bf16_t* out, int M) {
+// One wave per (row, query head) of the requests that were cut into several chunks:
+// combine the chunk partials (log2-domain maxima).
+__global__ void __launch_bounds__(256) k_attn_merge(AttnArgs a, AttnPlan plan, int M) {
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int item = blockIdx.x * 4 + wave;
   if (item >= M * a.n_q) return;
   const int row = item / a.n_q, head = item - row * a.n_q;
-  const int seg = a.rows[row].seg;
+  int seg = 0;
+  while (seg + 1 < plan.n_seg && row >= plan.seg_row0[seg + 1]) ++seg;
   const int chunks = plan.seg_chunks[seg], seg_rows = plan.seg_rows[seg];
+  if (chunks == 1) return;               // written directly by the attention kernel
   const size_t stride = (size_t)seg_rows * a.n_q;
   const size_t u0 = (size_t)plan.seg_unit0[seg] + (size_t)(row - plan.seg_row0[seg]) * a.n_q + head;
   float mx = -INFINITY;
@@ -255,33 +335,33 @@ __global__ void __launch_bounds__(256) k_attn_merge(AttnArgs a, AttnPlan plan, b
     const size_t u = u0 + c * stride;
     const float m = a.part_ml[u * 2], l = a.part_ml[u * 2 + 1];
     if (m == -INFINITY) continue;
-    const float wgt = exp2f(m - mx);
+    const float wgt = __builtin_amdgcn_exp2f(m - mx);
     lsum += wgt * l;
     acc0 += wgt * a.part_o[u * DH + lane];
     acc1 += wgt * a.part_o[u * DH + 64 + lane];
   }
   const float inv = 1.f / lsum;
-  bf16_t* po = out + ((size_t)row * a.n_q + head) * DH;
+  bf16_t* po = a.out + ((size_t)row * a.n_q + head) * DH;
   po[lane] = f32_to_bf16(acc0 * inv);
   po[64 + lane] = f32_to_bf16(acc1 * inv);
 }
 
-hipError_t sp_launch_attn_bf16(const bf16_t* q, const RowInfo* rows, const ReqTables* tables, KvGeom g, int layer,
-                               const AttnPlan& plan, float* part, bf16_t* out, int M, int n_q, int n_kv, int d_head,
-                               hipStream_t st) {
+hipError_t sp_launch_attn_bf16(const bf16_t* q, const ReqTables* tables, KvGeom g, int layer, const AttnPlan& plan,
+                               float* part, bf16_t* out, int M, int n_q, int n_kv, int d_head, hipStream_t st) {
   if (d_head != DH || g.row_bytes != 256) return hipErrorInvalidValue;
   AttnArgs a;
-  a.q = q; a.rows = rows; a.tables = tables; a.g = g; a.layer = layer; a.n_q = n_q; a.n_kv = n_kv;
+  a.q = q; a.tables = tables; a.g = g; a.layer = layer; a.n_q = n_q; a.n_kv = n_kv;
   a.part_o = part;
   a.part_ml = part + (size_t)plan.units_total * DH;
-  dim3 grid((plan.total_items + 3) / 4, n_kv);
+  a.out = out;
+  dim3 grid(plan.total_items * n_kv);
   switch (plan.qt) {
-    case 1: hipLaunchKernelGGL(k_attn_bf16<1>, grid, dim3(256), 0, st, a, plan, 16); break;
-    case 2: hipLaunchKernelGGL(k_attn_bf16<2>, grid, dim3(256), 0, st, a, plan, 32); break;
+    case 1: hipLaunchKernelGGL(k_attn_bf16<1>, grid, dim3(64 * AW), 0, st, a, plan); break;
+    case 2: hipLaunchKernelGGL(k_attn_bf16<2>, grid, dim3(64 * AW), 0, st, a, plan); break;
     default: return hipErrorInvalidValue;
   }
   hipError_t e = hipGetLastError();
-  if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(k_attn_merge, dim3((M * n_q + 3) / 4), dim3(256), 0, st, a, plan, out, M);
+  if (e != hipSuccess || !plan.any_split) return e;
+  hipLaunchKernelGGL(k_attn_merge, dim3((M * n_q + 3) / 4), dim3(256), 0, st, a, plan, M);
   return hipGetLastError();
 }

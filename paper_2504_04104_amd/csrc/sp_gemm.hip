@@ -2,8 +2,8 @@
 // CDNA4 matrix cores.  With so few rows every weight is used once, so the kernel is a
 // weight streamer (decode is bound by loading parameters, Sec. 2.2): each wave pulls
 // its 16 weight rows straight from HBM into registers in MFMA operand layout (one
-// 16-byte load per lane per k-step, two chunks deep), while the M x K activation
-// panel -- shared by every wave -- is staged once per workgroup through LDS.
+// 16-byte load per lane per k-step, PF chunks ahead of the math), while the M x K
+// activation panel -- shared by every wave -- is staged once per workgroup through LDS.
 //
 //   out[y][m][n] = sum_{k in slice y} X[m][k] * W[n][k]        (f32 partial sums)
 //
@@ -11,17 +11,39 @@
 // B = 32 k x 16 activation rows (lane l: row l%16, same k), D[4*(l/16)+i][l%16].
 #include "sp_launch.h"
 
-#define KC 256                 // k per staged chunk
-#define XS 528                 // LDS row stride in bytes: KC*2 + 16 (conflict-free 16-byte reads)
+// Tunables (defaults chosen by measurement on MI355X).
+#ifndef SP_GEMM_KC_PLAIN
+#define SP_GEMM_KC_PLAIN 128      // k per staged chunk (smaller LDS panel: three workgroups per CU)
+#endif
+#ifndef SP_GEMM_KC_GATEUP
+#define SP_GEMM_KC_GATEUP 256
+#endif
+#ifndef SP_GEMM_PF
+#define SP_GEMM_PF 2              // weight chunks in flight ahead of the math
+#endif
+#ifndef SP_GEMM_NCG_PLAIN
+#define SP_GEMM_NCG_PLAIN 4       // column groups (of 16 weight rows) per workgroup
+#endif
+#ifndef SP_GEMM_NCG_GATEUP
+#define SP_GEMM_NCG_GATEUP 2
+#endif
+#ifndef SP_GEMM_TARGET_WGS
+#define SP_GEMM_TARGET_WGS 768    // split K until the grid has about this many workgroups
+#endif
 
-template <int MT, int NCG, bool GATEUP>
+template <int MT, int NCG, bool GATEUP, int KC, int PF>
 __global__ void __launch_bounds__(256)
 k_gemm_bf16(const bf16_t* __restrict__ X, const bf16_t* __restrict__ W, float* __restrict__ out,
             bf16_t* __restrict__ act, int M, int N, int K, int chunks_total, int S) {
-  constexpr int NKH = 4 / NCG;          // waves sharing a column group split each chunk's k-steps
-  constexpr int KSTEPS = 8 / NKH;
+  constexpr int NKH = 4 / NCG;            // waves sharing a column group split each chunk's k-steps
+  constexpr int KSTEPS = (KC / 32) / NKH;
   constexpr int NW = GATEUP ? 2 : 1;
   constexpr int ROWS = MT * 16;
+  constexpr int XS = KC * 2 + 16;         // LDS row stride in bytes (conflict-free 16-byte reads)
+  constexpr int UPR = KC / 8;             // 16-byte units per X row chunk
+  constexpr int RPP = 256 / UPR;          // rows per staging pass
+  constexpr int PASSES = ROWS / RPP;
+  constexpr int NB = PF + 1;              // weight register buffers
   __shared__ __attribute__((aligned(16))) char lds[2][ROWS * XS];
 
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
@@ -34,68 +56,75 @@ k_gemm_bf16(const bf16_t* __restrict__ X, const bf16_t* __restrict__ W, float* _
 
   const bf16_t* w0 = W + (size_t)(n0 + r) * K + kg * 8 + kh * (KSTEPS * 32);
   const bf16_t* w1 = W + (size_t)(N + n0 + r) * K + kg * 8 + kh * (KSTEPS * 32);   // up rows (GATEUP)
-  const int xu = tid & 31, xr = tid >> 5;       // 16-byte unit and row (8 rows per pass) of the X stager
+#define SP_WOFF(C, s) ((size_t)(C)*KC + (s) * 32)
+  const int xu = tid % UPR, xr = tid / UPR;
+  // rows past M are read from the last valid row and multiply into output rows that are never stored
+  const int m_last = M - 1;
 
-  uint4 wcur[NW][KSTEPS], wnxt[NW][KSTEPS];
-  uint4 xnxt[2 * MT];
+  u32x4_t wb[NB][NW][KSTEPS];
+  u32x4_t xnxt[PASSES];
   f32x4_t acc[NW][MT];
 #pragma unroll
   for (int a = 0; a < NW; ++a)
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) acc[a][mt] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
 
-  auto load_x = [&](int c) {
-#pragma unroll
-    for (int p = 0; p < 2 * MT; ++p) {
-      const int m = m_base + p * 8 + xr;
-      xnxt[p] = (m < M) ? *reinterpret_cast<const uint4*>(X + (size_t)m * K + (size_t)c * KC + xu * 8)
-                        : make_uint4(0u, 0u, 0u, 0u);
-    }
-  };
-  auto store_x = [&](int buf) {
-#pragma unroll
-    for (int p = 0; p < 2 * MT; ++p)
-      *reinterpret_cast<uint4*>(&lds[buf][(p * 8 + xr) * XS + xu * 16]) = xnxt[p];
-  };
-  auto load_w = [&](uint4 (&dst)[NW][KSTEPS], int c) {
-#pragma unroll
-    for (int s = 0; s < KSTEPS; ++s) {
-      dst[0][s] = *reinterpret_cast<const uint4*>(w0 + (size_t)c * KC + s * 32);
-      if (GATEUP) dst[NW - 1][s] = *reinterpret_cast<const uint4*>(w1 + (size_t)c * KC + s * 32);
-    }
-  };
+#define SP_LOAD_X(C)                                                                                   \
+  _Pragma("unroll") for (int p = 0; p < PASSES; ++p) {                                                  \
+    const int m = min(m_base + p * RPP + xr, m_last);                                                   \
+    xnxt[p] = *reinterpret_cast<const u32x4_t*>(X + (size_t)m * K + (size_t)(C)*KC + xu * 8);           \
+  }
+#define SP_STORE_X(BUF)                                                                                 \
+  _Pragma("unroll") for (int p = 0; p < PASSES; ++p)                                                    \
+      *reinterpret_cast<u32x4_t*>(&lds[BUF][(p * RPP + xr) * XS + xu * 16]) = xnxt[p];
+#define SP_LOAD_W(B, C)                                                                                 \
+  _Pragma("unroll") for (int s = 0; s < KSTEPS; ++s) {                                                  \
+    wb[B][0][s] = *reinterpret_cast<const u32x4_t*>(w0 + SP_WOFF(C, s));                                \
+    if (GATEUP) wb[B][NW - 1][s] = *reinterpret_cast<const u32x4_t*>(w1 + SP_WOFF(C, s));               \
+  }
+  // One chunk C out of weight buffer B.  The activation panel of chunk C+1 was loaded to
+  // registers one chunk earlier and goes to the other LDS buffer first; then the loads of
+  // panel C+2 and of weight chunk C+PF are issued, and chunk C is multiplied.  A wave only
+  // ever waits for loads that have had a whole chunk of math to arrive, and never for the
+  // youngest weight loads (waits retire loads in issue order).
+#define SP_CHUNK(B, C)                                                                                  \
+  {                                                                                                     \
+    const int c_ = (C);                                                                                 \
+    const int buf = (c_ - c_begin) & 1;                                                                 \
+    if (c_ + 1 < c_end) { SP_STORE_X(buf ^ 1) }                                                         \
+    if (c_ + 2 < c_end) { SP_LOAD_X(c_ + 2) }                                                           \
+    if (c_ + PF < c_end) { SP_LOAD_W((B + PF) % NB, c_ + PF) }                                          \
+    _Pragma("unroll") for (int s = 0; s < KSTEPS; ++s) {                                                \
+      _Pragma("unroll") for (int mt = 0; mt < MT; ++mt) {                                               \
+        const bf16x8_t b = *reinterpret_cast<const bf16x8_t*>(                                          \
+            &lds[buf][(mt * 16 + r) * XS + ((kh * KSTEPS + s) * 32 + kg * 8) * 2]);                     \
+        _Pragma("unroll") for (int a = 0; a < NW; ++a) acc[a][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16( \
+            *reinterpret_cast<const bf16x8_t*>(&wb[B][a][s]), b, acc[a][mt], 0, 0, 0);                  \
+      }                                                                                                 \
+    }                                                                                                   \
+    __syncthreads();                                                                                    \
+  }
 
   if (c_begin < c_end) {
-    load_x(c_begin);
-    load_w(wcur, c_begin);
-    store_x(0);
+    SP_LOAD_X(c_begin)
+    SP_LOAD_W(0, c_begin)
+    SP_STORE_X(0)
+    if (c_begin + 1 < c_end) {
+      SP_LOAD_X(c_begin + 1)
+      if (PF >= 2) { SP_LOAD_W(1 % NB, c_begin + 1) }
+    }
   }
   __syncthreads();
-  for (int c = c_begin; c < c_end; ++c) {
-    const int buf = (c - c_begin) & 1;
-    const bool more = c + 1 < c_end;
-    if (more) { load_x(c + 1); load_w(wnxt, c + 1); }   // X first: its wait must not drain the weight loads
-#pragma unroll
-    for (int s = 0; s < KSTEPS; ++s) {
-#pragma unroll
-      for (int mt = 0; mt < MT; ++mt) {
-        const bf16x8_t b = *reinterpret_cast<const bf16x8_t*>(
-            &lds[buf][(mt * 16 + r) * XS + ((kh * KSTEPS + s) * 32 + kg * 8) * 2]);
-#pragma unroll
-        for (int a = 0; a < NW; ++a)
-          acc[a][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(*reinterpret_cast<const bf16x8_t*>(&wcur[a][s]), b,
-                                                               acc[a][mt], 0, 0, 0);
-      }
-    }
-    if (more) store_x(buf ^ 1);
-    __syncthreads();
-    if (more) {
-#pragma unroll
-      for (int a = 0; a < NW; ++a)
-#pragma unroll
-        for (int s = 0; s < KSTEPS; ++s) wcur[a][s] = wnxt[a][s];
-    }
+  for (int c = c_begin; c < c_end; c += NB) {
+    SP_CHUNK(0, c)
+    if (NB >= 2 && c + 1 < c_end) SP_CHUNK(1 % NB, c + 1)
+    if (NB >= 3 && c + 2 < c_end) SP_CHUNK(2 % NB, c + 2)
   }
+#undef SP_CHUNK
+#undef SP_LOAD_W
+#undef SP_STORE_X
+#undef SP_LOAD_X
+#undef SP_WOFF
 
   if (NKH == 2) {       // fold the two k-halves of a column group together through LDS
     float* red = reinterpret_cast<float*>(&lds[0][0]);
@@ -139,40 +168,47 @@ k_gemm_bf16(const bf16_t* __restrict__ X, const bf16_t* __restrict__ W, float* _
 }
 
 // ---- launchers -------------------------------------------------------------------
-template <int NCG, bool GATEUP>
+template <int NCG, bool GATEUP, int KCV>
 static hipError_t launch_mt(int MT, dim3 grid, hipStream_t st, const bf16_t* X, const bf16_t* W, float* out,
                             bf16_t* act, int M, int N, int K, int chunks, int S) {
+#define SP_GO(MTV)                                                                                       \
+  hipLaunchKernelGGL((k_gemm_bf16<MTV, NCG, GATEUP, KCV, SP_GEMM_PF>), grid, dim3(256), 0, st, X, W, out, \
+                     act, M, N, K, chunks, S)
   switch (MT) {
-    case 1: hipLaunchKernelGGL((k_gemm_bf16<1, NCG, GATEUP>), grid, dim3(256), 0, st, X, W, out, act, M, N, K, chunks, S); break;
-    case 2: hipLaunchKernelGGL((k_gemm_bf16<2, NCG, GATEUP>), grid, dim3(256), 0, st, X, W, out, act, M, N, K, chunks, S); break;
-    case 3: hipLaunchKernelGGL((k_gemm_bf16<3, NCG, GATEUP>), grid, dim3(256), 0, st, X, W, out, act, M, N, K, chunks, S); break;
-    default: hipLaunchKernelGGL((k_gemm_bf16<4, NCG, GATEUP>), grid, dim3(256), 0, st, X, W, out, act, M, N, K, chunks, S); break;
+    case 1: SP_GO(1); break;
+    case 2: SP_GO(2); break;
+    case 3: SP_GO(3); break;
+    default: SP_GO(4); break;
   }
+#undef SP_GO
   return hipGetLastError();
 }
 
 hipError_t sp_launch_gemm_bf16(const bf16_t* X, const bf16_t* W, float* out, int M, int N, int K, int max_split,
                                size_t part_capacity_floats, int* S_out, hipStream_t st) {
-  if (M < 1 || N % 64 || K % KC) return hipErrorInvalidValue;
-  const int chunks = K / KC;
+  constexpr int TILE = 16 * SP_GEMM_NCG_PLAIN;
+  if (M < 1 || N % TILE || K % SP_GEMM_KC_PLAIN) return hipErrorInvalidValue;
+  const int chunks = K / SP_GEMM_KC_PLAIN;
   const int mblocks = (M + 63) / 64;
   const int MT = M >= 64 ? 4 : (M + 15) / 16;
-  const int tiles = N / 64;
+  const int tiles = N / TILE;
   // enough workgroups to keep every CU streaming, within the partial-sum buffer
-  int S = (768 + tiles * mblocks - 1) / (tiles * mblocks);
+  int S = (SP_GEMM_TARGET_WGS + tiles * mblocks - 1) / (tiles * mblocks);
   if (S > max_split) S = max_split;
   if (S > chunks) S = chunks;
   while (S > 1 && (size_t)S * M * N > part_capacity_floats) --S;
   if (S < 1) S = 1;
   if ((size_t)S * M * N > part_capacity_floats) return hipErrorInvalidValue;
   *S_out = S;
-  return launch_mt<4, false>(MT, dim3(tiles, S, mblocks), st, X, W, out, nullptr, M, N, K, chunks, S);
+  return launch_mt<SP_GEMM_NCG_PLAIN, false, SP_GEMM_KC_PLAIN>(MT, dim3(tiles, S, mblocks), st, X, W, out, nullptr, M, N, K, chunks, S);
 }
 
 hipError_t sp_launch_gemm_gateup_bf16(const bf16_t* X, const bf16_t* W, bf16_t* act, int M, int F, int K,
                                       hipStream_t st) {
-  if (M < 1 || F % 32 || K % KC) return hipErrorInvalidValue;
+  constexpr int TILE = 16 * SP_GEMM_NCG_GATEUP;
+  if (M < 1 || F % TILE || K % SP_GEMM_KC_GATEUP) return hipErrorInvalidValue;
   const int mblocks = (M + 63) / 64;
   const int MT = M >= 64 ? 4 : (M + 15) / 16;
-  return launch_mt<2, true>(MT, dim3(F / 32, 1, mblocks), st, X, W, nullptr, act, M, F, K, K / KC, 1);
+  return launch_mt<SP_GEMM_NCG_GATEUP, true, SP_GEMM_KC_GATEUP>(MT, dim3(F / TILE, 1, mblocks), st, X, W, nullptr, act, M, F, K,
+                                             K / SP_GEMM_KC_GATEUP, 1);
 }

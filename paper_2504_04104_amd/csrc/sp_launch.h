@@ -56,18 +56,23 @@ hipError_t sp_launch_attn_simple(int dtype, const void* q, const RowInfo* rows, 
 
 struct AttnPlan {          // host-made split of a forward call's attention work
   int n_seg;
-  int chunk_len;           // slots per chunk (multiple of 32)
+  int chunk_len;           // slots per chunk (multiple of 256: eight waves x 32-slot tiles)
   int qt;                  // 16-row query tiles per wave: 1 or 2
-  int units_total;         // partial-result units: sum over segments of chunks * rows * n_q
+  int units_total;         // partial-result units: sum over split segments of chunks * rows * n_q
   int total_items;         // sum over segments of q_blocks * chunks
+  int any_split;           // some segment has more than one chunk: the merge kernel must run
   int seg_item0[SP_BATCH + 1];   // first work item of each segment
   int seg_chunks[SP_BATCH];
   int seg_qblocks[SP_BATCH];
   int seg_unit0[SP_BATCH];
-  int seg_row0[SP_BATCH];
+  int seg_row0[SP_BATCH];  // first row of the call that belongs to the segment
   int seg_rows[SP_BATCH];
-  int seg_P[SP_BATCH];     // host mirror of the prefix length (sizes the split only)
+  int seg_req[SP_BATCH];
+  int seg_first[SP_BATCH]; // first node of the segment
+  int seg_P[SP_BATCH];     // host mirror of prefix length and live nodes
+  int seg_T[SP_BATCH];
+  long long seg_base[SP_BATCH];
 };
-hipError_t sp_launch_attn_bf16(const bf16_t* q, const RowInfo* rows, const ReqTables* tables, KvGeom g, int layer,
-                               const AttnPlan& plan, float* part /*workspace*/, bf16_t* out, int M, int n_q,
-                               int n_kv, int d_head, hipStream_t st);
+hipError_t sp_launch_attn_bf16(const bf16_t* q, const ReqTables* tables, KvGeom g, int layer, const AttnPlan& plan,
+                               float* part /*workspace*/, bf16_t* out, int M, int n_q, int n_kv, int d_head,
+                               hipStream_t st);

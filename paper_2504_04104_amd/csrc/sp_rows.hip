@@ -37,7 +37,7 @@ __global__ void k_load_rows(const T* x, float* h, size_t n) {
     h[i] = Elt<T>::ld(x + i);
 }
 
-__device__ __forceinline__ float block_sum_256(float v, float* s_red) {
+__device__ __forceinline__ float block_sum(float v, float* s_red) {
   v = wave_sum(v);
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   if (lane == 0) s_red[wave] = v;
@@ -49,72 +49,72 @@ __device__ __forceinline__ float block_sum_256(float v, float* s_red) {
   return tot;
 }
 
-// One workgroup per row: h[row] += sum_s part[s][row]; xn[row] = h * rsqrt(mean(h^2)+eps) * gain.
+// One workgroup (1024 threads) per row, four columns per thread and pass:
+// h[row] += sum_s part[s][row]; xn[row] = h * rsqrt(mean(h^2)+eps) * gain.
 template <typename T>
-__global__ void __launch_bounds__(256) k_add_norm(float* h, const float* part, int S, size_t part_stride,
-                                                   const T* gain, T* xn, int d, float eps) {
-  __shared__ float s_red[4];
+__global__ void __launch_bounds__(1024) k_add_norm(float* h, const float* part, int S, size_t part_stride,
+                                                    const T* gain, T* xn, int d, float eps) {
+  __shared__ float s_red[16];
   const int row = blockIdx.x;
   float* hr = h + (size_t)row * d;
   float ss = 0.f;
-  for (int c = threadIdx.x; c < d; c += blockDim.x) {
-    float v = hr[c];
+  for (int c = threadIdx.x * 4; c < d; c += blockDim.x * 4) {
+    f32x4_t v = *reinterpret_cast<const f32x4_t*>(hr + c);
     if (part) {
-      float a = 0.f;
-      for (int s = 0; s < S; ++s) a += part[(size_t)s * part_stride + (size_t)row * d + c];
+      f32x4_t a = {0.f, 0.f, 0.f, 0.f};
+      for (int s = 0; s < S; ++s)
+        a += *reinterpret_cast<const f32x4_t*>(part + (size_t)s * part_stride + (size_t)row * d + c);
       v += a;
-      hr[c] = v;
+      *reinterpret_cast<f32x4_t*>(hr + c) = v;
     }
-    ss += v * v;
+    ss += v[0] * v[0] + v[1] * v[1] + v[2] * v[2] + v[3] * v[3];
   }
-  const float tot = block_sum_256(ss, s_red);
+  const float tot = block_sum(ss, s_red);
   const float scale = rsqrtf(tot / (float)d + eps);
-  for (int c = threadIdx.x; c < d; c += blockDim.x)
-    Elt<T>::st(xn + (size_t)row * d + c, hr[c] * scale * Elt<T>::ld(gain + c));
+  for (int c = threadIdx.x * 4; c < d; c += blockDim.x * 4) {
+    const f32x4_t v = *reinterpret_cast<const f32x4_t*>(hr + c);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) Elt<T>::st(xn + (size_t)row * d + c + i, v[i] * scale * Elt<T>::ld(gain + c + i));
+  }
 }
 
-// One workgroup per row.  Columns of the projection: n_q query heads, n_kv key
-// heads, n_kv value heads.  Half-split rotary pairing: t with t + d_head/2.
+// One workgroup per (row, head) over the projection's columns: n_q query heads, n_kv key
+// heads, n_kv value heads.  Query and key heads are rotated (half-split pairing: t with
+// t + d_head/2); value heads are copied.  Keys and values go to the node's cache slot.
 template <typename T>
-__global__ void __launch_bounds__(256) k_rope_kv(const float* part, int S, size_t part_stride, const RowInfo* rows,
-                                                  const float* cs, T* qbuf, KvGeom g, int layer, int n_q, int n_kv,
-                                                  int d_head) {
-  const int row = blockIdx.x;
+__global__ void __launch_bounds__(64) k_rope_kv(const float* part, int S, size_t part_stride, const RowInfo* rows,
+                                                 const float* cs, T* qbuf, KvGeom g, int layer, int n_q, int n_kv,
+                                                 int d_head) {
+  const int row = blockIdx.x, head = blockIdx.y;
   const int half = d_head >> 1;
   const int N = (n_q + 2 * n_kv) * d_head;
   const RowInfo ri = rows[row];
-  const float* c = cs + (size_t)row * d_head;
   const size_t slot = (size_t)(ri.base + ri.P + ri.node);
-  const float* pr = part + (size_t)row * N;
-  // rotated heads: q then k
-  const int n_rot = (n_q + n_kv) * half;
-  for (int i = threadIdx.x; i < n_rot; i += blockDim.x) {
-    const int head = i / half, t = i - head * half;
-    float a = 0.f, bb = 0.f;
-    for (int s = 0; s < S; ++s) {
-      a += pr[(size_t)s * part_stride + head * d_head + t];
-      bb += pr[(size_t)s * part_stride + head * d_head + half + t];
+  const float* pr = part + (size_t)row * N + (size_t)head * d_head;
+  if (head < n_q + n_kv) {
+    const float* c = cs + (size_t)row * d_head;
+    T* dst = head < n_q
+                 ? qbuf + ((size_t)row * n_q + head) * d_head
+                 : reinterpret_cast<T*>(g.kv + ((size_t)(layer * 2 + 0) * n_kv + (head - n_q)) * g.plane_bytes +
+                                        slot * g.row_bytes);
+    for (int t = threadIdx.x; t < half; t += blockDim.x) {
+      float a = 0.f, bb = 0.f;
+      for (int s = 0; s < S; ++s) {
+        a += pr[(size_t)s * part_stride + t];
+        bb += pr[(size_t)s * part_stride + half + t];
+      }
+      const float co = c[t], si = c[half + t];
+      Elt<T>::st(dst + t, a * co - bb * si);
+      Elt<T>::st(dst + half + t, bb * co + a * si);
     }
-    const float co = c[t], si = c[half + t];
-    const float ra = a * co - bb * si, rb = bb * co + a * si;
-    if (head < n_q) {
-      T* q = qbuf + (size_t)row * n_q * d_head + (size_t)head * d_head;
-      Elt<T>::st(q + t, ra);
-      Elt<T>::st(q + half + t, rb);
-    } else {
-      const int kh = head - n_q;
-      T* k = reinterpret_cast<T*>(g.kv + ((size_t)(layer * 2 + 0) * n_kv + kh) * g.plane_bytes + slot * g.row_bytes);
-      Elt<T>::st(k + t, ra);
-      Elt<T>::st(k + half + t, rb);
+  } else {
+    T* dst = reinterpret_cast<T*>(g.kv + ((size_t)(layer * 2 + 1) * n_kv + (head - n_q - n_kv)) * g.plane_bytes +
+                                  slot * g.row_bytes);
+    for (int t = threadIdx.x; t < d_head; t += blockDim.x) {
+      float a = 0.f;
+      for (int s = 0; s < S; ++s) a += pr[(size_t)s * part_stride + t];
+      Elt<T>::st(dst + t, a);
     }
-  }
-  const int n_v = n_kv * d_head;
-  for (int i = threadIdx.x; i < n_v; i += blockDim.x) {
-    const int kh = i / d_head, t = i - kh * d_head;
-    float a = 0.f;
-    for (int s = 0; s < S; ++s) a += pr[(size_t)s * part_stride + (n_q + n_kv) * d_head + i];
-    T* v = reinterpret_cast<T*>(g.kv + ((size_t)(layer * 2 + 1) * n_kv + kh) * g.plane_bytes + slot * g.row_bytes);
-    Elt<T>::st(v + t, a);
   }
 }
 
@@ -161,10 +161,10 @@ hipError_t sp_launch_load_rows(int dtype, const void* x, float* h, size_t n, hip
 hipError_t sp_launch_add_norm(int dtype, float* h, const float* part, int S, size_t part_stride, const void* gain,
                               void* xn, int M, int d, float eps, hipStream_t st) {
   if (dtype == 0)
-    hipLaunchKernelGGL(k_add_norm<float>, dim3(M), dim3(256), 0, st, h, part, S, part_stride, (const float*)gain,
+    hipLaunchKernelGGL(k_add_norm<float>, dim3(M), dim3(1024), 0, st, h, part, S, part_stride, (const float*)gain,
                        (float*)xn, d, eps);
   else
-    hipLaunchKernelGGL(k_add_norm<bf16_t>, dim3(M), dim3(256), 0, st, h, part, S, part_stride, (const bf16_t*)gain,
+    hipLaunchKernelGGL(k_add_norm<bf16_t>, dim3(M), dim3(1024), 0, st, h, part, S, part_stride, (const bf16_t*)gain,
                        (bf16_t*)xn, d, eps);
   return hipGetLastError();
 }
@@ -173,10 +173,10 @@ hipError_t sp_launch_rope_kv(int dtype, const float* part, int S, size_t part_st
                              const float* cs, void* qbuf, KvGeom g, int layer, int M, int n_q, int n_kv, int d_head,
                              hipStream_t st) {
   if (dtype == 0)
-    hipLaunchKernelGGL(k_rope_kv<float>, dim3(M), dim3(256), 0, st, part, S, part_stride, rows, cs, (float*)qbuf, g,
+    hipLaunchKernelGGL(k_rope_kv<float>, dim3(M, n_q + 2 * n_kv), dim3(64), 0, st, part, S, part_stride, rows, cs, (float*)qbuf, g,
                        layer, n_q, n_kv, d_head);
   else
-    hipLaunchKernelGGL(k_rope_kv<bf16_t>, dim3(M), dim3(256), 0, st, part, S, part_stride, rows, cs, (bf16_t*)qbuf,
+    hipLaunchKernelGGL(k_rope_kv<bf16_t>, dim3(M, n_q + 2 * n_kv), dim3(64), 0, st, part, S, part_stride, rows, cs, (bf16_t*)qbuf,
                        g, layer, n_q, n_kv, d_head);
   return hipGetLastError();
 }

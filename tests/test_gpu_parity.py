@@ -236,3 +236,22 @@ def test_error_codes():
     assert g.tree_insert(0, [-1, -1]) == 0
     torch.cuda.synchronize()
     pair.close()
+
+
+def test_c2_full_size_in_bench_configuration():
+    """Config 2 at full size, launched exactly as bench.py does (one request, prefix 2048, the
+    64-node tree, accept + compact): every output element against the oracle."""
+    w = wl.CONFIGS["C2"]
+    say("C2 full size")
+    pair = Pair(w.shape, w.seed, {0: w.prefix_len})
+    par = wl.tree_branching(w.seed, w.n_nodes, w.max_children, w.max_levels)
+    x = wl.hidden_rows(w.shape, w.seed, ("x",), w.n_nodes)
+    pair.insert(0, par)
+    y, ref = pair.forward([0], [0], [w.n_nodes], x)
+    e = rel_err(y, ref)
+    say("C2 rel err", e)
+    assert e <= TOL["bf16"]
+    pair.check_kv(0, TOL["bf16"])
+    roots = [i for i, p in enumerate(par) if p < 0]
+    pair.prune(0, sp.SP_ACCEPT, roots[0], x_rows=y, row_nodes=list(range(w.n_nodes)))
+    pair.close()
