@@ -38,6 +38,8 @@ def main() -> int:
     ap.add_argument("--nodes", type=int, default=0, help="tree nodes per step (default: the workload's)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--kernels", action="store_true", help="also time every kernel kind (extra passes)")
+    ap.add_argument("--unpacked", action="store_true",
+                    help="keep the weights row-major instead of the load-time MFMA-fragment re-layout")
     ap.add_argument("--calib-copy", action="store_true",
                     help="first run three plain 1 GiB device copies (a known-size kernel that scales rocprofv3's "
                          "FETCH_SIZE / WRITE_SIZE counters)")
@@ -65,8 +67,12 @@ def main() -> int:
     with ThreadPoolExecutor(4) as ex:
         weights = list(ex.map(lambda l: wl.layer_weights(sh, w.seed, l), range(sh.n_layers)))
     layers = [sp.pack_layer_weights(x, sh.dtype, dev) for x in weights]
+    flags = 0
+    if not args.unpacked:
+        layers = sp.pack_weights(sh, layers, dev)      # load-time re-layout, outside the timed region
+        flags |= sp.SP_FLAG_PACKED_WEIGHTS
     cap = P + 256 + 64
-    stage = sp.Stage(sh, layers, kv_slots=cap, max_requests=1, max_batch_nodes=max(64, n))
+    stage = sp.Stage(sh, layers, kv_slots=cap, max_requests=1, max_batch_nodes=max(64, n), flags=flags)
     prefix = [wl.prefix_kv(sh, w.seed, l, P) for l in range(sh.n_layers)]
     for l, (k, v) in enumerate(prefix):
         sp.write_prefix(stage, l, 0, k, v)
@@ -105,6 +111,7 @@ def main() -> int:
     t1 = time.perf_counter()
     for _ in range(args.steps):
         step()
+    t_enq = time.perf_counter()
     torch.cuda.synchronize()
     t2 = time.perf_counter()
     n_launch, gu_ms = stage.profile_end()
@@ -172,8 +179,10 @@ def main() -> int:
         "config": {"workload": "%s: %d-layer stage d=%d heads=%d/%d d_head=%d ffn=%d, prefix %d, tree of %d nodes, "
                                "step = insert + forward + accept + compact" %
                                (args.workload, L, sh.d_model, sh.n_q_heads, sh.n_kv_heads, sh.d_head, sh.d_ff, P, n),
-                   "seed": w.seed, "tree_nodes": n, "prefix_len": P, "layers": L},
+                   "seed": w.seed, "tree_nodes": n, "prefix_len": P, "layers": L,
+                   "weights_layout": "row-major" if args.unpacked else "mfma-fragment (sp_pack_weights)"},
         "step_latency_us": round(ms_per_step * 1e3, 1),
+        "host_enqueue_us_per_step": round((t_enq - t1) * 1e6 / args.steps, 1),
         "step_hbm_floor_frac": round(step_frac, 4),
         "roofline": roofline,
         "cpu_baseline": cpu,

@@ -74,6 +74,7 @@ typedef enum sp_prune_mode { SP_ACCEPT = 0, SP_DROP = 1 } sp_prune_mode;
 
 /* sp_config.flags */
 #define SP_FLAG_SIMPLE_KERNELS 1u   /* use the plain (non-MFMA) kernels for every step */
+#define SP_FLAG_PACKED_WEIGHTS 2u   /* wqkv, wo, wgu, wd were re-laid by sp_pack_weights() (bf16 MFMA path only) */
 
 typedef struct sp_config {
   int32_t n_layers;
@@ -132,6 +133,18 @@ typedef struct sp_tree_view {
 
 /* Buffer sizes a stage of this config needs.  Pure host arithmetic. */
 int sp_stage_query_sizes(const sp_config* cfg, sp_sizes* out);
+
+/* Load-time re-layout of one layer's four projection matrices (bf16) into the order the
+ * matrix-core kernels read them in: per strip of 16 output rows and per step of 32 inputs,
+ * one contiguous 1 KB block holding, for lane l of a wave, the 8 values
+ * W[strip*16 + l%16][step*32 + (l/16)*8 .. +8].  It changes no value and no result, only
+ * how many bytes each wave load fetches contiguously.  `in` and `out` hold device pointers;
+ * `out` buffers are caller-allocated, of the same sizes, and distinct from `in`.  norm1 and
+ * norm2 are not touched (pass the originals to sp_stage_create).  Create the stage with
+ * SP_FLAG_PACKED_WEIGHTS to use the result.  Errors: SP_E_UNSUPPORTED unless dtype is bf16
+ * and d_model, d_ff are multiples of 32. */
+int sp_pack_weights(const sp_config* cfg, const sp_layer_weights* in, const sp_layer_weights* out,
+                    sp_stream stream);
 
 /* Builds a stage.  `layers` is a host array of n_layers entries holding device
  * pointers.  Buffers must be at least as large as sp_stage_query_sizes() says and

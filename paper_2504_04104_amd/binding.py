@@ -20,6 +20,7 @@ SP_MAX_BATCH_REQ = 64
 SP_F32, SP_BF16 = 0, 1
 SP_ACCEPT, SP_DROP = 0, 1
 SP_FLAG_SIMPLE_KERNELS = 1
+SP_FLAG_PACKED_WEIGHTS = 2
 
 # sp_kernel_kind
 K_GEMM_QKV, K_GEMM_O, K_GEMM_GATEUP, K_GEMM_DOWN = 1, 2, 3, 4
@@ -84,6 +85,7 @@ def load_library(path: Optional[str] = None) -> C.CDLL:
         "sp_stage_query_sizes": [C.POINTER(sp_config), C.POINTER(sp_sizes)],
         "sp_stage_create": [C.POINTER(sp_config), C.POINTER(sp_layer_weights), C.POINTER(sp_buffers), vp,
                             C.POINTER(vp)],
+        "sp_pack_weights": [C.POINTER(sp_config), C.POINTER(sp_layer_weights), C.POINTER(sp_layer_weights), vp],
         "sp_request_init": [vp, C.c_int32, C.c_int64, C.c_int32, C.c_int32, vp],
         "sp_tree_insert": [vp, C.c_int32, C.c_int32, i32p, i32p, f32p, i32p, vp],
         "sp_stage_forward": [vp, C.c_int32, i32p, i32p, i32p, vp, vp, vp],
@@ -275,6 +277,31 @@ class Stage:
         n, ms = C.c_int32(), C.c_float()
         _check(self.lib.sp_profile_end(self.handle, C.byref(n), C.byref(ms)), "sp_profile_end")
         return n.value, ms.value
+
+
+def pack_weights(shape, layers: List[Dict[str, "object"]], device: str = "cuda:0"):
+    """sp_pack_weights on every layer: returns new layer dicts whose four projection matrices are in
+    MFMA fragment order (create the Stage with SP_FLAG_PACKED_WEIGHTS).  The inputs can be dropped."""
+    import torch
+    lib = load_library()
+    cfg = sp_config(shape.n_layers, shape.d_model, shape.n_q_heads, shape.n_kv_heads, shape.d_head, shape.d_ff,
+                    shape.rms_eps, shape.rope_theta, SP_BF16, 1, SP_MAX_TREE_NODES, 1, 1, 0)
+    stream = C.c_void_p(torch.cuda.current_stream(torch.device(device)).cuda_stream)
+    out = []
+    for w in layers:
+        o = dict(w)
+        a, b = sp_layer_weights(), sp_layer_weights()
+        for name in ("wqkv", "wo", "wgu", "wd"):
+            o[name] = torch.empty_like(w[name])
+            setattr(a, name, w[name].data_ptr())
+            setattr(b, name, o[name].data_ptr())
+        for name in ("norm1", "norm2"):
+            setattr(a, name, w[name].data_ptr())
+            setattr(b, name, w[name].data_ptr())
+        _check(lib.sp_pack_weights(C.byref(cfg), C.byref(a), C.byref(b), stream), "sp_pack_weights")
+        out.append(o)
+    torch.cuda.synchronize()
+    return out
 
 
 # ---- data preparation helpers (layout only) ---------------------------------------------

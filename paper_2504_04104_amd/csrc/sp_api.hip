@@ -103,6 +103,8 @@ struct sp_stage {
   KvGeom geom;
   std::vector<HostReq> reqs;
   bool fast = false;           // bf16 MFMA kernels in use
+  bool packed = false;         // weights are in MFMA fragment order
+  int n_cu = 256;              // compute units of the device
   int last_hip = 0;
   // profiling
   int prof_kind = 0, prof_max = 0, prof_n = 0;
@@ -240,6 +242,14 @@ int sp_stage_create(const sp_config* cfg, const sp_layer_weights* layers, const 
   s->fast = cfg->dtype == SP_BF16 && !(cfg->flags & SP_FLAG_SIMPLE_KERNELS) && cfg->d_head == 128 &&
             cfg->d_model % 256 == 0 && cfg->d_ff % 256 == 0 &&
             (cfg->n_q_heads * cfg->d_head) % 256 == 0;
+  {
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) == hipSuccess &&
+        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && cus > 0)
+      s->n_cu = cus;
+  }
+  s->packed = (cfg->flags & SP_FLAG_PACKED_WEIGHTS) != 0;
+  if (s->packed && !s->fast) { delete s; return SP_E_UNSUPPORTED; }
   hipError_t e = sp_launch_tables_clear(s->d_meta, s->d_tables, cfg->max_requests, (hipStream_t)stream);
   if (e != hipSuccess) { delete s; return SP_E_HIP; }
   *out = s;
@@ -250,6 +260,22 @@ void sp_stage_destroy(sp_stage* stage) {
   if (!stage) return;
   for (hipEvent_t ev : stage->prof_ev) (void)hipEventDestroy(ev);
   delete stage;
+}
+
+int sp_pack_weights(const sp_config* cfg, const sp_layer_weights* in, const sp_layer_weights* out, sp_stream stream) {
+  int rc = check_config(cfg);
+  if (rc != SP_OK) return rc;
+  if (!in || !out) return SP_E_INVALID;
+  if (cfg->dtype != SP_BF16 || cfg->d_model % 32 || cfg->d_ff % 32 || cfg->d_head % 16) return SP_E_UNSUPPORTED;
+  const int dq = cfg->n_q_heads * cfg->d_head, nqkv = (cfg->n_q_heads + 2 * cfg->n_kv_heads) * cfg->d_head;
+  hipStream_t st = (hipStream_t)stream;
+  if (!in->wqkv || !in->wo || !in->wgu || !in->wd || !out->wqkv || !out->wo || !out->wgu || !out->wd) return SP_E_INVALID;
+  if (sp_launch_pack_weights(in->wqkv, (void*)out->wqkv, nqkv, cfg->d_model, st) != hipSuccess ||
+      sp_launch_pack_weights(in->wo, (void*)out->wo, cfg->d_model, dq, st) != hipSuccess ||
+      sp_launch_pack_weights(in->wgu, (void*)out->wgu, 2 * cfg->d_ff, cfg->d_model, st) != hipSuccess ||
+      sp_launch_pack_weights(in->wd, (void*)out->wd, cfg->d_model, cfg->d_ff, st) != hipSuccess)
+    return SP_E_HIP;
+  return SP_OK;
 }
 
 int sp_request_init(sp_stage* s, int32_t req, int64_t slot_base, int32_t capacity, int32_t prefix_len,
@@ -355,14 +381,23 @@ int sp_stage_forward(sp_stage* s, int32_t n_req, const int32_t* req_ids, const i
     for (int i = 0; i < b.n_req; ++i) if (b.n[i] * g > maxq) maxq = b.n[i] * g;
     plan.qt = maxq <= 16 ? 1 : 2;
     const int qrows_per_block = 16 * plan.qt;
-    auto fill = [&](int chunk_len, size_t* units_out) {
+    // One workgroup per CU is the target.  If the query blocks alone give that many, every
+    // request keeps its whole cache range in one chunk (no partial results, no merge kernel);
+    // otherwise each range is cut into `want` chunks, but never below one 32-slot tile per
+    // wave, and fewer if the partial results would not fit the workspace.
+    auto fill = [&](int want, size_t* units_out) {
       size_t units = 0; int items = 0, split = 0;
       for (int i = 0; i < b.n_req; ++i) {
         const HostReq& r = s->reqs[b.req[i]];
         const int span = r.P + r.T;
-        const int chunks = (span + chunk_len - 1) / chunk_len;
+        int chunks = want;
+        const int max_chunks = (span + 255) / 256;
+        if (chunks > max_chunks) chunks = max_chunks;
+        if (chunks < 1) chunks = 1;
+        const int clen = ((span + chunks - 1) / chunks + 31) / 32 * 32;
+        chunks = (span + clen - 1) / clen;
         const int qblocks = (b.n[i] * g + qrows_per_block - 1) / qrows_per_block;
-        plan.seg_item0[i] = items; plan.seg_chunks[i] = chunks; plan.seg_qblocks[i] = qblocks;
+        plan.seg_item0[i] = items; plan.seg_chunks[i] = chunks; plan.seg_clen[i] = clen; plan.seg_qblocks[i] = qblocks;
         plan.seg_row0[i] = b.row0[i]; plan.seg_rows[i] = b.n[i]; plan.seg_req[i] = b.req[i];
         plan.seg_first[i] = b.first[i]; plan.seg_P[i] = r.P; plan.seg_T[i] = r.T; plan.seg_base[i] = r.base;
         plan.seg_unit0[i] = (int)units;
@@ -372,22 +407,17 @@ int sp_stage_forward(sp_stage* s, int32_t n_req, const int32_t* req_ids, const i
       plan.seg_item0[b.n_req] = items;
       plan.total_items = items;
       plan.units_total = (int)units;
-      plan.chunk_len = chunk_len;
       plan.any_split = split;
       *units_out = units;
       return items;
     };
-    // Whole cache ranges if that already gives every CU a workgroup; otherwise halve the
-    // chunk (down to one 32-slot tile per wave) until it does.  Then grow it again if the
-    // partial results would not fit the workspace.
+    int base_blocks = 0;
+    for (int i = 0; i < b.n_req; ++i) base_blocks += (b.n[i] * g + qrows_per_block - 1) / qrows_per_block;
+    int want = s->n_cu / (base_blocks * nkv);
     size_t units = 0;
-    int chunk_len = 1 << 20;
-    while (fill(chunk_len, &units) * nkv < 256 && chunk_len > 256) chunk_len >>= 1;
-    while (units > w.attn_units) {
-      chunk_len <<= 1;
-      if (chunk_len > (1 << 20)) return SP_E_CAPACITY;
-      fill(chunk_len, &units);
-    }
+    fill(want, &units);
+    while (units > w.attn_units && want > 1) { want = (want + 1) / 2; fill(want, &units); }
+    if (units > w.attn_units) return SP_E_CAPACITY;
   }
 
   int S_prev = 0;                                   // split count of the previous layer's down projection
@@ -398,7 +428,7 @@ int sp_stage_forward(sp_stage* s, int32_t n_req, const int32_t* req_ids, const i
       SP_TRY(sp_launch_add_norm(dt, w.h, l ? w.part : nullptr, S_prev, strideD, L.norm1, w.xn, M, d, c.rms_eps, st)); }
     int S = 1;
     { ProfScope p(s, SP_K_GEMM_QKV, st);
-      if (s->fast) SP_TRY(sp_launch_gemm_bf16((const bf16_t*)w.xn, (const bf16_t*)L.wqkv, w.part, M, nqkv, d, 16, w.part_floats, &S, st));
+      if (s->fast) SP_TRY(sp_launch_gemm_bf16((const bf16_t*)w.xn, (const bf16_t*)L.wqkv, s->packed, w.part, M, nqkv, d, 16, w.part_floats, &S, st));
       else SP_TRY(sp_launch_gemm_simple(dt, w.xn, L.wqkv, w.part, M, nqkv, d, st)); }
     { ProfScope p(s, SP_K_ROPE_KV, st);
       SP_TRY(sp_launch_rope_kv(dt, w.part, S, strideQ, w.rows, w.cs, w.qbuf, s->geom, l, M, nq, nkv, dh, st)); }
@@ -412,20 +442,20 @@ int sp_stage_forward(sp_stage* s, int32_t n_req, const int32_t* req_ids, const i
     }
     { ProfScope p(s, SP_K_GEMM_O, st);
       S = 1;
-      if (s->fast) SP_TRY(sp_launch_gemm_bf16((const bf16_t*)w.attn, (const bf16_t*)L.wo, w.part, M, d, dq, 16, w.part_floats, &S, st));
+      if (s->fast) SP_TRY(sp_launch_gemm_bf16((const bf16_t*)w.attn, (const bf16_t*)L.wo, s->packed, w.part, M, d, dq, 16, w.part_floats, &S, st));
       else SP_TRY(sp_launch_gemm_simple(dt, w.attn, L.wo, w.part, M, d, dq, st)); }
     { ProfScope p(s, SP_K_NORM, st);
       SP_TRY(sp_launch_add_norm(dt, w.h, w.part, S, strideD, L.norm2, w.xn, M, d, c.rms_eps, st)); }
     { ProfScope p(s, SP_K_GEMM_GATEUP, st);
       if (s->fast) {
-        SP_TRY(sp_launch_gemm_gateup_bf16((const bf16_t*)w.xn, (const bf16_t*)L.wgu, (bf16_t*)w.act, M, F, d, st));
+        SP_TRY(sp_launch_gemm_gateup_bf16((const bf16_t*)w.xn, (const bf16_t*)L.wgu, s->packed, (bf16_t*)w.act, M, F, d, st));
       } else {
         SP_TRY(sp_launch_gemm_simple(dt, w.xn, L.wgu, w.part, M, 2 * F, d, st));
         SP_TRY(sp_launch_silu_mul(dt, w.part, w.act, M, F, st));
       } }
     { ProfScope p(s, SP_K_GEMM_DOWN, st);
       S = 1;
-      if (s->fast) SP_TRY(sp_launch_gemm_bf16((const bf16_t*)w.act, (const bf16_t*)L.wd, w.part, M, d, F, 16, w.part_floats, &S, st));
+      if (s->fast) SP_TRY(sp_launch_gemm_bf16((const bf16_t*)w.act, (const bf16_t*)L.wd, s->packed, w.part, M, d, F, 16, w.part_floats, &S, st));
       else SP_TRY(sp_launch_gemm_simple(dt, w.act, L.wd, w.part, M, d, F, st)); }
     S_prev = S;
   }

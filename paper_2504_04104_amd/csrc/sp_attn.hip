@@ -60,8 +60,8 @@ __global__ void __launch_bounds__(64 * AW) k_attn_bf16(AttnArgs a, AttnPlan plan
   const int nqrows = seg_rows * g;                 // query rows of this (request, KV head)
   const int P = plan.seg_P[seg], T = plan.seg_T[seg];
   const int span = P + T;
-  const int c0 = ch * plan.chunk_len;
-  const int c1 = min(c0 + plan.chunk_len, span);
+  const int c0 = ch * plan.seg_clen[seg];
+  const int c1 = min(c0 + plan.seg_clen[seg], span);
   // this wave's run of 32-slot tiles inside [c0, c1)
   const int ntiles = (c1 - c0 + 31) >> 5;
   const int w0 = c0 + 32 * ((wave * ntiles) / AW);

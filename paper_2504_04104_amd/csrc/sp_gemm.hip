@@ -31,7 +31,10 @@
 #define SP_GEMM_TARGET_WGS 768    // split K until the grid has about this many workgroups
 #endif
 
-template <int MT, int NCG, bool GATEUP, int KC, int PF>
+// PACKED: the weights were re-laid at load time (sp_pack_weights) into MFMA fragment order --
+// per strip of 16 rows, one contiguous 1 KB block per k-step of 32, lane-major -- so that every
+// wave load is one contiguous kilobyte instead of sixteen 64-byte pieces.
+template <int MT, int NCG, bool GATEUP, int KC, int PF, bool PACKED>
 __global__ void __launch_bounds__(256)
 k_gemm_bf16(const bf16_t* __restrict__ X, const bf16_t* __restrict__ W, float* __restrict__ out,
             bf16_t* __restrict__ act, int M, int N, int K, int chunks_total, int S) {
@@ -54,9 +57,11 @@ k_gemm_bf16(const bf16_t* __restrict__ X, const bf16_t* __restrict__ W, float* _
   const int c_begin = (int)(((long long)blockIdx.y * chunks_total) / S);
   const int c_end = (int)(((long long)(blockIdx.y + 1) * chunks_total) / S);
 
-  const bf16_t* w0 = W + (size_t)(n0 + r) * K + kg * 8 + kh * (KSTEPS * 32);
-  const bf16_t* w1 = W + (size_t)(N + n0 + r) * K + kg * 8 + kh * (KSTEPS * 32);   // up rows (GATEUP)
-#define SP_WOFF(C, s) ((size_t)(C)*KC + (s) * 32)
+  const bf16_t* w0 = PACKED ? W + ((size_t)(n0 / 16) * (K / 32) + kh * KSTEPS) * 512 + lane * 8
+                            : W + (size_t)(n0 + r) * K + kg * 8 + kh * (KSTEPS * 32);
+  const bf16_t* w1 = PACKED ? W + ((size_t)((N + n0) / 16) * (K / 32) + kh * KSTEPS) * 512 + lane * 8
+                            : W + (size_t)(N + n0 + r) * K + kg * 8 + kh * (KSTEPS * 32);   // up rows (GATEUP)
+#define SP_WOFF(C, s) (PACKED ? ((size_t)(C) * (KC / 32) + (s)) * 512 : (size_t)(C)*KC + (s) * 32)
   const int xu = tid % UPR, xr = tid / UPR;
   // rows past M are read from the last valid row and multiply into output rows that are never stored
   const int m_last = M - 1;
@@ -108,11 +113,9 @@ k_gemm_bf16(const bf16_t* __restrict__ X, const bf16_t* __restrict__ W, float* _
   if (c_begin < c_end) {
     SP_LOAD_X(c_begin)
     SP_LOAD_W(0, c_begin)
+    if (PF >= 2 && c_begin + 1 < c_end) { SP_LOAD_W(1 % NB, c_begin + 1) }
     SP_STORE_X(0)
-    if (c_begin + 1 < c_end) {
-      SP_LOAD_X(c_begin + 1)
-      if (PF >= 2) { SP_LOAD_W(1 % NB, c_begin + 1) }
-    }
+    if (c_begin + 1 < c_end) { SP_LOAD_X(c_begin + 1) }
   }
   __syncthreads();
   for (int c = c_begin; c < c_end; c += NB) {
@@ -151,15 +154,15 @@ k_gemm_bf16(const bf16_t* __restrict__ X, const bf16_t* __restrict__ W, float* _
     const int m = m_base + mt * 16 + r;
     if (m >= M) continue;
     if (GATEUP) {
-      uint16_t o[4];
+      float o[4];
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
         const float gte = acc[0][mt][i], up = acc[NW - 1][mt][i];
-        o[i] = f32_to_bf16(gte / (1.f + __expf(-gte)) * up);
+        o[i] = gte / (1.f + __expf(-gte)) * up;
       }
       uint2 pk;
-      pk.x = (uint32_t)o[0] | ((uint32_t)o[1] << 16);
-      pk.y = (uint32_t)o[2] | ((uint32_t)o[3] << 16);
+      pk.x = pack_bf16x2(o[0], o[1]);
+      pk.y = pack_bf16x2(o[2], o[3]);
       *reinterpret_cast<uint2*>(act + (size_t)m * N + ncol) = pk;
     } else {
       *reinterpret_cast<f32x4_t*>(out + ((size_t)blockIdx.y * M + m) * N + ncol) = acc[0][mt];
@@ -168,11 +171,11 @@ k_gemm_bf16(const bf16_t* __restrict__ X, const bf16_t* __restrict__ W, float* _
 }
 
 // ---- launchers -------------------------------------------------------------------
-template <int NCG, bool GATEUP, int KCV>
+template <int NCG, bool GATEUP, int KCV, bool PACKED>
 static hipError_t launch_mt(int MT, dim3 grid, hipStream_t st, const bf16_t* X, const bf16_t* W, float* out,
                             bf16_t* act, int M, int N, int K, int chunks, int S) {
 #define SP_GO(MTV)                                                                                       \
-  hipLaunchKernelGGL((k_gemm_bf16<MTV, NCG, GATEUP, KCV, SP_GEMM_PF>), grid, dim3(256), 0, st, X, W, out, \
+  hipLaunchKernelGGL((k_gemm_bf16<MTV, NCG, GATEUP, KCV, SP_GEMM_PF, PACKED>), grid, dim3(256), 0, st, X, W, out, \
                      act, M, N, K, chunks, S)
   switch (MT) {
     case 1: SP_GO(1); break;
@@ -184,8 +187,8 @@ static hipError_t launch_mt(int MT, dim3 grid, hipStream_t st, const bf16_t* X, 
   return hipGetLastError();
 }
 
-hipError_t sp_launch_gemm_bf16(const bf16_t* X, const bf16_t* W, float* out, int M, int N, int K, int max_split,
-                               size_t part_capacity_floats, int* S_out, hipStream_t st) {
+hipError_t sp_launch_gemm_bf16(const bf16_t* X, const bf16_t* W, bool packed, float* out, int M, int N, int K,
+                               int max_split, size_t part_capacity_floats, int* S_out, hipStream_t st) {
   constexpr int TILE = 16 * SP_GEMM_NCG_PLAIN;
   if (M < 1 || N % TILE || K % SP_GEMM_KC_PLAIN) return hipErrorInvalidValue;
   const int chunks = K / SP_GEMM_KC_PLAIN;
@@ -200,15 +203,41 @@ hipError_t sp_launch_gemm_bf16(const bf16_t* X, const bf16_t* W, float* out, int
   if (S < 1) S = 1;
   if ((size_t)S * M * N > part_capacity_floats) return hipErrorInvalidValue;
   *S_out = S;
-  return launch_mt<SP_GEMM_NCG_PLAIN, false, SP_GEMM_KC_PLAIN>(MT, dim3(tiles, S, mblocks), st, X, W, out, nullptr, M, N, K, chunks, S);
+  if (packed)
+    return launch_mt<SP_GEMM_NCG_PLAIN, false, SP_GEMM_KC_PLAIN, true>(MT, dim3(tiles, S, mblocks), st, X, W, out,
+                                                                       nullptr, M, N, K, chunks, S);
+  return launch_mt<SP_GEMM_NCG_PLAIN, false, SP_GEMM_KC_PLAIN, false>(MT, dim3(tiles, S, mblocks), st, X, W, out,
+                                                                      nullptr, M, N, K, chunks, S);
 }
 
-hipError_t sp_launch_gemm_gateup_bf16(const bf16_t* X, const bf16_t* W, bf16_t* act, int M, int F, int K,
-                                      hipStream_t st) {
+hipError_t sp_launch_gemm_gateup_bf16(const bf16_t* X, const bf16_t* W, bool packed, bf16_t* act, int M, int F,
+                                      int K, hipStream_t st) {
   constexpr int TILE = 16 * SP_GEMM_NCG_GATEUP;
   if (M < 1 || F % TILE || K % SP_GEMM_KC_GATEUP) return hipErrorInvalidValue;
   const int mblocks = (M + 63) / 64;
   const int MT = M >= 64 ? 4 : (M + 15) / 16;
-  return launch_mt<SP_GEMM_NCG_GATEUP, true, SP_GEMM_KC_GATEUP>(MT, dim3(F / TILE, 1, mblocks), st, X, W, nullptr, act, M, F, K,
-                                             K / SP_GEMM_KC_GATEUP, 1);
+  if (packed)
+    return launch_mt<SP_GEMM_NCG_GATEUP, true, SP_GEMM_KC_GATEUP, true>(MT, dim3(F / TILE, 1, mblocks), st, X, W,
+                                                                        nullptr, act, M, F, K, K / SP_GEMM_KC_GATEUP, 1);
+  return launch_mt<SP_GEMM_NCG_GATEUP, true, SP_GEMM_KC_GATEUP, false>(MT, dim3(F / TILE, 1, mblocks), st, X, W,
+                                                                       nullptr, act, M, F, K, K / SP_GEMM_KC_GATEUP, 1);
+}
+
+// Re-lays a [N][K] row-major bf16 matrix into MFMA fragment order: 16-byte unit u of the output
+// holds W[strip*16 + u%16][kstep*32 + ((u/16)%4)*8 .. +8] with u/64 = strip*(K/32) + kstep.
+__global__ void k_pack_weights(const u32x4_t* __restrict__ in, u32x4_t* __restrict__ out, int N, int K) {
+  const size_t units = (size_t)N * K / 8;
+  for (size_t u = (size_t)blockIdx.x * blockDim.x + threadIdx.x; u < units; u += (size_t)gridDim.x * blockDim.x) {
+    const size_t blk = u >> 6;
+    const int lane = (int)(u & 63);
+    const size_t strip = blk / (K / 32), ks = blk - strip * (K / 32);
+    const size_t n = strip * 16 + (lane & 15), k = ks * 32 + (lane >> 4) * 8;
+    out[u] = in[(n * K + k) / 8];
+  }
+}
+
+hipError_t sp_launch_pack_weights(const void* in, void* out, int N, int K, hipStream_t st) {
+  if (N % 16 || K % 32 || in == out) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(k_pack_weights, dim3(4096), dim3(256), 0, st, (const u32x4_t*)in, (u32x4_t*)out, N, K);
+  return hipGetLastError();
 }

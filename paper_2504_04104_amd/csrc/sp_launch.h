@@ -29,6 +29,7 @@ hipError_t sp_launch_prep_rows(const FwdBatch& b, const ReqMeta* meta, const Req
                                float* cs /*[rows][d_head]: cos then sin*/, int d_head, float theta,
                                hipStream_t st);
 hipError_t sp_launch_load_rows(int dtype, const void* x, float* h, size_t n, hipStream_t st);
+
 // h += sum_s part[s]; xn = rmsnorm(h) * gain   (part may be null)
 hipError_t sp_launch_add_norm(int dtype, float* h, const float* part, int S, size_t part_stride,
                               const void* gain, void* xn, int M, int d, float eps, hipStream_t st);
@@ -43,12 +44,15 @@ hipError_t sp_launch_finish(int dtype, const float* h, const float* part, int S,
 // ---- GEMM: out[s][m][n] (f32) = sum over the s-th K slice of X[m][k] * W[n][k] -----
 hipError_t sp_launch_gemm_simple(int dtype, const void* X, const void* W, float* out, int M, int N, int K,
                                  hipStream_t st);
-// bf16 MFMA kernels.  Returns the split count used in *S_out (partials [S][M][N]).
-hipError_t sp_launch_gemm_bf16(const bf16_t* X, const bf16_t* W, float* out, int M, int N, int K, int max_split,
-                               size_t part_capacity_floats, int* S_out, hipStream_t st);
+// bf16 MFMA kernels.  Returns the split count used in *S_out (partials [S][M][N]).  packed: the
+// weights are in MFMA fragment order (sp_launch_pack_weights).
+hipError_t sp_launch_gemm_bf16(const bf16_t* X, const bf16_t* W, bool packed, float* out, int M, int N, int K,
+                               int max_split, size_t part_capacity_floats, int* S_out, hipStream_t st);
 // act[m][f] = silu(X Wg^T) * (X Wu^T), W = [gate rows ; up rows]
-hipError_t sp_launch_gemm_gateup_bf16(const bf16_t* X, const bf16_t* W, bf16_t* act, int M, int F, int K,
-                                      hipStream_t st);
+hipError_t sp_launch_gemm_gateup_bf16(const bf16_t* X, const bf16_t* W, bool packed, bf16_t* act, int M, int F,
+                                      int K, hipStream_t st);
+// [N][K] row-major bf16 -> MFMA fragment order (N % 16 == 0, K % 32 == 0, out != in)
+hipError_t sp_launch_pack_weights(const void* in, void* out, int N, int K, hipStream_t st);
 
 // ---- tree attention -------------------------------------------------------------
 hipError_t sp_launch_attn_simple(int dtype, const void* q, const RowInfo* rows, const ReqTables* tables, KvGeom g,
@@ -56,13 +60,13 @@ hipError_t sp_launch_attn_simple(int dtype, const void* q, const RowInfo* rows, 
 
 struct AttnPlan {          // host-made split of a forward call's attention work
   int n_seg;
-  int chunk_len;           // slots per chunk (multiple of 256: eight waves x 32-slot tiles)
   int qt;                  // 16-row query tiles per wave: 1 or 2
   int units_total;         // partial-result units: sum over split segments of chunks * rows * n_q
   int total_items;         // sum over segments of q_blocks * chunks
   int any_split;           // some segment has more than one chunk: the merge kernel must run
   int seg_item0[SP_BATCH + 1];   // first work item of each segment
   int seg_chunks[SP_BATCH];
+  int seg_clen[SP_BATCH];  // slots per chunk of the segment (multiple of 32)
   int seg_qblocks[SP_BATCH];
   int seg_unit0[SP_BATCH];
   int seg_row0[SP_BATCH];  // first row of the call that belongs to the segment

@@ -34,6 +34,8 @@ class Pair:
         self.shape, self.seed = shape, seed
         self.weights = [wl.layer_weights(shape, seed, l) for l in range(shape.n_layers)]
         layers = [sp.pack_layer_weights(w, shape.dtype) for w in self.weights]
+        if flags & sp.SP_FLAG_PACKED_WEIGHTS:
+            layers = sp.pack_weights(shape, layers)
         n_req = max(prefixes) + 1
         self.base: Dict[int, int] = {}
         self.cap: Dict[int, int] = {}

@@ -48,7 +48,8 @@ def test_c1_tiny_fp32_forward_drop_compact():
     pair.close()
 
 
-@pytest.mark.parametrize("flags", [sp.SP_FLAG_SIMPLE_KERNELS, 0], ids=["simple", "mfma"])
+@pytest.mark.parametrize("flags", [sp.SP_FLAG_SIMPLE_KERNELS, 0, sp.SP_FLAG_PACKED_WEIGHTS],
+                         ids=["simple", "mfma", "mfma_packed"])
 @pytest.mark.parametrize("shape", [MINI_BF16, MINI_GQA4], ids=["g2", "g4"])
 def test_mini_bf16_forward(shape, flags):
     """Several attention tiles with a ragged tail (prefix 300), 37 nodes (ragged M), both kernel sets."""
@@ -84,7 +85,7 @@ def test_mini_f32_gqa_forward_in_pieces():
 def test_row_counts_across_tile_edges(n):
     """M below, at and above the 16-row MFMA tile and the 64-row block."""
     shape = MINI_BF16
-    pair = Pair(shape, 13, {0: 129}, max_batch_nodes=160)
+    pair = Pair(shape, 13, {0: 129}, max_batch_nodes=160, flags=sp.SP_FLAG_PACKED_WEIGHTS if n % 2 else 0)
     par = wl.tree_uniform_parents(13, n, 9, name=("t", n))
     x = wl.hidden_rows(shape, 13, ("r", n), n)
     pair.insert(0, par)
@@ -126,7 +127,7 @@ def test_streaming_mini():
     """Config 4 in miniature: per step insert 1-8 nodes, forward only those, prune, compact
     (cache and in-flight hidden rows); every step checked."""
     shape = MINI_BF16
-    pair = Pair(shape, 15, {0: 200}, tree_room=700)
+    pair = Pair(shape, 15, {0: 200}, tree_room=700, flags=sp.SP_FLAG_PACKED_WEIGHTS)
     steps = wl.streaming_schedule(15, 40, max_new=8, cap=256, p_accept=0.7)
     worst = 0.0
     for s, st in enumerate(steps):
@@ -243,7 +244,7 @@ def test_c2_full_size_in_bench_configuration():
     64-node tree, accept + compact): every output element against the oracle."""
     w = wl.CONFIGS["C2"]
     say("C2 full size")
-    pair = Pair(w.shape, w.seed, {0: w.prefix_len})
+    pair = Pair(w.shape, w.seed, {0: w.prefix_len}, flags=sp.SP_FLAG_PACKED_WEIGHTS)
     par = wl.tree_branching(w.seed, w.n_nodes, w.max_children, w.max_levels)
     x = wl.hidden_rows(w.shape, w.seed, ("x",), w.n_nodes)
     pair.insert(0, par)
