@@ -68,6 +68,34 @@ __global__ void __launch_bounds__(64 * AW) k_attn_bf16(AttnArgs a, AttnPlan plan
   const int w1 = min(c0 + 32 * (((wave + 1) * ntiles) / AW), c1);
   const int l15 = lane & 15, kg = lane >> 4;
 
+  const size_t base_b = (size_t)plan.seg_base[seg] * 256;
+  const char* kplane = a.g.kv + ((size_t)(a.layer * 2 + 0) * a.n_kv + kvh) * a.g.plane_bytes + base_b;
+  const char* vplane = a.g.kv + ((size_t)(a.layer * 2 + 1) * a.n_kv + kvh) * a.g.plane_bytes + base_b;
+
+  // Loads of one 32-slot tile: K as MFMA A fragments (row l15 of each 16-slot half, 16 B at
+  // d = s*32 + kg*8), V as plain 16-byte pieces (row i*4+kg, piece l15).  Slots past the
+  // request's data are read from slot 0 (always valid) and masked later.
+#define SP_LOAD_TILE(S0)                                                                           \
+  {                                                                                                \
+    _Pragma("unroll") for (int t2 = 0; t2 < 2; ++t2) {                                             \
+      int slot = (S0) + t2 * 16 + l15;                                                             \
+      slot = slot < span ? slot : 0;                                                               \
+      const char* kp = kplane + (size_t)slot * 256 + kg * 16;                                      \
+      _Pragma("unroll") for (int s = 0; s < 4; ++s)                                                \
+          kreg[t2][s] = *reinterpret_cast<const u32x4_t*>(kp + s * 64);                            \
+    }                                                                                              \
+    _Pragma("unroll") for (int i = 0; i < 8; ++i) {                                                \
+      int slot = (S0) + i * 4 + kg;                                                                \
+      slot = slot < span ? slot : 0;                                                               \
+      vreg[i] = *reinterpret_cast<const u32x4_t*>(vplane + (size_t)slot * 256 + l15 * 16);         \
+    }                                                                                              \
+  }
+
+  // the first tile's loads go out before anything else that has to wait
+  u32x4_t kreg[2][4], vreg[8];
+  char* vt = s_v + wave * VT_BYTES;
+  SP_LOAD_TILE(w0 < w1 ? w0 : span)
+
   // ---- query fragments and ancestor masks of this lane's query row per tile ------
   u32x4_t qf[QT][4];
   unsigned long long anc[QT][SP_W];
@@ -93,10 +121,6 @@ __global__ void __launch_bounds__(64 * AW) k_attn_bf16(AttnArgs a, AttnPlan plan
     }
   }
 
-  const size_t base_b = (size_t)plan.seg_base[seg] * 256;
-  const char* kplane = a.g.kv + ((size_t)(a.layer * 2 + 0) * a.n_kv + kvh) * a.g.plane_bytes + base_b;
-  const char* vplane = a.g.kv + ((size_t)(a.layer * 2 + 1) * a.n_kv + kvh) * a.g.plane_bytes + base_b;
-
   f32x4_t o[QT][8];
   float mrun[QT], lrun[QT];
 #pragma unroll
@@ -112,28 +136,6 @@ __global__ void __launch_bounds__(64 * AW) k_attn_bf16(AttnArgs a, AttnPlan plan
 #pragma unroll
   for (int t = 0; t < QT; ++t) negm[t] = 0.f;
 
-  // Loads of one 32-slot tile: K as MFMA A fragments (row l15 of each 16-slot half, 16 B at
-  // d = s*32 + kg*8), V as plain 16-byte pieces (row i*4+kg, piece l15).  Slots past the
-  // request's data are read from slot 0 (always valid) and masked later.
-#define SP_LOAD_TILE(S0)                                                                           \
-  {                                                                                                \
-    _Pragma("unroll") for (int t2 = 0; t2 < 2; ++t2) {                                             \
-      int slot = (S0) + t2 * 16 + l15;                                                             \
-      slot = slot < span ? slot : 0;                                                               \
-      const char* kp = kplane + (size_t)slot * 256 + kg * 16;                                      \
-      _Pragma("unroll") for (int s = 0; s < 4; ++s)                                                \
-          kreg[t2][s] = *reinterpret_cast<const u32x4_t*>(kp + s * 64);                            \
-    }                                                                                              \
-    _Pragma("unroll") for (int i = 0; i < 8; ++i) {                                                \
-      int slot = (S0) + i * 4 + kg;                                                                \
-      slot = slot < span ? slot : 0;                                                               \
-      vreg[i] = *reinterpret_cast<const u32x4_t*>(vplane + (size_t)slot * 256 + l15 * 16);         \
-    }                                                                                              \
-  }
-
-  u32x4_t kreg[2][4], vreg[8];
-  char* vt = s_v + wave * VT_BYTES;
-  SP_LOAD_TILE(w0 < w1 ? w0 : span)
   for (int s0 = w0; s0 < w1; s0 += 32) {
     // V tile -> LDS and the K fragments into the score MFMAs; then the next tile's loads
     // are issued so that they fly during the softmax and the PV product (the tile after
@@ -314,8 +316,9 @@ __global__ void __launch_bounds__(64 * AW) k_attn_bf16(AttnArgs a, AttnPlan plan
   }
 }
 
-// One wave per (row, query head) of the requests that were cut into several chunks:
-// combine the chunk partials (log2-domain maxima).
+// One wave per (row, query head) of the requests that were cut into several chunks: combine the
+// chunk partials (log2-domain maxima).  Lane c first takes chunk c's (max, sum) and turns them into
+// the chunk's weight; the outputs are then accumulated chunk by chunk, two columns per lane.
 __global__ void __launch_bounds__(256) k_attn_merge(AttnArgs a, AttnPlan plan, int M) {
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int item = blockIdx.x * 4 + wave;
@@ -327,18 +330,40 @@ __global__ void __launch_bounds__(256) k_attn_merge(AttnArgs a, AttnPlan plan, i
   if (chunks == 1) return;               // written directly by the attention kernel
   const size_t stride = (size_t)seg_rows * a.n_q;
   const size_t u0 = (size_t)plan.seg_unit0[seg] + (size_t)(row - plan.seg_row0[seg]) * a.n_q + head;
-  float mx = -INFINITY;
-  for (int c = lane; c < chunks; c += 64) mx = fmaxf(mx, a.part_ml[(u0 + c * stride) * 2]);
-  mx = wave_max(mx);
-  float acc0 = 0.f, acc1 = 0.f, lsum = 0.f;
-  for (int c = 0; c < chunks; ++c) {
-    const size_t u = u0 + c * stride;
-    const float m = a.part_ml[u * 2], l = a.part_ml[u * 2 + 1];
-    if (m == -INFINITY) continue;
-    const float wgt = __builtin_amdgcn_exp2f(m - mx);
-    lsum += wgt * l;
-    acc0 += wgt * a.part_o[u * DH + lane];
-    acc1 += wgt * a.part_o[u * DH + 64 + lane];
+  float acc0 = 0.f, acc1 = 0.f, lsum = 0.f, mx = -INFINITY;
+  for (int c0 = 0; c0 < chunks; c0 += 64) {        // blocks of 64 chunks (one is the rule)
+    const int c = c0 + lane;
+    float m = -INFINITY, l = 0.f;
+    if (c < chunks) {
+      const float2 ml = *reinterpret_cast<const float2*>(a.part_ml + (u0 + c * stride) * 2);
+      m = ml.x; l = ml.y;
+    }
+    const float bm = wave_max(m);
+    const float nmx = fmaxf(mx, bm);
+    if (nmx == -INFINITY) continue;
+    const float resc = (mx == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(mx - nmx);
+    acc0 *= resc; acc1 *= resc; lsum *= resc;
+    mx = nmx;
+    const float wgt = (m == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(m - mx);
+    lsum += wave_sum(wgt * l);
+    const int nb = min(64, chunks - c0);
+    int j = 0;
+    for (; j + 4 <= nb; j += 4) {
+      float w4[4], o0[4], o1[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        w4[i] = __shfl(wgt, j + i, 64);
+        const float* po = a.part_o + (u0 + (size_t)(c0 + j + i) * stride) * DH;
+        o0[i] = po[lane]; o1[i] = po[64 + lane];
+      }
+#pragma unroll
+      for (int i = 0; i < 4; ++i) { acc0 += w4[i] * o0[i]; acc1 += w4[i] * o1[i]; }
+    }
+    for (; j < nb; ++j) {
+      const float w1 = __shfl(wgt, j, 64);
+      const float* po = a.part_o + (u0 + (size_t)(c0 + j) * stride) * DH;
+      acc0 += w1 * po[lane]; acc1 += w1 * po[64 + lane];
+    }
   }
   const float inv = 1.f / lsum;
   bf16_t* po = a.out + ((size_t)row * a.n_q + head) * DH;

@@ -53,7 +53,7 @@ k_gemm_bf16(const bf16_t* __restrict__ X, const bf16_t* __restrict__ W, float* _
   const int cg = wave % NCG, kh = wave / NCG;
   const int r = lane & 15, kg = lane >> 4;
   const int n0 = blockIdx.x * (16 * NCG) + cg * 16;
-  const int m_base = blockIdx.z * 64;
+  const int m_base = blockIdx.z * ROWS;
   const int c_begin = (int)(((long long)blockIdx.y * chunks_total) / S);
   const int c_end = (int)(((long long)(blockIdx.y + 1) * chunks_total) / S);
 
@@ -171,29 +171,37 @@ k_gemm_bf16(const bf16_t* __restrict__ X, const bf16_t* __restrict__ W, float* _
 }
 
 // ---- launchers -------------------------------------------------------------------
+// Up to 64 rows run as one block of MT = ceil(M/16) tiles; more rows run in blocks of 128 (MT = 8,
+// always with the 128-wide chunk so that the two LDS panels fit), each block streaming the weights once.
 template <int NCG, bool GATEUP, int KCV, bool PACKED>
 static hipError_t launch_mt(int MT, dim3 grid, hipStream_t st, const bf16_t* X, const bf16_t* W, float* out,
-                            bf16_t* act, int M, int N, int K, int chunks, int S) {
-#define SP_GO(MTV)                                                                                       \
-  hipLaunchKernelGGL((k_gemm_bf16<MTV, NCG, GATEUP, KCV, SP_GEMM_PF, PACKED>), grid, dim3(256), 0, st, X, W, out, \
-                     act, M, N, K, chunks, S)
+                            bf16_t* act, int M, int N, int K, int S) {
+#define SP_GO(MTV, KCX)                                                                                        \
+  hipLaunchKernelGGL((k_gemm_bf16<MTV, NCG, GATEUP, KCX, SP_GEMM_PF, PACKED>), grid, dim3(256), 0, st, X, W, out, \
+                     act, M, N, K, K / KCX, S)
   switch (MT) {
-    case 1: SP_GO(1); break;
-    case 2: SP_GO(2); break;
-    case 3: SP_GO(3); break;
-    default: SP_GO(4); break;
+    case 1: SP_GO(1, KCV); break;
+    case 2: SP_GO(2, KCV); break;
+    case 3: SP_GO(3, KCV); break;
+    case 4: SP_GO(4, KCV); break;
+    default: SP_GO(8, 128); break;
   }
 #undef SP_GO
   return hipGetLastError();
 }
 
+static inline void row_blocks(int M, int* MT, int* mblocks) {
+  if (M <= 64) { *MT = (M + 15) / 16; *mblocks = 1; }
+  else { *MT = 8; *mblocks = (M + 127) / 128; }
+}
+
 hipError_t sp_launch_gemm_bf16(const bf16_t* X, const bf16_t* W, bool packed, float* out, int M, int N, int K,
                                int max_split, size_t part_capacity_floats, int* S_out, hipStream_t st) {
   constexpr int TILE = 16 * SP_GEMM_NCG_PLAIN;
-  if (M < 1 || N % TILE || K % SP_GEMM_KC_PLAIN) return hipErrorInvalidValue;
-  const int chunks = K / SP_GEMM_KC_PLAIN;
-  const int mblocks = (M + 63) / 64;
-  const int MT = M >= 64 ? 4 : (M + 15) / 16;
+  if (M < 1 || N % TILE || K % SP_GEMM_KC_PLAIN || K % 128) return hipErrorInvalidValue;
+  int MT, mblocks;
+  row_blocks(M, &MT, &mblocks);
+  const int chunks = K / (MT == 8 ? 128 : SP_GEMM_KC_PLAIN);
   const int tiles = N / TILE;
   // enough workgroups to keep every CU streaming, within the partial-sum buffer
   int S = (SP_GEMM_TARGET_WGS + tiles * mblocks - 1) / (tiles * mblocks);
@@ -203,24 +211,20 @@ hipError_t sp_launch_gemm_bf16(const bf16_t* X, const bf16_t* W, bool packed, fl
   if (S < 1) S = 1;
   if ((size_t)S * M * N > part_capacity_floats) return hipErrorInvalidValue;
   *S_out = S;
-  if (packed)
-    return launch_mt<SP_GEMM_NCG_PLAIN, false, SP_GEMM_KC_PLAIN, true>(MT, dim3(tiles, S, mblocks), st, X, W, out,
-                                                                       nullptr, M, N, K, chunks, S);
-  return launch_mt<SP_GEMM_NCG_PLAIN, false, SP_GEMM_KC_PLAIN, false>(MT, dim3(tiles, S, mblocks), st, X, W, out,
-                                                                      nullptr, M, N, K, chunks, S);
+  const dim3 grid(tiles, S, mblocks);
+  if (packed) return launch_mt<SP_GEMM_NCG_PLAIN, false, SP_GEMM_KC_PLAIN, true>(MT, grid, st, X, W, out, nullptr, M, N, K, S);
+  return launch_mt<SP_GEMM_NCG_PLAIN, false, SP_GEMM_KC_PLAIN, false>(MT, grid, st, X, W, out, nullptr, M, N, K, S);
 }
 
 hipError_t sp_launch_gemm_gateup_bf16(const bf16_t* X, const bf16_t* W, bool packed, bf16_t* act, int M, int F,
                                       int K, hipStream_t st) {
   constexpr int TILE = 16 * SP_GEMM_NCG_GATEUP;
-  if (M < 1 || F % TILE || K % SP_GEMM_KC_GATEUP) return hipErrorInvalidValue;
-  const int mblocks = (M + 63) / 64;
-  const int MT = M >= 64 ? 4 : (M + 15) / 16;
-  if (packed)
-    return launch_mt<SP_GEMM_NCG_GATEUP, true, SP_GEMM_KC_GATEUP, true>(MT, dim3(F / TILE, 1, mblocks), st, X, W,
-                                                                        nullptr, act, M, F, K, K / SP_GEMM_KC_GATEUP, 1);
-  return launch_mt<SP_GEMM_NCG_GATEUP, true, SP_GEMM_KC_GATEUP, false>(MT, dim3(F / TILE, 1, mblocks), st, X, W,
-                                                                       nullptr, act, M, F, K, K / SP_GEMM_KC_GATEUP, 1);
+  if (M < 1 || F % TILE || K % SP_GEMM_KC_GATEUP || K % 128) return hipErrorInvalidValue;
+  int MT, mblocks;
+  row_blocks(M, &MT, &mblocks);
+  const dim3 grid(F / TILE, 1, mblocks);
+  if (packed) return launch_mt<SP_GEMM_NCG_GATEUP, true, SP_GEMM_KC_GATEUP, true>(MT, grid, st, X, W, nullptr, act, M, F, K, 1);
+  return launch_mt<SP_GEMM_NCG_GATEUP, true, SP_GEMM_KC_GATEUP, false>(MT, grid, st, X, W, nullptr, act, M, F, K, 1);
 }
 
 // Re-lays a [N][K] row-major bf16 matrix into MFMA fragment order: 16-byte unit u of the output

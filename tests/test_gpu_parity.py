@@ -256,3 +256,22 @@ def test_c2_full_size_in_bench_configuration():
     roots = [i for i, p in enumerate(par) if p < 0]
     pair.prune(0, sp.SP_ACCEPT, roots[0], x_rows=y, row_nodes=list(range(w.n_nodes)))
     pair.close()
+
+
+def test_c3_dimensions_one_layer():
+    """One layer at the 70B shape (d=8192, 64/8 heads, FFN 28672) with config 3's 128-node tree and
+    prefix 4096: two 64-row blocks per projection, 8 query heads per KV head.  (The full 10-layer
+    stage only repeats this layer; its float64 oracle would need 70 GB.)"""
+    w = wl.CONFIGS["C3"]
+    shape = wl.scaled(w.shape, n_layers=1)
+    say("C3 dims, 1 layer")
+    pair = Pair(shape, w.seed, {0: w.prefix_len}, max_batch_nodes=128, flags=sp.SP_FLAG_PACKED_WEIGHTS)
+    par = wl.tree_branching(w.seed, w.n_nodes, w.max_children, w.max_levels)
+    x = wl.hidden_rows(shape, w.seed, ("x",), w.n_nodes)
+    pair.insert(0, par)
+    y, ref = pair.forward([0], [0], [w.n_nodes], x)
+    e = rel_err(y, ref)
+    say("C3-dims rel err", e)
+    assert e <= TOL["bf16"]
+    pair.check_kv(0, TOL["bf16"])
+    pair.close()
