@@ -422,13 +422,22 @@ int sp_stage_forward(sp_stage* s, int32_t n_req, const int32_t* req_ids, const i
 
   int S_prev = 0;                                   // split count of the previous layer's down projection
   const size_t strideD = (size_t)M * d, strideQ = (size_t)M * nqkv;
+  // projections: few rows stream the weights (HBM-bound); many rows use the register-blocked kernel
+  const bool wide = s->fast && M > 128 && nqkv % 256 == 0 && d % 256 == 0 && F % 128 == 0 && dq % 128 == 0;
+  auto gemm = [&](const void* X, const void* Wm, int N_, int K_, int* S_) -> hipError_t {
+    if (wide)
+      return sp_launch_gemm_wide((const bf16_t*)X, (const bf16_t*)Wm, s->packed, w.part, M, N_, K_, s->n_cu,
+                                 w.part_floats, S_, st);
+    return sp_launch_gemm_bf16((const bf16_t*)X, (const bf16_t*)Wm, s->packed, w.part, M, N_, K_, 16, w.part_floats,
+                               S_, st);
+  };
   for (int l = 0; l < c.n_layers; ++l) {
     const sp_layer_weights& L = s->W[l];
     { ProfScope p(s, SP_K_NORM, st);
       SP_TRY(sp_launch_add_norm(dt, w.h, l ? w.part : nullptr, S_prev, strideD, L.norm1, w.xn, M, d, c.rms_eps, st)); }
     int S = 1;
     { ProfScope p(s, SP_K_GEMM_QKV, st);
-      if (s->fast) SP_TRY(sp_launch_gemm_bf16((const bf16_t*)w.xn, (const bf16_t*)L.wqkv, s->packed, w.part, M, nqkv, d, 16, w.part_floats, &S, st));
+      if (s->fast) SP_TRY(gemm(w.xn, L.wqkv, nqkv, d, &S));
       else SP_TRY(sp_launch_gemm_simple(dt, w.xn, L.wqkv, w.part, M, nqkv, d, st)); }
     { ProfScope p(s, SP_K_ROPE_KV, st);
       SP_TRY(sp_launch_rope_kv(dt, w.part, S, strideQ, w.rows, w.cs, w.qbuf, s->geom, l, M, nq, nkv, dh, st)); }
@@ -442,20 +451,21 @@ int sp_stage_forward(sp_stage* s, int32_t n_req, const int32_t* req_ids, const i
     }
     { ProfScope p(s, SP_K_GEMM_O, st);
       S = 1;
-      if (s->fast) SP_TRY(sp_launch_gemm_bf16((const bf16_t*)w.attn, (const bf16_t*)L.wo, s->packed, w.part, M, d, dq, 16, w.part_floats, &S, st));
+      if (s->fast) SP_TRY(gemm(w.attn, L.wo, d, dq, &S));
       else SP_TRY(sp_launch_gemm_simple(dt, w.attn, L.wo, w.part, M, d, dq, st)); }
     { ProfScope p(s, SP_K_NORM, st);
       SP_TRY(sp_launch_add_norm(dt, w.h, w.part, S, strideD, L.norm2, w.xn, M, d, c.rms_eps, st)); }
     { ProfScope p(s, SP_K_GEMM_GATEUP, st);
       if (s->fast) {
-        SP_TRY(sp_launch_gemm_gateup_bf16((const bf16_t*)w.xn, (const bf16_t*)L.wgu, s->packed, (bf16_t*)w.act, M, F, d, st));
+        if (wide) SP_TRY(sp_launch_gemm_wide_gateup((const bf16_t*)w.xn, (const bf16_t*)L.wgu, s->packed, (bf16_t*)w.act, M, F, d, st));
+        else SP_TRY(sp_launch_gemm_gateup_bf16((const bf16_t*)w.xn, (const bf16_t*)L.wgu, s->packed, (bf16_t*)w.act, M, F, d, st));
       } else {
         SP_TRY(sp_launch_gemm_simple(dt, w.xn, L.wgu, w.part, M, 2 * F, d, st));
         SP_TRY(sp_launch_silu_mul(dt, w.part, w.act, M, F, st));
       } }
     { ProfScope p(s, SP_K_GEMM_DOWN, st);
       S = 1;
-      if (s->fast) SP_TRY(sp_launch_gemm_bf16((const bf16_t*)w.act, (const bf16_t*)L.wd, s->packed, w.part, M, d, F, 16, w.part_floats, &S, st));
+      if (s->fast) SP_TRY(gemm(w.act, L.wd, d, F, &S));
       else SP_TRY(sp_launch_gemm_simple(dt, w.act, L.wd, w.part, M, d, F, st)); }
     S_prev = S;
   }

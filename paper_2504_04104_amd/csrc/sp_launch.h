@@ -51,6 +51,12 @@ hipError_t sp_launch_gemm_bf16(const bf16_t* X, const bf16_t* W, bool packed, fl
 // act[m][f] = silu(X Wg^T) * (X Wu^T), W = [gate rows ; up rows]
 hipError_t sp_launch_gemm_gateup_bf16(const bf16_t* X, const bf16_t* W, bool packed, bf16_t* act, int M, int F,
                                       int K, hipStream_t st);
+// Many rows (M > 128): workgroups of 128 rows x 256 columns, weights kept in registers per wave.
+// Needs N % 256 == 0 (gate/up: F % 128 == 0) and K % 64 == 0.
+hipError_t sp_launch_gemm_wide(const bf16_t* X, const bf16_t* W, bool packed, float* out, int M, int N, int K,
+                               int n_cu, size_t part_capacity_floats, int* S_out, hipStream_t st);
+hipError_t sp_launch_gemm_wide_gateup(const bf16_t* X, const bf16_t* W, bool packed, bf16_t* act, int M, int F, int K,
+                                      hipStream_t st);
 // [N][K] row-major bf16 -> MFMA fragment order (N % 16 == 0, K % 32 == 0, out != in)
 hipError_t sp_launch_pack_weights(const void* in, void* out, int N, int K, hipStream_t st);
 

@@ -81,11 +81,11 @@ def test_mini_f32_gqa_forward_in_pieces():
     pair.close()
 
 
-@pytest.mark.parametrize("n", [1, 15, 16, 17, 33, 64, 65, 130])
+@pytest.mark.parametrize("n", [1, 15, 16, 17, 33, 64, 65, 128, 130, 255])
 def test_row_counts_across_tile_edges(n):
     """M below, at and above the 16-row MFMA tile and the 64-row block."""
     shape = MINI_BF16
-    pair = Pair(shape, 13, {0: 129}, max_batch_nodes=160, flags=sp.SP_FLAG_PACKED_WEIGHTS if n % 2 else 0)
+    pair = Pair(shape, 13, {0: 129}, max_batch_nodes=256, flags=sp.SP_FLAG_PACKED_WEIGHTS if n % 2 else 0)
     par = wl.tree_uniform_parents(13, n, 9, name=("t", n))
     x = wl.hidden_rows(shape, 13, ("r", n), n)
     pair.insert(0, par)
@@ -199,6 +199,27 @@ def test_ragged_batch_mini():
             y, ref = pair.forward(act_ids, firsts, counts, x)
             e = rel_err(y, ref)
             assert e <= TOL["bf16"], (s, e)
+    pair.close()
+
+
+@pytest.mark.parametrize("packed", [0, sp.SP_FLAG_PACKED_WEIGHTS], ids=["rowmajor", "packed"])
+def test_wide_batch(packed):
+    """A cold batch of several hundred rows (three requests) goes through the many-row projection
+    kernels: row blocks of 128 with a ragged last block."""
+    shape = MINI_GQA4
+    sizes = {0: (150, 333), 1: (97, 64), 2: (140, 200)}          # nodes, prefix
+    pair = Pair(shape, 18, {r: p for r, (n, p) in sizes.items()}, max_batch_nodes=400, flags=packed)
+    counts = []
+    for r, (n, p) in sizes.items():
+        pair.insert(r, wl.tree_uniform_parents(18, n, 12, name=("w", r)))
+        counts.append(n)
+    x = wl.hidden_rows(shape, 18, ("w",), sum(counts))
+    y, ref = pair.forward(list(sizes), [0] * 3, counts, x)
+    e = rel_err(y, ref)
+    say("wide batch rel err", e)
+    assert e <= TOL["bf16"]
+    for r in sizes:
+        pair.check_kv(r, TOL["bf16"])
     pair.close()
 
 
