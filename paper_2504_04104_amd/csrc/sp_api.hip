@@ -368,9 +368,6 @@ int sp_stage_forward(sp_stage* s, int32_t n_req, const int32_t* req_ids, const i
   hipError_t e;
 #define SP_TRY(call) do { e = (call); if (e != hipSuccess) return hip_fail(s, e); } while (0)
 
-  SP_TRY(sp_launch_prep_rows(b, s->d_meta, s->d_tables, w.rows, w.cs, dh, c.rope_theta, st));
-  SP_TRY(sp_launch_load_rows(dt, x_in, w.h, (size_t)M * d, st));
-
   AttnPlan plan;
   if (s->fast) {
     // Split every request's cache range into chunks so that the grid fills the chip
@@ -434,7 +431,11 @@ int sp_stage_forward(sp_stage* s, int32_t n_req, const int32_t* req_ids, const i
   for (int l = 0; l < c.n_layers; ++l) {
     const sp_layer_weights& L = s->W[l];
     { ProfScope p(s, SP_K_NORM, st);
-      SP_TRY(sp_launch_add_norm(dt, w.h, l ? w.part : nullptr, S_prev, strideD, L.norm1, w.xn, M, d, c.rms_eps, st)); }
+      if (l == 0)
+        SP_TRY(sp_launch_enter_norm(dt, x_in, b, s->d_meta, s->d_tables, w.rows, w.cs, dh, c.rope_theta, w.h, L.norm1,
+                                    w.xn, M, d, c.rms_eps, st));
+      else
+        SP_TRY(sp_launch_add_norm(dt, w.h, w.part, S_prev, strideD, L.norm1, w.xn, M, d, c.rms_eps, st)); }
     int S = 1;
     { ProfScope p(s, SP_K_GEMM_QKV, st);
       if (s->fast) SP_TRY(gemm(w.xn, L.wqkv, nqkv, d, &S));

@@ -25,12 +25,13 @@ hipError_t sp_launch_rows_compact(void* rows, size_t row_stride_bytes, int row_b
                                   hipStream_t st);
 
 // ---- elementwise / row kernels --------------------------------------------------
-hipError_t sp_launch_prep_rows(const FwdBatch& b, const ReqMeta* meta, const ReqTables* tables, RowInfo* rows,
-                               float* cs /*[rows][d_head]: cos then sin*/, int d_head, float theta,
-                               hipStream_t st);
-hipError_t sp_launch_load_rows(int dtype, const void* x, float* h, size_t n, hipStream_t st);
+// Rows enter the stage: row descriptors and rotary tables (cs: [rows][d_head], cos then sin),
+// h = x, xn = rmsnorm(h) * gain.
+hipError_t sp_launch_enter_norm(int dtype, const void* x, const FwdBatch& b, const ReqMeta* meta,
+                                const ReqTables* tables, RowInfo* rows, float* cs, int d_head, float theta, float* h,
+                                const void* gain, void* xn, int M, int d, float eps, hipStream_t st);
 
-// h += sum_s part[s]; xn = rmsnorm(h) * gain   (part may be null)
+// h += sum_s part[s]; xn = rmsnorm(h) * gain
 hipError_t sp_launch_add_norm(int dtype, float* h, const float* part, int S, size_t part_stride,
                               const void* gain, void* xn, int M, int d, float eps, hipStream_t st);
 // q,k rotated, v copied; q -> qbuf [M][n_q*d_head]; k,v -> slab rows

@@ -4,38 +4,24 @@
 // float32 partial sums [S][M][N]; the kernels here fold the S slices in.
 #include "sp_launch.h"
 
-// -----------------------------------------------------------------------------
-// One thread per (row, pair t).  Position of a node = prefix length + depth: each
-// tree level is one future position (Sec. 3.2).  The angle is formed in double so
-// that positions of tens of thousands keep full float accuracy in cos and sin.
-__global__ void k_prep_rows(FwdBatch b, const ReqMeta* meta, const ReqTables* tables, RowInfo* rows, float* cs,
-                            int d_head, float theta) {
-  const int half = d_head >> 1;
-  const int idx = blockIdx.x * blockDim.x + threadIdx.x;
-  const int row = idx / half, tt = idx - row * half;
-  if (row >= b.n_rows) return;
-  int seg = 0;
-  while (seg + 1 < b.n_req && row >= b.row0[seg + 1]) ++seg;
-  const int req = b.req[seg];
-  const int node = b.first[seg] + (row - b.row0[seg]);
-  const ReqMeta m = meta[req];
-  const int pos = m.P + tables[req].depth[node];
-  if (tt == 0) {
-    RowInfo ri;
-    ri.base = m.base; ri.req = req; ri.node = node; ri.pos = pos; ri.P = m.P; ri.T = m.T; ri.seg = seg;
-    rows[row] = ri;
+// Four consecutive elements of the storage type to and from float.
+template <typename T> struct Vec4;
+template <> struct Vec4<float> {
+  static __device__ __forceinline__ f32x4_t ld(const float* p) { return *reinterpret_cast<const f32x4_t*>(p); }
+  static __device__ __forceinline__ void st(float* p, f32x4_t v) { *reinterpret_cast<f32x4_t*>(p) = v; }
+};
+template <> struct Vec4<bf16_t> {
+  static __device__ __forceinline__ f32x4_t ld(const bf16_t* p) {
+    const uint2 u = *reinterpret_cast<const uint2*>(p);
+    return (f32x4_t){bf16_lo(u.x), bf16_hi(u.x), bf16_lo(u.y), bf16_hi(u.y)};
   }
-  const double inv_freq = exp2(-(2.0 * (double)tt / (double)d_head) * log2((double)theta));
-  const double ang = (double)pos * inv_freq;
-  cs[(size_t)row * d_head + tt] = (float)cos(ang);
-  cs[(size_t)row * d_head + half + tt] = (float)sin(ang);
-}
-
-template <typename T>
-__global__ void k_load_rows(const T* x, float* h, size_t n) {
-  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x)
-    h[i] = Elt<T>::ld(x + i);
-}
+  static __device__ __forceinline__ void st(bf16_t* p, f32x4_t v) {
+    uint2 u;
+    u.x = pack_bf16x2(v[0], v[1]);
+    u.y = pack_bf16x2(v[2], v[3]);
+    *reinterpret_cast<uint2*>(p) = u;
+  }
+};
 
 __device__ __forceinline__ float block_sum(float v, float* s_red) {
   v = wave_sum(v);
@@ -49,72 +35,120 @@ __device__ __forceinline__ float block_sum(float v, float* s_red) {
   return tot;
 }
 
-// One workgroup (1024 threads) per row, four columns per thread and pass:
-// h[row] += sum_s part[s][row]; xn[row] = h * rsqrt(mean(h^2)+eps) * gain.
-template <typename T>
-__global__ void __launch_bounds__(1024) k_add_norm(float* h, const float* part, int S, size_t part_stride,
-                                                    const T* gain, T* xn, int d, float eps) {
-  __shared__ float s_red[16];
-  const int row = blockIdx.x;
-  float* hr = h + (size_t)row * d;
-  float ss = 0.f;
-  for (int c = threadIdx.x * 4; c < d; c += blockDim.x * 4) {
-    f32x4_t v = *reinterpret_cast<const f32x4_t*>(hr + c);
-    if (part) {
-      f32x4_t a = {0.f, 0.f, 0.f, 0.f};
-      for (int s = 0; s < S; ++s)
-        a += *reinterpret_cast<const f32x4_t*>(part + (size_t)s * part_stride + (size_t)row * d + c);
-      v += a;
-      *reinterpret_cast<f32x4_t*>(hr + c) = v;
-    }
-    ss += v[0] * v[0] + v[1] * v[1] + v[2] * v[2] + v[3] * v[3];
+// Folds S partial slices into four columns: all loads are issued before the first add.
+__device__ __forceinline__ f32x4_t fold4(const float* p, int S, size_t stride) {
+  f32x4_t a = {0.f, 0.f, 0.f, 0.f};
+  int s = 0;
+  for (; s + 4 <= S; s += 4) {
+    const f32x4_t v0 = *reinterpret_cast<const f32x4_t*>(p + (size_t)s * stride);
+    const f32x4_t v1 = *reinterpret_cast<const f32x4_t*>(p + (size_t)(s + 1) * stride);
+    const f32x4_t v2 = *reinterpret_cast<const f32x4_t*>(p + (size_t)(s + 2) * stride);
+    const f32x4_t v3 = *reinterpret_cast<const f32x4_t*>(p + (size_t)(s + 3) * stride);
+    a += (v0 + v1) + (v2 + v3);
   }
-  const float tot = block_sum(ss, s_red);
-  const float scale = rsqrtf(tot / (float)d + eps);
-  for (int c = threadIdx.x * 4; c < d; c += blockDim.x * 4) {
-    const f32x4_t v = *reinterpret_cast<const f32x4_t*>(hr + c);
-#pragma unroll
-    for (int i = 0; i < 4; ++i) Elt<T>::st(xn + (size_t)row * d + c + i, v[i] * scale * Elt<T>::ld(gain + c + i));
-  }
+  for (; s < S; ++s) a += *reinterpret_cast<const f32x4_t*>(p + (size_t)s * stride);
+  return a;
 }
 
-// One workgroup per (row, head) over the projection's columns: n_q query heads, n_kv key
-// heads, n_kv value heads.  Query and key heads are rotated (half-split pairing: t with
-// t + d_head/2); value heads are copied.  Keys and values go to the node's cache slot.
+// One workgroup (1024 threads) per row, four columns per thread and pass.
+//   FIRST: the row enters the stage: h[row] = x[row]; the row's descriptor and its rotary
+//          table are written as well.  Position of a node = prefix length + depth: each tree
+//          level is one future position (Sec. 3.2).  The angle is formed in double so that
+//          positions of tens of thousands keep full float accuracy in cos and sin.
+//   else:  h[row] += sum_s part[s][row].
+// Then xn[row] = h * rsqrt(mean(h^2)+eps) * gain.  The first two passes stay in registers.
+template <typename T, bool FIRST>
+__global__ void __launch_bounds__(1024) k_add_norm(float* h, const float* part, int S, size_t part_stride,
+                                                    const T* gain, T* xn, int d, float eps, const T* x, FwdBatch b,
+                                                    const ReqMeta* meta, const ReqTables* tables, RowInfo* rows,
+                                                    float* cs, int d_head, float theta) {
+  __shared__ float s_red[16];
+  const int row = blockIdx.x;
+  if (FIRST) {
+    const int half = d_head >> 1;
+    if ((int)threadIdx.x < half) {
+      const int tt = threadIdx.x;
+      int seg = 0;
+      while (seg + 1 < b.n_req && row >= b.row0[seg + 1]) ++seg;
+      const int req = b.req[seg];
+      const int node = b.first[seg] + (row - b.row0[seg]);
+      const ReqMeta m = meta[req];
+      const int pos = m.P + tables[req].depth[node];
+      if (tt == 0) {
+        RowInfo ri;
+        ri.base = m.base; ri.req = req; ri.node = node; ri.pos = pos; ri.P = m.P; ri.T = m.T; ri.seg = seg;
+        rows[row] = ri;
+      }
+      const double inv_freq = exp2(-(2.0 * (double)tt / (double)d_head) * log2((double)theta));
+      const double ang = (double)pos * inv_freq;
+      cs[(size_t)row * d_head + tt] = (float)cos(ang);
+      cs[(size_t)row * d_head + half + tt] = (float)sin(ang);
+    }
+  }
+  float* hr = h + (size_t)row * d;
+  const int c0 = threadIdx.x * 4, step = blockDim.x * 4;
+  f32x4_t keep[2];
+  float ss = 0.f;
+#define SP_ROW_VALUE(c, v)                                                             \
+  if (FIRST) {                                                                         \
+    v = Vec4<T>::ld(x + (size_t)row * d + (c));                                        \
+    *reinterpret_cast<f32x4_t*>(hr + (c)) = v;                                         \
+  } else {                                                                             \
+    v = *reinterpret_cast<const f32x4_t*>(hr + (c));                                   \
+    v += fold4(part + (size_t)row * d + (c), S, part_stride);                          \
+    *reinterpret_cast<f32x4_t*>(hr + (c)) = v;                                         \
+  }                                                                                    \
+  ss += v[0] * v[0] + v[1] * v[1] + v[2] * v[2] + v[3] * v[3];
+#pragma unroll
+  for (int p = 0; p < 2; ++p) {
+    const int c = c0 + p * step;
+    if (c < d) { f32x4_t v; SP_ROW_VALUE(c, v) keep[p] = v; }
+  }
+  for (int c = c0 + 2 * step; c < d; c += step) { f32x4_t v; SP_ROW_VALUE(c, v) }
+#undef SP_ROW_VALUE
+  const float tot = block_sum(ss, s_red);
+  const float scale = rsqrtf(tot / (float)d + eps);
+#pragma unroll
+  for (int p = 0; p < 2; ++p) {
+    const int c = c0 + p * step;
+    if (c < d) Vec4<T>::st(xn + (size_t)row * d + c, keep[p] * scale * Vec4<T>::ld(gain + c));
+  }
+  for (int c = c0 + 2 * step; c < d; c += step)
+    Vec4<T>::st(xn + (size_t)row * d + c, *reinterpret_cast<const f32x4_t*>(hr + c) * scale * Vec4<T>::ld(gain + c));
+}
+
+// Threads work in groups of d_head/8, one group per (row, head) over the projection's
+// columns: n_q query heads, n_kv key heads, n_kv value heads; a thread owns four pairs
+// (t, t + d_head/2).  Query and key heads are rotated (half-split pairing); value heads are
+// copied.  Keys and values go to the node's cache slot.
 template <typename T>
-__global__ void __launch_bounds__(64) k_rope_kv(const float* part, int S, size_t part_stride, const RowInfo* rows,
-                                                 const float* cs, T* qbuf, KvGeom g, int layer, int n_q, int n_kv,
-                                                 int d_head) {
-  const int row = blockIdx.x, head = blockIdx.y;
-  const int half = d_head >> 1;
+__global__ void __launch_bounds__(256) k_rope_kv(const float* part, int S, size_t part_stride, const RowInfo* rows,
+                                                  const float* cs, T* qbuf, KvGeom g, int layer, int n_q, int n_kv,
+                                                  int d_head) {
+  const int half = d_head >> 1, tph = half >> 2;
+  const int row = blockIdx.x;
+  const int head = blockIdx.y * (256 / tph) + threadIdx.x / tph;
+  if (head >= n_q + 2 * n_kv) return;
+  const int t = (threadIdx.x % tph) * 4;
   const int N = (n_q + 2 * n_kv) * d_head;
   const RowInfo ri = rows[row];
   const size_t slot = (size_t)(ri.base + ri.P + ri.node);
   const float* pr = part + (size_t)row * N + (size_t)head * d_head;
+  const f32x4_t a = fold4(pr + t, S, part_stride), bb = fold4(pr + half + t, S, part_stride);
   if (head < n_q + n_kv) {
     const float* c = cs + (size_t)row * d_head;
+    const f32x4_t co = *reinterpret_cast<const f32x4_t*>(c + t), si = *reinterpret_cast<const f32x4_t*>(c + half + t);
     T* dst = head < n_q
                  ? qbuf + ((size_t)row * n_q + head) * d_head
                  : reinterpret_cast<T*>(g.kv + ((size_t)(layer * 2 + 0) * n_kv + (head - n_q)) * g.plane_bytes +
                                         slot * g.row_bytes);
-    for (int t = threadIdx.x; t < half; t += blockDim.x) {
-      float a = 0.f, bb = 0.f;
-      for (int s = 0; s < S; ++s) {
-        a += pr[(size_t)s * part_stride + t];
-        bb += pr[(size_t)s * part_stride + half + t];
-      }
-      const float co = c[t], si = c[half + t];
-      Elt<T>::st(dst + t, a * co - bb * si);
-      Elt<T>::st(dst + half + t, bb * co + a * si);
-    }
+    Vec4<T>::st(dst + t, a * co - bb * si);
+    Vec4<T>::st(dst + half + t, bb * co + a * si);
   } else {
     T* dst = reinterpret_cast<T*>(g.kv + ((size_t)(layer * 2 + 1) * n_kv + (head - n_q - n_kv)) * g.plane_bytes +
                                   slot * g.row_bytes);
-    for (int t = threadIdx.x; t < d_head; t += blockDim.x) {
-      float a = 0.f;
-      for (int s = 0; s < S; ++s) a += pr[(size_t)s * part_stride + t];
-      Elt<T>::st(dst + t, a);
-    }
+    Vec4<T>::st(dst + t, a);
+    Vec4<T>::st(dst + half + t, bb);
   }
 }
 
@@ -130,11 +164,8 @@ __global__ void k_silu_mul(const float* gu, T* act, int M, int F) {
 
 template <typename T>
 __global__ void k_finish(const float* h, const float* part, int S, size_t part_stride, T* out, size_t n) {
-  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) {
-    float v = h[i];
-    for (int s = 0; s < S; ++s) v += part[(size_t)s * part_stride + i];
-    Elt<T>::st(out + i, v);
-  }
+  for (size_t i = ((size_t)blockIdx.x * blockDim.x + threadIdx.x) * 4; i < n; i += (size_t)gridDim.x * blockDim.x * 4)
+    Vec4<T>::st(out + i, *reinterpret_cast<const f32x4_t*>(h + i) + fold4(part + i, S, part_stride));
 }
 
 // ---- launchers -------------------------------------------------------------------
@@ -145,38 +176,43 @@ static inline int grid_for(size_t n, int block, int cap = 4096) {
   return (int)g;
 }
 
-hipError_t sp_launch_prep_rows(const FwdBatch& b, const ReqMeta* meta, const ReqTables* tables, RowInfo* rows,
-                               float* cs, int d_head, float theta, hipStream_t st) {
-  const int n = b.n_rows * (d_head / 2);
-  hipLaunchKernelGGL(k_prep_rows, dim3((n + 255) / 256), dim3(256), 0, st, b, meta, tables, rows, cs, d_head, theta);
-  return hipGetLastError();
-}
-
-hipError_t sp_launch_load_rows(int dtype, const void* x, float* h, size_t n, hipStream_t st) {
-  if (dtype == 0) hipLaunchKernelGGL(k_load_rows<float>, dim3(grid_for(n, 256)), dim3(256), 0, st, (const float*)x, h, n);
-  else hipLaunchKernelGGL(k_load_rows<bf16_t>, dim3(grid_for(n, 256)), dim3(256), 0, st, (const bf16_t*)x, h, n);
+hipError_t sp_launch_enter_norm(int dtype, const void* x, const FwdBatch& b, const ReqMeta* meta,
+                                const ReqTables* tables, RowInfo* rows, float* cs, int d_head, float theta, float* h,
+                                const void* gain, void* xn, int M, int d, float eps, hipStream_t st) {
+  if (dtype == 0)
+    hipLaunchKernelGGL((k_add_norm<float, true>), dim3(M), dim3(1024), 0, st, h, nullptr, 0, 0, (const float*)gain,
+                       (float*)xn, d, eps, (const float*)x, b, meta, tables, rows, cs, d_head, theta);
+  else
+    hipLaunchKernelGGL((k_add_norm<bf16_t, true>), dim3(M), dim3(1024), 0, st, h, nullptr, 0, 0,
+                       (const bf16_t*)gain, (bf16_t*)xn, d, eps, (const bf16_t*)x, b, meta, tables, rows, cs, d_head,
+                       theta);
   return hipGetLastError();
 }
 
 hipError_t sp_launch_add_norm(int dtype, float* h, const float* part, int S, size_t part_stride, const void* gain,
                               void* xn, int M, int d, float eps, hipStream_t st) {
+  const FwdBatch none{};
   if (dtype == 0)
-    hipLaunchKernelGGL(k_add_norm<float>, dim3(M), dim3(1024), 0, st, h, part, S, part_stride, (const float*)gain,
-                       (float*)xn, d, eps);
+    hipLaunchKernelGGL((k_add_norm<float, false>), dim3(M), dim3(1024), 0, st, h, part, S, part_stride,
+                       (const float*)gain, (float*)xn, d, eps, nullptr, none, nullptr, nullptr, nullptr, nullptr, 0,
+                       0.f);
   else
-    hipLaunchKernelGGL(k_add_norm<bf16_t>, dim3(M), dim3(1024), 0, st, h, part, S, part_stride, (const bf16_t*)gain,
-                       (bf16_t*)xn, d, eps);
+    hipLaunchKernelGGL((k_add_norm<bf16_t, false>), dim3(M), dim3(1024), 0, st, h, part, S, part_stride,
+                       (const bf16_t*)gain, (bf16_t*)xn, d, eps, nullptr, none, nullptr, nullptr, nullptr, nullptr, 0,
+                       0.f);
   return hipGetLastError();
 }
 
 hipError_t sp_launch_rope_kv(int dtype, const float* part, int S, size_t part_stride, const RowInfo* rows,
                              const float* cs, void* qbuf, KvGeom g, int layer, int M, int n_q, int n_kv, int d_head,
                              hipStream_t st) {
+  const int heads_per_block = 256 / (d_head / 8);
+  const dim3 grid(M, (n_q + 2 * n_kv + heads_per_block - 1) / heads_per_block);
   if (dtype == 0)
-    hipLaunchKernelGGL(k_rope_kv<float>, dim3(M, n_q + 2 * n_kv), dim3(64), 0, st, part, S, part_stride, rows, cs, (float*)qbuf, g,
+    hipLaunchKernelGGL(k_rope_kv<float>, grid, dim3(256), 0, st, part, S, part_stride, rows, cs, (float*)qbuf, g,
                        layer, n_q, n_kv, d_head);
   else
-    hipLaunchKernelGGL(k_rope_kv<bf16_t>, dim3(M, n_q + 2 * n_kv), dim3(64), 0, st, part, S, part_stride, rows, cs, (bf16_t*)qbuf,
+    hipLaunchKernelGGL(k_rope_kv<bf16_t>, grid, dim3(256), 0, st, part, S, part_stride, rows, cs, (bf16_t*)qbuf,
                        g, layer, n_q, n_kv, d_head);
   return hipGetLastError();
 }
@@ -192,10 +228,10 @@ hipError_t sp_launch_finish(int dtype, const float* h, const float* part, int S,
                             int M, int d, hipStream_t st) {
   const size_t n = (size_t)M * d;
   if (dtype == 0)
-    hipLaunchKernelGGL(k_finish<float>, dim3(grid_for(n, 256)), dim3(256), 0, st, h, part, S, part_stride,
+    hipLaunchKernelGGL(k_finish<float>, dim3(grid_for(n / 4, 256)), dim3(256), 0, st, h, part, S, part_stride,
                        (float*)out, n);
   else
-    hipLaunchKernelGGL(k_finish<bf16_t>, dim3(grid_for(n, 256)), dim3(256), 0, st, h, part, S, part_stride,
+    hipLaunchKernelGGL(k_finish<bf16_t>, dim3(grid_for(n / 4, 256)), dim3(256), 0, st, h, part, S, part_stride,
                        (bf16_t*)out, n);
   return hipGetLastError();
 }

@@ -202,21 +202,35 @@ def test_ragged_batch_mini():
     pair.close()
 
 
+WIDE_BATCHES = {
+    # rows 387: one block of 256 and a ragged block of 131
+    "387": {0: (150, 333), 1: (97, 64), 2: (140, 200)},          # request: (nodes, prefix)
+    # rows 574: two blocks of 256 and a short last block of 62
+    "574": {0: (200, 100), 1: (180, 257), 2: (130, 31), 3: (64, 500)},
+    # rows 200: blocks of 128, the last with 72 rows
+    "200": {0: (120, 90), 1: (80, 300)},
+    # rows 130: blocks of 128, the last with 2 rows
+    "130": {0: (130, 77)},
+}
+
+
+@pytest.mark.parametrize("batch", list(WIDE_BATCHES))
 @pytest.mark.parametrize("packed", [0, sp.SP_FLAG_PACKED_WEIGHTS], ids=["rowmajor", "packed"])
-def test_wide_batch(packed):
-    """A cold batch of several hundred rows (three requests) goes through the many-row projection
-    kernels: row blocks of 128 with a ragged last block."""
+def test_wide_batch(packed, batch):
+    """A cold batch of several hundred rows goes through the many-row projection kernels: full
+    row blocks of 128 or 256 and a ragged last block that runs a body of its own height."""
     shape = MINI_GQA4
-    sizes = {0: (150, 333), 1: (97, 64), 2: (140, 200)}          # nodes, prefix
-    pair = Pair(shape, 18, {r: p for r, (n, p) in sizes.items()}, max_batch_nodes=400, flags=packed)
+    sizes = WIDE_BATCHES[batch]
+    total = sum(n for n, _ in sizes.values())
+    pair = Pair(shape, 18, {r: p for r, (n, p) in sizes.items()}, max_batch_nodes=total, flags=packed)
     counts = []
     for r, (n, p) in sizes.items():
         pair.insert(r, wl.tree_uniform_parents(18, n, 12, name=("w", r)))
         counts.append(n)
     x = wl.hidden_rows(shape, 18, ("w",), sum(counts))
-    y, ref = pair.forward(list(sizes), [0] * 3, counts, x)
+    y, ref = pair.forward(list(sizes), [0] * len(sizes), counts, x)
     e = rel_err(y, ref)
-    say("wide batch rel err", e)
+    say("wide batch", batch, "rel err", e)
     assert e <= TOL["bf16"]
     for r in sizes:
         pair.check_kv(r, TOL["bf16"])
