@@ -14,16 +14,19 @@ back to it or serves as a fallback for it.
 Parity pins (tests/test_oracle_*.py): ancestor walk by brute force, the block
 form of layer appending, prune == rebuild from survivors, Hugging Face's Llama
 decoder layer run sequentially along every root-to-leaf path, torch SDPA with
-an explicit mask, RoPE's relative-position identity, and the closed forms of
-the paper's memory table.  No function here is "parity unpinned".
+an explicit mask, RoPE's relative-position identity, the closed forms of
+the paper's memory table, and for verification Hugging Face's RMSNorm + a
+torch Linear and the lossless property (tree-speculative decoding emits the
+sequence of plain greedy decoding).  No function here is "parity unpinned".
 """
 from .tree import SpecTree
 from .stage import (StageOracle, RequestState, rmsnorm, rope_rotate, silu, tree_attention,
                     decoder_layer)
 from .prune import (accept_masks, drop_masks, compact_rows, PruneResult)
+from .verify import lm_head_logits, greedy_token, greedy_token_fast, match_root_child
 
 __all__ = [
     "SpecTree", "StageOracle", "RequestState", "rmsnorm", "rope_rotate", "silu",
     "tree_attention", "decoder_layer", "accept_masks", "drop_masks", "compact_rows",
-    "PruneResult",
+    "PruneResult", "lm_head_logits", "greedy_token", "greedy_token_fast", "match_root_child",
 ]

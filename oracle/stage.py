@@ -112,6 +112,9 @@ class RequestState:
     tree: SpecTree
     K: List[np.ndarray]           # per layer [capacity, H_kv, d_h] float64
     V: List[np.ndarray]
+    # pred[j]: the model's next token after tree node j (root = 0), -1 while unknown
+    # (set once the node has left the last stage: Algorithm 1, "verify new token")
+    pred: np.ndarray = None
 
 
 class StageOracle:
@@ -140,7 +143,7 @@ class StageOracle:
             V[:P] = prefix_v[l]
             Ks.append(K)
             Vs.append(V)
-        self.req[req] = RequestState(P, SpecTree(), Ks, Vs)
+        self.req[req] = RequestState(P, SpecTree(), Ks, Vs, np.full(1, -1, dtype=np.int64))
 
     # -- layer appending; parents in the library's numbering (-1 = root) -------
     def tree_insert(self, req: int, parents: Sequence[int], tokens: Optional[Sequence[int]] = None,
@@ -151,6 +154,7 @@ class StageOracle:
         tokens = [0] * k if tokens is None else tokens
         probs = [0.0] * k if probs is None else probs
         st.tree.append([p + 1 for p in parents], tokens, probs)
+        st.pred = np.concatenate([st.pred, np.full(k, -1, dtype=np.int64)])
         return first
 
     # -- node-wise computation on nodes [first, first+n) (library numbering) ---
@@ -183,9 +187,10 @@ class StageOracle:
             for C in (st.K[l], st.V[l]):
                 C[lo:lo + n_keep] = compact_rows(C[lo:lo + n], pr.kv_keep)
         if new_root is not None:
-            st.tree.to_subtree(new_root)
+            st.tree.to_subtree(new_root)          # tau_hat is the first kept node: it becomes the root
         else:
             st.tree.select(pr.table_keep)
+        st.pred = st.pred[pr.table_keep]          # the new root's prediction is the accepted node's
         st.P += pr.n_commit
 
     def accept(self, req: int, node: int) -> PruneResult:
@@ -200,6 +205,36 @@ class StageOracle:
         pr = drop_masks(st.tree, node + 1)
         self._apply(st, pr, None)
         return pr
+
+    def clear(self, req: int) -> PruneResult:
+        """Pipeline stall: every speculative node goes, the root stays; nothing is committed."""
+        st = self.req[req]
+        keep = np.zeros(st.tree.n, dtype=bool)
+        keep[0] = True
+        pr = PruneResult(keep, keep.copy(), 0)
+        self._apply(st, pr, None)
+        return pr
+
+    # -- verification on the last stage (Algorithm 1, "verify new token") ---------
+    def set_root_pred(self, req: int, token: int) -> None:
+        self.req[req].pred[0] = int(token)
+
+    def verify_head(self, req: int, first: int, h: np.ndarray, gain: np.ndarray, w_vocab: np.ndarray):
+        """Next-token predictions of nodes [first, first+n) from their last-layer outputs h.
+        Returns (pred, logits)."""
+        from .verify import lm_head_logits, greedy_token_fast
+        st = self.req[req]
+        logits = lm_head_logits(h, gain, w_vocab, self.shape.rms_eps)
+        pred = greedy_token_fast(logits)
+        st.pred[first + 1:first + 1 + len(pred)] = pred
+        return pred, logits
+
+    def match(self, req: int) -> int:
+        """The root child that carries the model's token for the root's successor, or -1."""
+        from .verify import match_root_child
+        st = self.req[req]
+        par, _, tok, _, _ = st.tree.view()
+        return match_root_child(par, tok, int(st.pred[0]))
 
     @staticmethod
     def prune_hidden_rows(rows: np.ndarray, row_nodes: Sequence[int], pr: PruneResult) -> np.ndarray:

@@ -190,6 +190,21 @@ def prefix_kv(shape: ModelShape, seed: int, layer: int, prefix_len: int, req: in
     return k, v
 
 
+def head_weights(shape: ModelShape, seed: int, vocab: int) -> Dict[str, np.ndarray]:
+    """Output head of the last stage: final RMSNorm gain 1 + N(0, 0.02) and the vocabulary
+    projection [vocab, d_model], N(0, 0.02) (y = x W^T)."""
+    return {
+        "norm": normal(seed, ("head_norm",), (shape.d_model,), WEIGHT_STD, mean=1.0, dtype=shape.dtype),
+        "wvocab": normal(seed, ("head_vocab",), (vocab, shape.d_model), WEIGHT_STD, dtype=shape.dtype),
+    }
+
+
+def embedding_table(shape: ModelShape, seed: int, vocab: int) -> np.ndarray:
+    """Input embeddings [vocab, d_model], N(0, 1): the hidden row that enters the first layer
+    for a token."""
+    return normal(seed, ("embed",), (vocab, shape.d_model), dtype=shape.dtype)
+
+
 def hidden_rows(shape: ModelShape, seed: int, name: Sequence, n: int) -> np.ndarray:
     """Input hidden states of n tree nodes, N(0,1), [n, d_model]."""
     return normal(seed, ("x",) + tuple(name), (n, shape.d_model), dtype=shape.dtype)
