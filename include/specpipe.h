@@ -70,7 +70,7 @@ typedef enum sp_status {
 } sp_status;
 
 typedef enum sp_dtype { SP_F32 = 0, SP_BF16 = 1 } sp_dtype;
-typedef enum sp_prune_mode { SP_ACCEPT = 0, SP_DROP = 1 } sp_prune_mode;
+typedef enum sp_prune_mode { SP_ACCEPT = 0, SP_DROP = 1, SP_CLEAR = 2 } sp_prune_mode;
 
 /* sp_config.flags */
 #define SP_FLAG_SIMPLE_KERNELS 1u   /* use the plain (non-MFMA) kernels for every step */
@@ -127,7 +127,19 @@ typedef struct sp_tree_view {
   int32_t token[SP_MAX_TREE_NODES];
   float prob[SP_MAX_TREE_NODES];
   uint64_t anc[SP_MAX_TREE_NODES][SP_ANC_WORDS];
+  int32_t pred[SP_MAX_TREE_NODES];   /* the model's next token after the node, -1 while unknown */
+  int32_t root_pred;                 /* ... after the committed context, -1 while unknown      */
 } sp_tree_view;
+
+/* Output head of the last stage (device pointers; storage type of the config).  With
+ * SP_FLAG_PACKED_WEIGHTS the vocabulary matrix is expected in the re-laid order too
+ * (sp_pack_matrix). */
+typedef struct sp_head_weights {
+  const void* norm;     /* [d_model] gain of the final RMSNorm   */
+  const void* wvocab;   /* [vocab][d_model]                      */
+  int32_t vocab;
+  int32_t reserved;
+} sp_head_weights;
 
 /* ---- set-up ---------------------------------------------------------------- */
 
@@ -145,6 +157,11 @@ int sp_stage_query_sizes(const sp_config* cfg, sp_sizes* out);
  * and d_model, d_ff are multiples of 32. */
 int sp_pack_weights(const sp_config* cfg, const sp_layer_weights* in, const sp_layer_weights* out,
                     sp_stream stream);
+
+/* The same re-layout for one [n_rows][n_cols] bf16 matrix (n_rows % 16 == 0, n_cols % 32 == 0):
+ * used for the vocabulary matrix of the output head. */
+int sp_pack_matrix(const void* in /*device*/, void* out /*device, distinct*/, int32_t n_rows, int32_t n_cols,
+                   sp_stream stream);
 
 /* Builds a stage.  `layers` is a host array of n_layers entries holding device
  * pointers.  Buffers must be at least as large as sp_stage_query_sizes() says and
@@ -190,6 +207,9 @@ int sp_stage_forward(sp_stage* stage, int32_t n_req, const int32_t* req_ids /*ho
  *   descendants of `node` stay as the tree, re-indexed by rank; children of `node`
  *   get parent -1; depths shrink by n_commit.
  * SP_DROP(node): `node` and its descendants leave the tree; nothing is committed.
+ * SP_CLEAR: every speculative node leaves (a pipeline stall, Algorithm 1 lines 8-9: the true
+ *   token then enters as a level of its own); `node` is ignored; nothing is committed.
+ * On SP_ACCEPT the prediction stored for `node` becomes the root's (see sp_stage_verify_head).
  * Computes the keep flags from the mask column, their prefix sums, and the compacted
  * tables on the device, and leaves the old->new map there for sp_kv_compact, which
  * must be the next call for this request.  Outputs are computed on the host mirror. */
@@ -217,6 +237,38 @@ int sp_tree_prune_batch(sp_stage* stage, int32_t n, const int32_t* req_ids, cons
                         int32_t* n_commit_out /*nullable*/, sp_stream stream);
 int sp_kv_compact_batch(sp_stage* stage, int32_t n, const int32_t* req_ids, sp_stream stream);
 
+/* ---- verification on the last stage (Algorithm 1, "verify new token"; Sec. 3.3.3) ----- */
+
+/* Next-token prediction of tree nodes from their outputs of the last decoder layer:
+ *   pred = argmax_v ( RMSNorm(x; head->norm, rms_eps) . head->wvocab[v] ),
+ * the lowest v among equal maxima (top-1 validation).  Rows of `x` (device, [sum n][d_model],
+ * 16-byte aligned) are in the order of sp_stage_forward: request by request, nodes
+ * first_node[i] .. first_node[i] + n_nodes[i] - 1, which must have been forwarded
+ * (else SP_E_ORDER).  The prediction of every row is stored in its node's table entry and,
+ * if the pointers are given, written to pred_out[row] / the winning logit to max_out[row]
+ * (device).  The vocabulary matrix is read once; logits are not materialised on the bf16
+ * matrix-core path (vocab % 64 == 0), otherwise they take vocab * rows floats of the
+ * workspace (SP_E_CAPACITY if that does not fit).  Uses the stage's workspace: do not
+ * overlap with sp_stage_forward on another stream. */
+int sp_stage_verify_head(sp_stage* stage, const sp_head_weights* head, int32_t n_req,
+                         const int32_t* req_ids /*host*/, const int32_t* first_node /*host*/,
+                         const int32_t* n_nodes /*host*/, const void* x /*device*/,
+                         int32_t* pred_out /*device, nullable*/, float* max_out /*device, nullable*/,
+                         sp_stream stream);
+
+/* Declares the model's token after the committed context of a request whose tree the
+ * last stage has not fed yet (after prefill or a stall).  Later it follows the accepts. */
+int sp_request_set_root_pred(sp_stage* stage, int32_t req, int32_t token, sp_stream stream);
+
+/* The verified token of each request: nodes_dev[i] (device) = the first child of the root
+ * whose token equals the root's prediction, -1 if none does (stall) or the prediction is
+ * unknown.  If nodes_host != NULL the result is also copied there asynchronously on
+ * `stream` (pinned memory advised); it is valid once the stream has been synchronised.
+ * The caller then issues sp_tree_prune(SP_ACCEPT, node), or SP_CLEAR and an insert of the
+ * predicted token on a miss. */
+int sp_tree_match(sp_stage* stage, int32_t n, const int32_t* req_ids /*host*/, int32_t* nodes_dev /*device*/,
+                  int32_t* nodes_host /*host, nullable*/, sp_stream stream);
+
 /* ---- inspection ------------------------------------------------------------- */
 
 /* Copies a request's device tables to the host.  Waits for `stream`. */
@@ -233,7 +285,7 @@ int sp_request_info(const sp_stage* stage, int32_t req, int32_t* prefix_len, int
 typedef enum sp_kernel_kind {
   SP_K_NONE = 0, SP_K_GEMM_QKV = 1, SP_K_GEMM_O = 2, SP_K_GEMM_GATEUP = 3, SP_K_GEMM_DOWN = 4,
   SP_K_ATTENTION = 5, SP_K_ATTENTION_MERGE = 6, SP_K_KV_COMPACT = 7, SP_K_TREE_PRUNE = 8,
-  SP_K_TREE_INSERT = 9, SP_K_NORM = 10, SP_K_ROPE_KV = 11, SP_K_KIND_COUNT = 12
+  SP_K_TREE_INSERT = 9, SP_K_NORM = 10, SP_K_ROPE_KV = 11, SP_K_VERIFY_HEAD = 12, SP_K_KIND_COUNT = 13
 } sp_kernel_kind;
 int sp_profile_begin(sp_stage* stage, int32_t kind, int32_t max_launches);
 int sp_profile_end(sp_stage* stage, int32_t* n_launches, float* total_ms);

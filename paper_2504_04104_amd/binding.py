@@ -18,13 +18,14 @@ LIB_PATH = os.path.join(HERE, "libspecpipe.so")
 SP_MAX_TREE_NODES = 256
 SP_MAX_BATCH_REQ = 64
 SP_F32, SP_BF16 = 0, 1
-SP_ACCEPT, SP_DROP = 0, 1
+SP_ACCEPT, SP_DROP, SP_CLEAR = 0, 1, 2
 SP_FLAG_SIMPLE_KERNELS = 1
 SP_FLAG_PACKED_WEIGHTS = 2
 
 # sp_kernel_kind
 K_GEMM_QKV, K_GEMM_O, K_GEMM_GATEUP, K_GEMM_DOWN = 1, 2, 3, 4
 K_ATTENTION, K_ATTENTION_MERGE, K_KV_COMPACT, K_TREE_PRUNE, K_TREE_INSERT, K_NORM, K_ROPE_KV = 5, 6, 7, 8, 9, 10, 11
+K_VERIFY_HEAD = 12
 
 STATUS = {0: "SP_OK", -1: "SP_E_INVALID", -2: "SP_E_CAPACITY", -3: "SP_E_BAD_PARENT", -4: "SP_E_BAD_REQ",
           -5: "SP_E_BAD_NODE", -6: "SP_E_ORDER", -7: "SP_E_PENDING", -8: "SP_E_HIP", -9: "SP_E_UNSUPPORTED"}
@@ -62,7 +63,12 @@ class sp_tree_view(C.Structure):
     _fields_ = [("prefix_len", C.c_int32), ("n_live", C.c_int32),
                 ("parent", C.c_int32 * SP_MAX_TREE_NODES), ("depth", C.c_int32 * SP_MAX_TREE_NODES),
                 ("token", C.c_int32 * SP_MAX_TREE_NODES), ("prob", C.c_float * SP_MAX_TREE_NODES),
-                ("anc", (C.c_uint64 * 4) * SP_MAX_TREE_NODES)]
+                ("anc", (C.c_uint64 * 4) * SP_MAX_TREE_NODES),
+                ("pred", C.c_int32 * SP_MAX_TREE_NODES), ("root_pred", C.c_int32)]
+
+
+class sp_head_weights(C.Structure):
+    _fields_ = [("norm", C.c_void_p), ("wvocab", C.c_void_p), ("vocab", C.c_int32), ("reserved", C.c_int32)]
 
 
 _lib = None
@@ -86,7 +92,11 @@ def load_library(path: Optional[str] = None) -> C.CDLL:
         "sp_stage_create": [C.POINTER(sp_config), C.POINTER(sp_layer_weights), C.POINTER(sp_buffers), vp,
                             C.POINTER(vp)],
         "sp_pack_weights": [C.POINTER(sp_config), C.POINTER(sp_layer_weights), C.POINTER(sp_layer_weights), vp],
+        "sp_pack_matrix": [vp, vp, C.c_int32, C.c_int32, vp],
         "sp_request_init": [vp, C.c_int32, C.c_int64, C.c_int32, C.c_int32, vp],
+        "sp_stage_verify_head": [vp, C.POINTER(sp_head_weights), C.c_int32, i32p, i32p, i32p, vp, vp, vp, vp],
+        "sp_request_set_root_pred": [vp, C.c_int32, C.c_int32, vp],
+        "sp_tree_match": [vp, C.c_int32, i32p, vp, i32p, vp],
         "sp_tree_insert": [vp, C.c_int32, C.c_int32, i32p, i32p, f32p, i32p, vp],
         "sp_stage_forward": [vp, C.c_int32, i32p, i32p, i32p, vp, vp, vp],
         "sp_tree_prune": [vp, C.c_int32, C.c_int32, C.c_int32, i32p, i32p, vp],
@@ -263,7 +273,40 @@ class Stage:
         return {"prefix_len": v.prefix_len, "n_live": n,
                 "parent": np.ctypeslib.as_array(v.parent)[:n].copy(), "depth": np.ctypeslib.as_array(v.depth)[:n].copy(),
                 "token": np.ctypeslib.as_array(v.token)[:n].copy(), "prob": np.ctypeslib.as_array(v.prob)[:n].copy(),
-                "anc": anc, "M": M}
+                "anc": anc, "M": M, "pred": np.ctypeslib.as_array(v.pred)[:n].copy(), "root_pred": v.root_pred}
+
+    # -- verification on the last stage ------------------------------------------------------
+    def verify_head(self, head: Dict[str, "object"], req_ids: Sequence[int], first_node: Sequence[int],
+                    n_nodes: Sequence[int], x, want_max: bool = False):
+        """head: {"norm": tensor [d], "wvocab": tensor [V, d] (re-laid if the stage uses packed weights)}.
+        Returns the device tensor of predictions (int32 per row) and, if asked, the winning logits."""
+        import torch
+        ra, rp = _i32(req_ids)
+        fa, fp = _i32(first_node)
+        na, npn = _i32(n_nodes)
+        rows = int(sum(n_nodes))
+        assert x.is_contiguous() and x.dtype == self.tdtype
+        pred = torch.empty(max(rows, 1), dtype=torch.int32, device=self.device)
+        mx = torch.empty(max(rows, 1), dtype=torch.float32, device=self.device) if want_max else None
+        h = sp_head_weights(head["norm"].data_ptr(), head["wvocab"].data_ptr(), int(head["wvocab"].shape[0]), 0)
+        _check(self.lib.sp_stage_verify_head(self.handle, C.byref(h), len(ra), rp, fp, npn, x.data_ptr(),
+                                             pred.data_ptr(), mx.data_ptr() if want_max else None, self._stream()),
+               "sp_stage_verify_head")
+        return (pred[:rows], mx[:rows]) if want_max else pred[:rows]
+
+    def set_root_pred(self, req: int, token: int):
+        _check(self.lib.sp_request_set_root_pred(self.handle, req, token, self._stream()), "sp_request_set_root_pred")
+
+    def tree_match(self, req_ids: Sequence[int]) -> List[int]:
+        """Verified root child per request (-1 = miss); waits for the stream."""
+        import torch
+        ra, rp = _i32(req_ids)
+        dev = torch.empty(max(len(ra), 1), dtype=torch.int32, device=self.device)
+        host = torch.empty(max(len(ra), 1), dtype=torch.int32, pin_memory=True)
+        _check(self.lib.sp_tree_match(self.handle, len(ra), rp, dev.data_ptr(),
+                                      C.cast(host.data_ptr(), C.POINTER(C.c_int32)), self._stream()), "sp_tree_match")
+        torch.cuda.current_stream(self.device).synchronize()
+        return [int(v) for v in host[:len(ra)]]
 
     def request_info(self, req: int):
         p, t, f = C.c_int32(), C.c_int32(), C.c_int32()
@@ -300,6 +343,17 @@ def pack_weights(shape, layers: List[Dict[str, "object"]], device: str = "cuda:0
             setattr(b, name, w[name].data_ptr())
         _check(lib.sp_pack_weights(C.byref(cfg), C.byref(a), C.byref(b), stream), "sp_pack_weights")
         out.append(o)
+    torch.cuda.synchronize()
+    return out
+
+
+def pack_matrix(w, device: str = "cuda:0"):
+    """sp_pack_matrix: a [rows, cols] bf16 device tensor re-laid into MFMA fragment order (new tensor)."""
+    import torch
+    lib = load_library()
+    out = torch.empty_like(w)
+    stream = C.c_void_p(torch.cuda.current_stream(torch.device(device)).cuda_stream)
+    _check(lib.sp_pack_matrix(w.data_ptr(), out.data_ptr(), w.shape[0], w.shape[1], stream), "sp_pack_matrix")
     torch.cuda.synchronize()
     return out
 

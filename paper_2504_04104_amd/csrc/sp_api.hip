@@ -144,7 +144,7 @@ HostReq* get_req(sp_stage* s, int req) {
 void mirror_prune(HostReq& r, int mode, int node, int* n_tab, int* n_commit) {
   bool in_col[SP_T];
   for (int i = 0; i < r.T; ++i)
-    in_col[i] = (i == node) || (r.parent[i] >= 0 && in_col[r.parent[i]]);
+    in_col[i] = mode == SP_CLEAR || (i == node) || (r.parent[i] >= 0 && in_col[r.parent[i]]);
   int commit = 0;
   if (mode == SP_ACCEPT) for (int j = node; j >= 0; j = r.parent[j]) ++commit;
   short parent_new[SP_T];
@@ -276,6 +276,12 @@ int sp_pack_weights(const sp_config* cfg, const sp_layer_weights* in, const sp_l
       sp_launch_pack_weights(in->wd, (void*)out->wd, cfg->d_model, cfg->d_ff, st) != hipSuccess)
     return SP_E_HIP;
   return SP_OK;
+}
+
+int sp_pack_matrix(const void* in, void* out, int32_t n_rows, int32_t n_cols, sp_stream stream) {
+  if (!in || !out || in == out || n_rows < 1 || n_cols < 1) return SP_E_INVALID;
+  if (n_rows % 16 || n_cols % 32) return SP_E_UNSUPPORTED;
+  return sp_launch_pack_weights(in, out, n_rows, n_cols, (hipStream_t)stream) == hipSuccess ? SP_OK : SP_E_HIP;
 }
 
 int sp_request_init(sp_stage* s, int32_t req, int64_t slot_base, int32_t capacity, int32_t prefix_len,
@@ -491,9 +497,9 @@ int sp_tree_prune_batch(sp_stage* s, int32_t n, const int32_t* req_ids, const in
     if (modes[i] < 0) continue;
     HostReq* r = get_req(s, req_ids[i]);
     if (!r) return SP_E_BAD_REQ;
-    if (modes[i] != SP_ACCEPT && modes[i] != SP_DROP) return SP_E_INVALID;
+    if (modes[i] != SP_ACCEPT && modes[i] != SP_DROP && modes[i] != SP_CLEAR) return SP_E_INVALID;
     if (r->pending) return SP_E_PENDING;
-    if (nodes[i] < 0 || nodes[i] >= r->T) return SP_E_BAD_NODE;
+    if (modes[i] != SP_CLEAR && (nodes[i] < 0 || nodes[i] >= r->T)) return SP_E_BAD_NODE;
     for (int j = 0; j < i; ++j) if (modes[j] >= 0 && req_ids[j] == req_ids[i]) return SP_E_INVALID;
     any = true;
   }
@@ -603,12 +609,90 @@ int sp_tree_read(sp_stage* s, int32_t req, sp_tree_view* out, sp_stream stream) 
       (e = hipMemcpyAsync(out->depth, t->depth, sizeof(out->depth), hipMemcpyDeviceToHost, st)) != hipSuccess ||
       (e = hipMemcpyAsync(out->token, t->token, sizeof(out->token), hipMemcpyDeviceToHost, st)) != hipSuccess ||
       (e = hipMemcpyAsync(out->prob, t->prob, sizeof(out->prob), hipMemcpyDeviceToHost, st)) != hipSuccess ||
+      (e = hipMemcpyAsync(out->pred, t->pred, sizeof(out->pred), hipMemcpyDeviceToHost, st)) != hipSuccess ||
       (e = hipMemcpyAsync(out->anc, t->anc, sizeof(out->anc), hipMemcpyDeviceToHost, st)) != hipSuccess)
     return hip_fail(s, e);
   if ((e = hipStreamSynchronize(st)) != hipSuccess) return hip_fail(s, e);
   out->prefix_len = m.P;
   out->n_live = m.T;
+  out->root_pred = m.root_pred;
   return SP_OK;
+}
+
+int sp_request_set_root_pred(sp_stage* s, int32_t req, int32_t token, sp_stream stream) {
+  if (!s) return SP_E_INVALID;
+  if (!get_req(s, req)) return SP_E_BAD_REQ;
+  if (token < 0) return SP_E_INVALID;
+  hipError_t e = sp_launch_set_root_pred(s->d_meta, req, token, (hipStream_t)stream);
+  return e == hipSuccess ? SP_OK : hip_fail(s, e);
+}
+
+int sp_stage_verify_head(sp_stage* s, const sp_head_weights* head, int32_t n_req, const int32_t* req_ids,
+                         const int32_t* first_node, const int32_t* n_nodes, const void* x, int32_t* pred_out,
+                         float* max_out, sp_stream stream) {
+  if (!s || !head || !req_ids || !first_node || !n_nodes) return SP_E_INVALID;
+  if (!head->norm || !head->wvocab || head->vocab < 1) return SP_E_INVALID;
+  if (n_req < 0 || n_req > SP_MAX_BATCH_REQ) return SP_E_CAPACITY;
+  const sp_config& c = s->cfg;
+  hipStream_t st = (hipStream_t)stream;
+  FwdBatch b;
+  b.n_req = 0;
+  int rows = 0;
+  for (int i = 0; i < n_req; ++i) {
+    HostReq* r = get_req(s, req_ids[i]);
+    if (!r) return SP_E_BAD_REQ;
+    if (r->pending) return SP_E_PENDING;
+    for (int j = 0; j < i; ++j) if (req_ids[j] == req_ids[i]) return SP_E_INVALID;
+    if (n_nodes[i] < 0) return SP_E_INVALID;
+    if (n_nodes[i] == 0) continue;
+    if (first_node[i] < 0 || first_node[i] + n_nodes[i] > r->T) return SP_E_BAD_NODE;
+    // a prediction needs the node's output of the last layer: it must have been forwarded
+    for (int k = first_node[i]; k < first_node[i] + n_nodes[i]; ++k) if (!r->fwd[k]) return SP_E_ORDER;
+    b.req[b.n_req] = req_ids[i]; b.first[b.n_req] = first_node[i]; b.n[b.n_req] = n_nodes[i]; b.row0[b.n_req] = rows;
+    ++b.n_req;
+    rows += n_nodes[i];
+  }
+  if (rows > c.max_batch_nodes) return SP_E_CAPACITY;
+  if (rows == 0) return SP_OK;
+  if (!x) return SP_E_INVALID;
+  b.n_rows = rows;
+  const int M = rows, d = c.d_model, V = head->vocab;
+  Workspace& w = s->ws;
+  hipError_t e;
+  // final RMSNorm (the row descriptors and the float copy of x it also writes are scratch here)
+  e = sp_launch_enter_norm(c.dtype, x, b, s->d_meta, s->d_tables, w.rows, w.cs, c.d_head, c.rope_theta, w.h,
+                           head->norm, w.xn, M, d, c.rms_eps, st);
+  if (e != hipSuccess) return hip_fail(s, e);
+  ProfScope p(s, SP_K_VERIFY_HEAD, st);
+  if (s->fast && V % 64 == 0 && d % 128 == 0) {
+    int tiles = 0;
+    e = sp_launch_gemm_argmax_bf16((const bf16_t*)w.xn, (const bf16_t*)head->wvocab, s->packed, w.part, M, V, d,
+                                   w.part_floats, &tiles, st);
+    if (e == hipErrorInvalidValue) return SP_E_CAPACITY;
+    if (e == hipSuccess) e = sp_launch_argmax_rows(true, w.part, tiles, b, s->d_tables, pred_out, max_out, st);
+  } else {
+    if ((size_t)M * V > w.part_floats) return SP_E_CAPACITY;
+    e = sp_launch_gemm_simple(c.dtype, w.xn, head->wvocab, w.part, M, V, d, st);
+    if (e == hipSuccess) e = sp_launch_argmax_rows(false, w.part, V, b, s->d_tables, pred_out, max_out, st);
+  }
+  return e == hipSuccess ? SP_OK : hip_fail(s, e);
+}
+
+int sp_tree_match(sp_stage* s, int32_t n, const int32_t* req_ids, int32_t* nodes_dev, int32_t* nodes_host,
+                  sp_stream stream) {
+  if (!s || !req_ids || !nodes_dev) return SP_E_INVALID;
+  if (n < 0 || n > SP_MAX_BATCH_REQ) return SP_E_CAPACITY;
+  for (int i = 0; i < n; ++i) {
+    HostReq* r = get_req(s, req_ids[i]);
+    if (!r) return SP_E_BAD_REQ;
+    if (r->pending) return SP_E_PENDING;
+  }
+  if (n == 0) return SP_OK;
+  hipStream_t st = (hipStream_t)stream;
+  hipError_t e = sp_launch_tree_match(s->d_meta, s->d_tables, n, req_ids, nodes_dev, st);
+  if (e == hipSuccess && nodes_host)
+    e = hipMemcpyAsync(nodes_host, nodes_dev, sizeof(int32_t) * n, hipMemcpyDeviceToHost, st);
+  return e == hipSuccess ? SP_OK : hip_fail(s, e);
 }
 
 int sp_profile_begin(sp_stage* s, int32_t kind, int32_t max_launches) {

@@ -23,7 +23,7 @@ struct ReqMeta {
   int cap;          // slots it owns
   int P;            // committed tokens (root included)
   int T;            // live speculative nodes
-  int pad;
+  int root_pred;    // the model's token after the committed context, -1 while unknown
 };
 
 // Tree tables of a request (Sec. 3.2: I, P, M) plus the map the last prune left
@@ -34,6 +34,7 @@ struct ReqTables {
   int depth[SP_T];
   int token[SP_T];
   float prob[SP_T];
+  int pred[SP_T];         // the model's next token after the node, -1 until the last stage has seen it
   unsigned long long anc[SP_T][SP_W];
   // pending compaction: cache rows [0, n_kv_keep) of the tree region take the rows
   // of old nodes kv_src[0..n_kv_keep); rows below first_moved stay where they are.

@@ -34,7 +34,10 @@
 // PACKED: the weights were re-laid at load time (sp_pack_weights) into MFMA fragment order --
 // per strip of 16 rows, one contiguous 1 KB block per k-step of 32, lane-major -- so that every
 // wave load is one contiguous kilobyte instead of sixteen 64-byte pieces.
-template <int MT, int NCG, bool GATEUP, int KC, int PF, bool PACKED>
+// ARGMAX (output head of the last stage, Algorithm 1 "verify new token"): instead of the
+// products, a workgroup leaves per row the largest of its 16*NCG columns and that column's
+// index (the lowest one among equal maxima) as a (float, int) pair at out[(m * tiles + tile) * 2].
+template <int MT, int NCG, bool GATEUP, int KC, int PF, bool PACKED, bool ARGMAX = false>
 __global__ void __launch_bounds__(256)
 k_gemm_bf16(const bf16_t* __restrict__ X, const bf16_t* __restrict__ W, float* __restrict__ out,
             bf16_t* __restrict__ act, int M, int N, int K, int chunks_total, int S) {
@@ -149,6 +152,39 @@ k_gemm_bf16(const bf16_t* __restrict__ X, const bf16_t* __restrict__ W, float* _
 
   // lane holds, for activation row m = mt*16 + l%16, output columns n0 + 4*(l/16) + 0..3
   const int ncol = n0 + 4 * kg;
+  if (ARGMAX) {
+    static_assert(!ARGMAX || (NKH == 1 && !GATEUP), "one wave per column group");
+    float* s_val = reinterpret_cast<float*>(&lds[0][0]);          // [NCG][ROWS]; the panels are no longer read
+    int* s_idx = reinterpret_cast<int*>(s_val + NCG * ROWS);
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+      float bv = acc[0][mt][0];
+      int bi = ncol;
+#pragma unroll
+      for (int i = 1; i < 4; ++i)
+        if (acc[0][mt][i] > bv) { bv = acc[0][mt][i]; bi = ncol + i; }
+#pragma unroll
+      for (int off = 16; off <= 32; off <<= 1) {                  // the four lanes that hold the row
+        const float ov = __shfl_xor(bv, off, 64);
+        const int oi = __shfl_xor(bi, off, 64);
+        if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }
+      }
+      if (kg == 0) { s_val[cg * ROWS + mt * 16 + r] = bv; s_idx[cg * ROWS + mt * 16 + r] = bi; }
+    }
+    __syncthreads();
+    const int m = m_base + tid;
+    if (tid < ROWS && m < M) {
+      float bv = s_val[tid];
+      int bi = s_idx[tid];
+#pragma unroll
+      for (int c = 1; c < NCG; ++c)                               // ascending columns: ties keep the lower one
+        if (s_val[c * ROWS + tid] > bv) { bv = s_val[c * ROWS + tid]; bi = s_idx[c * ROWS + tid]; }
+      float* o = out + ((size_t)m * gridDim.x + blockIdx.x) * 2;
+      o[0] = bv;
+      reinterpret_cast<int*>(o)[1] = bi;
+    }
+    return;
+  }
 #pragma unroll
   for (int mt = 0; mt < MT; ++mt) {
     const int m = m_base + mt * 16 + r;
@@ -173,12 +209,12 @@ k_gemm_bf16(const bf16_t* __restrict__ X, const bf16_t* __restrict__ W, float* _
 // ---- launchers -------------------------------------------------------------------
 // Up to 64 rows run as one block of MT = ceil(M/16) tiles; more rows run in blocks of 128 (MT = 8,
 // always with the 128-wide chunk so that the two LDS panels fit), each block streaming the weights once.
-template <int NCG, bool GATEUP, int KCV, bool PACKED>
+template <int NCG, bool GATEUP, int KCV, bool PACKED, bool ARGMAX = false>
 static hipError_t launch_mt(int MT, dim3 grid, hipStream_t st, const bf16_t* X, const bf16_t* W, float* out,
                             bf16_t* act, int M, int N, int K, int S) {
 #define SP_GO(MTV, KCX)                                                                                        \
-  hipLaunchKernelGGL((k_gemm_bf16<MTV, NCG, GATEUP, KCX, SP_GEMM_PF, PACKED>), grid, dim3(256), 0, st, X, W, out, \
-                     act, M, N, K, K / KCX, S)
+  hipLaunchKernelGGL((k_gemm_bf16<MTV, NCG, GATEUP, KCX, SP_GEMM_PF, PACKED, ARGMAX>), grid, dim3(256), 0, st, X, \
+                     W, out, act, M, N, K, K / KCX, S)
   switch (MT) {
     case 1: SP_GO(1, KCV); break;
     case 2: SP_GO(2, KCV); break;
@@ -225,6 +261,23 @@ hipError_t sp_launch_gemm_gateup_bf16(const bf16_t* X, const bf16_t* W, bool pac
   const dim3 grid(F / TILE, 1, mblocks);
   if (packed) return launch_mt<SP_GEMM_NCG_GATEUP, true, SP_GEMM_KC_GATEUP, true>(MT, grid, st, X, W, nullptr, act, M, F, K, 1);
   return launch_mt<SP_GEMM_NCG_GATEUP, true, SP_GEMM_KC_GATEUP, false>(MT, grid, st, X, W, nullptr, act, M, F, K, 1);
+}
+
+// Output head: per row the top column of every 64-column tile, as (value, index) pairs
+// pairs[(m * tiles + tile) * 2]; *tiles_out = V / 64.  One pass over the vocabulary matrix.
+hipError_t sp_launch_gemm_argmax_bf16(const bf16_t* X, const bf16_t* W, bool packed, float* pairs, int M, int V, int K,
+                                      size_t pair_capacity_floats, int* tiles_out, hipStream_t st) {
+  constexpr int TILE = 16 * SP_GEMM_NCG_PLAIN;
+  static_assert(SP_GEMM_NCG_PLAIN == 4, "the top-column epilogue needs one wave per column group");
+  if (M < 1 || V % TILE || K % SP_GEMM_KC_PLAIN || K % 128) return hipErrorInvalidValue;
+  int MT, mblocks;
+  row_blocks(M, &MT, &mblocks);
+  const int tiles = V / TILE;
+  if ((size_t)M * tiles * 2 > pair_capacity_floats) return hipErrorInvalidValue;
+  *tiles_out = tiles;
+  const dim3 grid(tiles, 1, mblocks);
+  if (packed) return launch_mt<SP_GEMM_NCG_PLAIN, false, SP_GEMM_KC_PLAIN, true, true>(MT, grid, st, X, W, pairs, nullptr, M, V, K, 1);
+  return launch_mt<SP_GEMM_NCG_PLAIN, false, SP_GEMM_KC_PLAIN, false, true>(MT, grid, st, X, W, pairs, nullptr, M, V, K, 1);
 }
 
 // Re-lays a [N][K] row-major bf16 matrix into MFMA fragment order: 16-byte unit u of the output

@@ -19,6 +19,10 @@ hipError_t sp_launch_request_init(ReqMeta* meta, ReqTables* tables, int req, lon
 hipError_t sp_launch_tree_insert(ReqMeta* meta, ReqTables* tables, int req, int n_new, const InsertArgs& a,
                                  KvGeom g, long long first_slot, hipStream_t st);
 hipError_t sp_launch_tree_prune(ReqMeta* meta, ReqTables* tables, const PruneBatch& b, hipStream_t st);
+// out[i] (device) = verified root child of request reqs[i], or -1
+hipError_t sp_launch_tree_match(const ReqMeta* meta, const ReqTables* tables, int n, const int* reqs, int* out,
+                                hipStream_t st);
+hipError_t sp_launch_set_root_pred(ReqMeta* meta, int req, int token, hipStream_t st);
 hipError_t sp_launch_kv_compact(const ReqMeta* meta, const ReqTables* tables, const PruneBatch& b, KvGeom g,
                                 hipStream_t st);
 hipError_t sp_launch_rows_compact(void* rows, size_t row_stride_bytes, int row_bytes, const RowList& l,
@@ -38,6 +42,9 @@ hipError_t sp_launch_add_norm(int dtype, float* h, const float* part, int S, siz
 hipError_t sp_launch_rope_kv(int dtype, const float* part, int S, size_t part_stride, const RowInfo* rows,
                              const float* cs, void* qbuf, KvGeom g, int layer, int M, int n_q, int n_kv,
                              int d_head, hipStream_t st);
+// top-1 token per row from per-tile (value, index) pairs or from plain logits; also written to tables[..].pred
+hipError_t sp_launch_argmax_rows(bool pairs, const float* part, int n_items, const FwdBatch& b, ReqTables* tables,
+                                 int* pred_out /*nullable*/, float* max_out /*nullable*/, hipStream_t st);
 hipError_t sp_launch_silu_mul(int dtype, const float* gu, void* act, int M, int F, hipStream_t st);
 hipError_t sp_launch_finish(int dtype, const float* h, const float* part, int S, size_t part_stride, void* out,
                             int M, int d, hipStream_t st);
@@ -50,6 +57,8 @@ hipError_t sp_launch_gemm_simple(int dtype, const void* X, const void* W, float*
 hipError_t sp_launch_gemm_bf16(const bf16_t* X, const bf16_t* W, bool packed, float* out, int M, int N, int K,
                                int max_split, size_t part_capacity_floats, int* S_out, hipStream_t st);
 // act[m][f] = silu(X Wg^T) * (X Wu^T), W = [gate rows ; up rows]
+hipError_t sp_launch_gemm_argmax_bf16(const bf16_t* X, const bf16_t* W, bool packed, float* pairs, int M, int V, int K,
+                                      size_t pair_capacity_floats, int* tiles_out, hipStream_t st);
 hipError_t sp_launch_gemm_gateup_bf16(const bf16_t* X, const bf16_t* W, bool packed, bf16_t* act, int M, int F,
                                       int K, hipStream_t st);
 // Many rows (M > 128): workgroups of 128 rows x 256 columns, weights kept in registers per wave.

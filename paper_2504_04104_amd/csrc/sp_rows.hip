@@ -168,6 +168,51 @@ __global__ void k_finish(const float* h, const float* part, int S, size_t part_s
     Vec4<T>::st(out + i, *reinterpret_cast<const f32x4_t*>(h + i) + fold4(part + i, S, part_stride));
 }
 
+// Top-1 token of each row (Sec. 3.3.3) from either the per-tile (value, index) pairs the
+// output-head kernel left (PAIRS) or plain logits [rows][n_items]; the lowest index among
+// equal maxima.  Also stores it as the node's prediction in the request's tables.
+template <bool PAIRS>
+__global__ void __launch_bounds__(256) k_argmax_rows(const float* part, int n_items, FwdBatch b, ReqTables* tables,
+                                                      int* pred_out, float* max_out) {
+  __shared__ float s_v[4];
+  __shared__ int s_i[4];
+  const int row = blockIdx.x;
+  float bv = -INFINITY;
+  int bi = 0x7fffffff;
+  for (int t = threadIdx.x; t < n_items; t += blockDim.x) {
+    float v;
+    int i;
+    if (PAIRS) {
+      const float* p = part + ((size_t)row * n_items + t) * 2;
+      v = p[0];
+      i = reinterpret_cast<const int*>(p)[1];
+    } else {
+      v = part[(size_t)row * n_items + t];
+      i = t;
+    }
+    if (v > bv || (v == bv && i < bi)) { bv = v; bi = i; }
+  }
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) {
+    const float ov = __shfl_xor(bv, off, 64);
+    const int oi = __shfl_xor(bi, off, 64);
+    if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }
+  }
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  if (lane == 0) { s_v[wave] = bv; s_i[wave] = bi; }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+#pragma unroll
+    for (int w = 1; w < 4; ++w)
+      if (s_v[w] > bv || (s_v[w] == bv && s_i[w] < bi)) { bv = s_v[w]; bi = s_i[w]; }
+    if (pred_out) pred_out[row] = bi;
+    if (max_out) max_out[row] = bv;
+    int seg = 0;
+    while (seg + 1 < b.n_req && row >= b.row0[seg + 1]) ++seg;
+    tables[b.req[seg]].pred[b.first[seg] + (row - b.row0[seg])] = bi;
+  }
+}
+
 // ---- launchers -------------------------------------------------------------------
 static inline int grid_for(size_t n, int block, int cap = 4096) {
   size_t g = (n + block - 1) / block;
@@ -200,6 +245,13 @@ hipError_t sp_launch_add_norm(int dtype, float* h, const float* part, int S, siz
     hipLaunchKernelGGL((k_add_norm<bf16_t, false>), dim3(M), dim3(1024), 0, st, h, part, S, part_stride,
                        (const bf16_t*)gain, (bf16_t*)xn, d, eps, nullptr, none, nullptr, nullptr, nullptr, nullptr, 0,
                        0.f);
+  return hipGetLastError();
+}
+
+hipError_t sp_launch_argmax_rows(bool pairs, const float* part, int n_items, const FwdBatch& b, ReqTables* tables,
+                                 int* pred_out, float* max_out, hipStream_t st) {
+  if (pairs) hipLaunchKernelGGL(k_argmax_rows<true>, dim3(b.n_rows), dim3(256), 0, st, part, n_items, b, tables, pred_out, max_out);
+  else hipLaunchKernelGGL(k_argmax_rows<false>, dim3(b.n_rows), dim3(256), 0, st, part, n_items, b, tables, pred_out, max_out);
   return hipGetLastError();
 }
 

@@ -22,20 +22,20 @@ __global__ void k_tables_clear(ReqMeta* meta, ReqTables* tables, int n_req) {
   if (r >= n_req) return;
   ReqTables& t = tables[r];
   for (int i = threadIdx.x; i < SP_T; i += blockDim.x) {
-    t.parent[i] = -1; t.depth[i] = 0; t.token[i] = 0; t.prob[i] = 0.f;
+    t.parent[i] = -1; t.depth[i] = 0; t.token[i] = 0; t.prob[i] = 0.f; t.pred[i] = -1;
     for (int w = 0; w < SP_W; ++w) t.anc[i][w] = 0ull;
     t.kv_src[i] = 0; t.tab_new[i] = -1;
   }
   if (threadIdx.x == 0) {
     t.pend_n_kv_keep = 0; t.pend_first_moved = 0; t.pend_P_old = 0; t.pend_T_old = 0;
-    ReqMeta m; m.base = 0; m.cap = 0; m.P = 0; m.T = 0; m.pad = 0;
+    ReqMeta m; m.base = 0; m.cap = 0; m.P = 0; m.T = 0; m.root_pred = -1;
     meta[r] = m;
   }
 }
 
 __global__ void k_request_init(ReqMeta* meta, ReqTables* tables, int req, long long base, int cap, int P) {
   if (threadIdx.x == 0) {
-    ReqMeta m; m.base = base; m.cap = cap; m.P = P; m.T = 0; m.pad = 0;
+    ReqMeta m; m.base = base; m.cap = cap; m.P = P; m.T = 0; m.root_pred = -1;
     meta[req] = m;
     ReqTables& t = tables[req];
     t.pend_n_kv_keep = 0; t.pend_first_moved = 0; t.pend_P_old = P; t.pend_T_old = 0;
@@ -81,6 +81,7 @@ __global__ void __launch_bounds__(SP_T) k_tree_insert(ReqMeta* meta, ReqTables* 
     t.depth[self] = dep;
     t.token[self] = a.token[k];
     t.prob[self] = a.prob[k];
+    t.pred[self] = -1;
 #pragma unroll
     for (int w = 0; w < SP_W; ++w) t.anc[self][w] = bits[w];
   }
@@ -95,7 +96,7 @@ __global__ void __launch_bounds__(SP_T) k_tree_prune(ReqMeta* meta, ReqTables* t
   const int mode = b.mode[item];
   if (mode < 0) return;
   const int req = b.req[item];
-  const int r = b.node[item];
+  const int r = mode == 2 ? 0 : b.node[item];        // mode 2 (clear) names no node
   ReqTables& t = tables[req];
   const int T = meta[req].T;
   const int P = meta[req].P;
@@ -107,19 +108,20 @@ __global__ void __launch_bounds__(SP_T) k_tree_prune(ReqMeta* meta, ReqTables* t
   if (tid < SP_W) s_path[tid] = t.anc[r][tid];
   const bool live = tid < T;
   unsigned long long my[SP_W] = {0ull, 0ull, 0ull, 0ull};
-  int par = -1, dep = 0, tok = 0;
+  int par = -1, dep = 0, tok = 0, prd = -1;
   float prb = 0.f;
   if (live) {
 #pragma unroll
     for (int w = 0; w < SP_W; ++w) my[w] = t.anc[tid][w];
-    par = t.parent[tid]; dep = t.depth[tid]; tok = t.token[tid]; prb = t.prob[tid];
+    par = t.parent[tid]; dep = t.depth[tid]; tok = t.token[tid]; prb = t.prob[tid]; prd = t.pred[tid];
   }
   __syncthreads();
   const bool in_col = live && test_bit(my, r);                               // tid is r or below r
   const bool on_path = live && ((s_path[tid >> 6] >> (tid & 63)) & 1ull);   // tid is r or above r
   bool keep_tab, keep_kv;
-  if (mode == 0) { keep_tab = in_col && tid != r; keep_kv = in_col || on_path; }
-  else           { keep_tab = live && !in_col;    keep_kv = keep_tab; }
+  if (mode == 0)      { keep_tab = in_col && tid != r; keep_kv = in_col || on_path; }
+  else if (mode == 1) { keep_tab = live && !in_col;    keep_kv = keep_tab; }
+  else                { keep_tab = false;              keep_kv = false; }       // clear: the root alone stays
 
   const unsigned long long bt = __ballot(keep_tab), bk = __ballot(keep_kv);
   if (lane == 0) { s_tab[wave] = bt; s_kv[wave] = bk; }
@@ -158,9 +160,12 @@ __global__ void __launch_bounds__(SP_T) k_tree_prune(ReqMeta* meta, ReqTables* t
     t.depth[pre_tab] = dep - n_commit;
     t.token[pre_tab] = tok;
     t.prob[pre_tab] = prb;
+    t.pred[pre_tab] = prd;
 #pragma unroll
     for (int w = 0; w < SP_W; ++w) t.anc[pre_tab][w] = nrow[w];
   }
+  // the accepted node is the new root: its prediction is what the next step verifies against
+  if (mode == 0 && tid == r) meta[req].root_pred = prd;
   if (keep_kv) t.kv_src[pre_kv] = (short)tid;
   t.tab_new[tid] = s_new[tid];
   if (tid == 0) {
@@ -263,6 +268,53 @@ hipError_t sp_launch_tree_insert(ReqMeta* meta, ReqTables* tables, int req, int 
                      n_new, a, g, first_slot);
   return hipGetLastError();
 }
+// -----------------------------------------------------------------------------
+// Verification of the root's successor (Algorithm 1, "verify new token"; top-1 rule of
+// Sec. 3.3.3): the verified node is the first child of the root whose token is the
+// model's token after the committed context; -1 if no child carries it (pipeline stall)
+// or the prediction is not known yet.  One workgroup per request, thread t = node t.
+struct MatchBatch {
+  int n;
+  int req[SP_BATCH];
+};
+
+__global__ void __launch_bounds__(SP_T) k_tree_match(const ReqMeta* meta, const ReqTables* tables, MatchBatch b,
+                                                      int* out) {
+  const int item = blockIdx.x;
+  const int req = b.req[item];
+  const ReqTables& t = tables[req];
+  const ReqMeta m = meta[req];
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  __shared__ int s_first[SP_W];
+  const bool hit = tid < m.T && m.root_pred >= 0 && t.parent[tid] == -1 && t.token[tid] == m.root_pred;
+  const unsigned long long bal = __ballot(hit);
+  if (lane == 0) s_first[wave] = bal ? wave * 64 + (__ffsll((long long)bal) - 1) : -1;
+  __syncthreads();
+  if (tid == 0) {
+    int node = -1;
+#pragma unroll
+    for (int w = SP_W - 1; w >= 0; --w) if (s_first[w] >= 0) node = s_first[w];
+    out[item] = node;
+  }
+}
+
+__global__ void k_set_root_pred(ReqMeta* meta, int req, int token) {
+  if (threadIdx.x == 0 && blockIdx.x == 0) meta[req].root_pred = token;
+}
+
+hipError_t sp_launch_tree_match(const ReqMeta* meta, const ReqTables* tables, int n, const int* reqs, int* out,
+                                hipStream_t st) {
+  MatchBatch b;
+  b.n = n;
+  for (int i = 0; i < n; ++i) b.req[i] = reqs[i];
+  hipLaunchKernelGGL(k_tree_match, dim3(n), dim3(SP_T), 0, st, meta, tables, b, out);
+  return hipGetLastError();
+}
+hipError_t sp_launch_set_root_pred(ReqMeta* meta, int req, int token, hipStream_t st) {
+  hipLaunchKernelGGL(k_set_root_pred, dim3(1), dim3(64), 0, st, meta, req, token);
+  return hipGetLastError();
+}
+
 hipError_t sp_launch_tree_prune(ReqMeta* meta, ReqTables* tables, const PruneBatch& b, hipStream_t st) {
   hipLaunchKernelGGL(k_tree_prune, dim3(b.n), dim3(SP_T), 0, st, meta, tables, b);
   return hipGetLastError();

@@ -6,6 +6,7 @@
     python -m paper_2504_04104_amd.measure --run c4           # streaming, prefix 32768, 1-8 nodes per step
     python -m paper_2504_04104_amd.measure --run c5           # 32 requests, ragged batch
     python -m paper_2504_04104_amd.measure --run compact      # batched prune + KV compaction, scaled
+    python -m paper_2504_04104_amd.measure --run verify       # last stage: output head (vocab 128256) + match
 
 Each run prints one JSON line.  These runs only time the HIP path (parity is the tests' job), so
 weights are drawn on the GPU (seeded N(0, 0.02)) instead of through the host generators; trees,
@@ -295,12 +296,62 @@ def run_compact(args):
     stage.close()
 
 
+def run_verify(args):
+    """Last-stage step on the 8B-shaped stage: forward of 64 nodes, output head over a vocabulary of
+    128256 with the top-1 token per node, match of the root's successor, accept, compaction."""
+    w = wl.CONFIGS["C2"]
+    sh, P, n = w.shape, w.prefix_len, w.n_nodes
+    V = 128256
+    layers = gpu_layers(sh, w.seed)
+    g = torch.Generator(device=DEV).manual_seed(w.seed + 1)
+    wv = (torch.randn(V, sh.d_model, generator=g, device=DEV, dtype=torch.float32) * 0.02).to(torch.bfloat16)
+    head = {"norm": torch.ones(sh.d_model, device=DEV, dtype=torch.bfloat16), "wvocab": sp.pack_matrix(wv)}
+    del wv
+    cap = P + 320
+    stage = sp.Stage(sh, layers, kv_slots=cap, max_batch_nodes=64, flags=sp.SP_FLAG_PACKED_WEIGHTS)
+    fill_kv(stage, w.seed)
+    par = wl.tree_branching(w.seed, n, w.max_children, w.max_levels)
+    roots = [i for i, p in enumerate(par) if p < 0]
+    tokens = list(range(1000, 1000 + n))
+    x = torch.randn(n, sh.d_model, device=DEV).to(torch.bfloat16)
+    y = torch.empty_like(x)
+    rn = list(range(n))
+
+    def head_only():
+        stage.verify_head(head, [0], [0], [n], y)
+
+    def step():
+        stage.request_init(0, 0, cap, P)
+        stage.set_root_pred(0, tokens[roots[0]])
+        stage.tree_insert(0, par, tokens)
+        stage.stage_forward([0], [0], [n], x, y)
+        stage.verify_head(head, [0], [0], [n], y)
+        node = stage.tree_match([0])[0]                      # waits for the stream: the host decides
+        stage.tree_prune(0, sp.SP_ACCEPT, node)
+        stage.kv_compact(0, y, rn)
+    t = timed(step, 20)
+    stage.request_init(0, 0, cap, P)
+    stage.tree_insert(0, par, tokens)
+    stage.stage_forward([0], [0], [n], x, y)
+    t_head = timed(head_only, 30)
+    hd_us, cnt = kernel_us(stage, head_only, B.K_VERIFY_HEAD)
+    hbytes = V * sh.d_model * 2
+    res = {"run": "verify", "workload": "last stage of the 8B shape: 4 layers + output head, vocab 128256, 64 nodes",
+           "ms_per_step": round(t * 1e3, 3), "tree_tokens_per_s": round(n / t, 1),
+           "head_call_us": round(t_head * 1e6, 1), "head_kernels_us": round(hd_us / cnt, 1),
+           "head_weights_MB": round(hbytes / 1e6, 1),
+           "head_GBps": round(hbytes / (hd_us / cnt * 1e-6) / 1e9, 1),
+           "head_hbm_frac": round(hbytes / (hd_us / cnt * 1e-6) / 1e9 / HBM_PEAK, 4)}
+    print(json.dumps(res))
+    stage.close()
+
+
 def main():
     ap = argparse.ArgumentParser()
-    ap.add_argument("--run", required=True, choices=["sweep", "c3", "c4", "c5", "compact"])
+    ap.add_argument("--run", required=True, choices=["sweep", "c3", "c4", "c5", "compact", "verify"])
     ap.add_argument("--steps", type=int, default=0)
     args = ap.parse_args()
-    {"sweep": run_sweep, "c3": run_c3, "c4": run_c4, "c5": run_c5, "compact": run_compact}[args.run](args)
+    {"sweep": run_sweep, "c3": run_c3, "c4": run_c4, "c5": run_c5, "compact": run_compact, "verify": run_verify}[args.run](args)
 
 
 if __name__ == "__main__":

@@ -30,8 +30,9 @@ class Pair:
     """A GPU stage and an oracle stage with identical weights and committed contexts."""
 
     def __init__(self, shape: wl.ModelShape, seed: int, prefixes: Dict[int, int], *, tree_room: int = 256 + 64,
-                 flags: int = 0, max_batch_nodes: int = 64, oracle: bool = True):
+                 flags: int = 0, max_batch_nodes: int = 64, oracle: bool = True, vocab: int = 0):
         self.shape, self.seed = shape, seed
+        self.vocab = vocab
         self.weights = [wl.layer_weights(shape, seed, l) for l in range(shape.n_layers)]
         layers = [sp.pack_layer_weights(w, shape.dtype) for w in self.weights]
         if flags & sp.SP_FLAG_PACKED_WEIGHTS:
@@ -47,6 +48,14 @@ class Pair:
         self.gpu = sp.Stage(shape, layers, kv_slots=off, max_requests=n_req, max_batch_nodes=max_batch_nodes,
                             flags=flags)
         self.ora = StageOracle(shape, self.weights) if oracle else None
+        if vocab:
+            # output head of the last stage, same numbers on both sides
+            self.head_np = wl.head_weights(shape, seed, vocab)
+            td = torch.bfloat16 if shape.dtype == "bf16" else torch.float32
+            wv = torch.from_numpy(self.head_np["wvocab"]).to("cuda:0", td).contiguous()
+            if flags & sp.SP_FLAG_PACKED_WEIGHTS:
+                wv = sp.pack_matrix(wv)
+            self.head = {"norm": torch.from_numpy(self.head_np["norm"]).to("cuda:0", td).contiguous(), "wvocab": wv}
         for r, P in prefixes.items():
             pk, pv = zip(*[wl.prefix_kv(shape, seed, l, P, req=r) for l in range(shape.n_layers)])
             for l in range(shape.n_layers):
@@ -75,6 +84,38 @@ class Pair:
             ref = np.concatenate(outs) if outs else np.zeros_like(x, dtype=np.float64)
         return y, ref
 
+    def verify_head(self, reqs: Sequence[int], firsts: Sequence[int], counts: Sequence[int], y_dev: torch.Tensor,
+                    tol: float):
+        """Output head + top-1 on both sides, the oracle fed with the GPU's own rows so that only the
+        head is compared.  A row passes if the GPU's token is the oracle's, or if the oracle's logit of
+        the GPU's token is within `tol` (relative to the largest |logit|) of the oracle's maximum: the
+        GPU decides in bf16/fp32 arithmetic, the oracle in float64, and near-ties may fall either way.
+        The oracle's state then takes the GPU's decision, as a real last stage would.
+        Returns (gpu predictions, number of rows decided differently)."""
+        pred, mx = self.gpu.verify_head(self.head, reqs, firsts, counts, y_dev, want_max=True)
+        pred = pred.cpu().numpy().astype(np.int64)
+        mx = mx.cpu().numpy().astype(np.float64)
+        rows = to_np(y_dev).astype(np.float64)
+        row, differ = 0, 0
+        for r, f, n in zip(reqs, firsts, counts):
+            if not n:
+                continue
+            want, logits = self.ora.verify_head(r, f, rows[row:row + n], self.head_np["norm"], self.head_np["wvocab"])
+            scale = np.max(np.abs(logits))
+            for i in range(n):
+                g = int(pred[row + i])
+                assert 0 <= g < self.vocab
+                top = logits[i].max()
+                assert logits[i, g] >= top - tol * scale, ("token far from the maximum", r, f + i, g, int(want[i]))
+                assert abs(mx[row + i] - logits[i, g]) <= tol * scale, ("winning logit", r, f + i)
+                if g != int(want[i]):
+                    differ += 1
+                    # both are maxima up to the tolerance; the lower index must win an exact tie
+                    assert not (logits[i, g] == top and g > int(want[i]))
+                    self.ora.req[r].pred[f + 1 + i] = g
+            row += n
+        return pred, differ
+
     def tree_region(self, req: int, P: int, n: int) -> torch.Tensor:
         """Raw slab rows of tree slots [P, P+n): [layer, K|V, head, n, d_head] (a copy)."""
         b = self.base[req]
@@ -91,6 +132,8 @@ class Pair:
         assert np.array_equal(v["token"], tok)
         assert np.array_equal(v["prob"].view(np.uint32), prob.view(np.uint32))
         assert np.array_equal(v["M"], M)
+        assert np.array_equal(v["pred"], st.pred[1:]), (v["pred"], st.pred[1:])
+        assert v["root_pred"] == st.pred[0]
         assert self.gpu.request_info(req)[:2] == (st.P, len(par))
 
     def check_kv(self, req: int, tol: float):
@@ -116,7 +159,8 @@ class Pair:
         before = self.tree_region(req, P_old, T_old)
         untouched = self.gpu.kv_view()[:, :, :, self.base[req]:self.base[req] + P_old, :].clone()
         live, commit = self.gpu.tree_prune(req, mode, node)
-        pr = self.ora.accept(req, node) if mode == sp.SP_ACCEPT else self.ora.drop(req, node)
+        pr = (self.ora.accept(req, node) if mode == sp.SP_ACCEPT else
+              self.ora.drop(req, node) if mode == sp.SP_DROP else self.ora.clear(req))
         assert commit == pr.n_commit and live == st.tree.n - 1
         xg = None
         if x_rows is not None:

@@ -50,5 +50,8 @@ def test_query_sizes_is_host_arithmetic():
 
 
 def test_struct_layouts_match_the_header():
-    assert C.sizeof(binding.sp_tree_view) == 8 + 4 * 4 * 256 + 8 * 4 * 256
+    # counters, five 4-byte columns, the bitmask rows, the root's prediction + padding to 8
+    assert C.sizeof(binding.sp_tree_view) == 8 + 5 * 4 * 256 + 8 * 4 * 256 + 8
+    assert binding.sp_tree_view.pred.offset == 8 + 4 * 4 * 256 + 8 * 4 * 256
+    assert C.sizeof(binding.sp_head_weights) == 24
     assert C.sizeof(binding.sp_config) == 64

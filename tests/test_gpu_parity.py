@@ -237,6 +237,126 @@ def test_wide_batch(packed, batch):
     pair.close()
 
 
+# ---------------------------------------------------------------------------------------
+# verification on the last stage
+@pytest.mark.parametrize("flags", [0, sp.SP_FLAG_PACKED_WEIGHTS, sp.SP_FLAG_SIMPLE_KERNELS],
+                         ids=["mfma", "mfma_packed", "simple"])
+def test_verify_head_bf16(flags):
+    """Output head + top-1 token on tree nodes of two requests, bf16; vocabulary of 1088 = 17 tiles."""
+    shape = MINI_BF16
+    pair = Pair(shape, 21, {0: 40, 1: 75}, flags=flags, vocab=1088)
+    counts = [37, 21]
+    for r, n in enumerate(counts):
+        pair.insert(r, wl.tree_uniform_parents(21, n, 8, name=("v", r)), tokens=list(range(100 * r, 100 * r + n)))
+    x = wl.hidden_rows(shape, 21, ("v",), sum(counts))
+    y = pair.gpu.stage_forward([0, 1], [0, 0], counts, to_dev(x, pair.gpu))
+    for r, n, row0 in ((0, counts[0], 0), (1, counts[1], counts[0])):       # oracle state: forward as well
+        pair.ora.stage_forward(r, 0, x[row0:row0 + n])
+    pred, differ = pair.verify_head([0, 1], [0, 0], counts, y, TOL["bf16"])
+    say("verify head rows decided differently:", differ, "of", sum(counts))
+    assert differ <= 1
+    assert len(set(pred.tolist())) > 5                                     # not a constant
+    for r in (0, 1):
+        pair.check_tables(r)
+    # a partial range of one request: rows are its nodes 5..14
+    y1 = y[5:15].contiguous()
+    pred2, _ = pair.verify_head([0], [5], [10], y1, TOL["bf16"])
+    assert np.array_equal(pred2, pred[5:15])
+    pair.close()
+
+
+def test_verify_head_f32_odd_vocab():
+    """fp32 config, vocabulary that is no multiple of anything: the plain kernels and full logits."""
+    pair = Pair(MINI_F32, 22, {0: 33}, vocab=97)
+    n = 29
+    pair.insert(0, wl.tree_uniform_parents(22, n, 6, name=("v",)), tokens=list(range(n)))
+    x = wl.hidden_rows(MINI_F32, 22, ("v",), n)
+    y = pair.gpu.stage_forward([0], [0], [n], to_dev(x, pair.gpu))
+    pair.ora.stage_forward(0, 0, x)
+    pred, differ = pair.verify_head([0], [0], [n], y, TOL["f32"])
+    assert differ == 0
+    pair.check_tables(0)
+    pair.close()
+
+
+def test_verify_head_many_rows_and_order_error():
+    """More than 64 rows (two passes of the row tiles) and the error for a node that was not forwarded."""
+    shape = MINI_GQA4
+    pair = Pair(shape, 23, {0: 50}, max_batch_nodes=128, vocab=640)
+    n = 100
+    pair.insert(0, wl.tree_uniform_parents(23, n, 10, name=("v",)), tokens=list(range(n)))
+    x = wl.hidden_rows(shape, 23, ("v",), n)
+    with pytest.raises(sp.SpError) as ei:
+        pair.gpu.verify_head(pair.head, [0], [0], [n], to_dev(x, pair.gpu))
+    assert ei.value.status == -6                                           # SP_E_ORDER
+    y = pair.gpu.stage_forward([0], [0], [n], to_dev(x, pair.gpu))
+    pair.ora.stage_forward(0, 0, x)
+    pred, differ = pair.verify_head([0], [0], [n], y, TOL["bf16"])
+    assert differ <= 1
+    pair.check_tables(0)
+    pair.close()
+
+
+@pytest.mark.parametrize("shape,flags,tol", [(MINI_F32, 0, "f32"), (MINI_BF16, sp.SP_FLAG_PACKED_WEIGHTS, "bf16")],
+                         ids=["f32", "bf16_packed"])
+def test_verified_decoding_loop(shape, flags, tol):
+    """Insert a level, forward, predict, match the root's successor, accept or stall -- the loop of
+    Algorithm 1 with the stage as the whole model -- on the GPU and on the oracle side by side.  The
+    guesses hold the right token about two times in three, so hits, misses (SP_CLEAR + the true token
+    as a level of its own) and the hand-over of the accepted node's prediction to the root all occur."""
+    V = 128
+    pair = Pair(shape, 24, {0: 12}, tree_room=300, vocab=V)
+    emb = wl.embedding_table(shape, 24, V)
+    rs = np.random.RandomState(24)
+    pair.gpu.set_root_pred(0, 17)
+    pair.ora.set_root_pred(0, 17)
+    hits = misses = 0
+    emitted = []
+    for step in range(12):
+        v = pair.gpu.tree_read(0)
+        par, tok, n = v["parent"], v["token"], v["n_live"]
+        leaves = [k for k in range(n) if k not in set(par.tolist())] if n else [-1]
+        parents, tokens = [], []
+        for leaf in leaves:
+            known = int(v["pred"][leaf]) if leaf >= 0 else int(v["root_pred"])
+            guesses = [known] if rs.rand() < 0.67 else []
+            while len(guesses) < 3:
+                g = int(rs.randint(V))
+                if g != known and g not in guesses:
+                    guesses.append(g)
+            rs.shuffle(guesses)
+            parents += [leaf] * 3
+            tokens += guesses
+        if n + len(parents) > 200:
+            break
+        first = pair.insert(0, parents, tokens)
+        x = emb[tokens]
+        y = pair.gpu.stage_forward([0], [first], [len(tokens)], to_dev(x, pair.gpu))
+        pair.ora.stage_forward(0, first, x)
+        pair.verify_head([0], [first], [len(tokens)], y, TOL[tol])
+        pair.check_tables(0)
+        node = pair.gpu.tree_match([0])[0]
+        assert node == pair.ora.match(0)
+        want = int(pair.ora.req[0].pred[0])
+        emitted.append(want)
+        if node >= 0:
+            hits += 1
+            pair.prune(0, sp.SP_ACCEPT, node)
+        else:
+            misses += 1
+            pair.prune(0, sp.SP_CLEAR, 0)
+            k = pair.insert(0, [-1], [want])
+            y1 = pair.gpu.stage_forward([0], [k], [1], to_dev(emb[[want]], pair.gpu))
+            pair.ora.stage_forward(0, k, emb[[want]])
+            pair.verify_head([0], [k], [1], y1, TOL[tol])
+            pair.prune(0, sp.SP_ACCEPT, k)
+        assert pair.gpu.tree_read(0)["root_pred"] == pair.ora.req[0].pred[0]
+    say("verified decoding: hits", hits, "misses", misses, "tokens", emitted)
+    assert hits >= 3 and misses >= 1
+    assert pair.gpu.request_info(0)[0] == 12 + len(emitted)
+    pair.close()
+
+
 def test_error_codes():
     pair = Pair(MINI_F32, 17, {0: 10}, tree_room=30, oracle=False)
     g = pair.gpu
