@@ -237,6 +237,21 @@ int sp_tree_prune_batch(sp_stage* stage, int32_t n, const int32_t* req_ids, cons
                         int32_t* n_commit_out /*nullable*/, sp_stream stream);
 int sp_kv_compact_batch(sp_stage* stage, int32_t n, const int32_t* req_ids, sp_stream stream);
 
+/* Fixed-width expansion of the tree bottom (Sec. 3.4, "Fixed-width tree"): for each of the
+ * n_bottom nodes bottom_nodes[] (host; live nodes in ascending order, or the single entry -1
+ * for the root of an empty tree) the token source proposes k candidates, cand_tokens /
+ * cand_probs (device, [n_bottom][k]; a negative token marks an absent candidate).  A
+ * candidate's cumulative probability is its own probability times the probabilities stored in
+ * the tables for the bottom node and its ancestors (float32, multiplied from the root
+ * downwards).  The w candidates with the highest cumulative probability are kept -- an earlier
+ * candidate wins a tie -- and written in parent order, ready for sp_tree_insert:
+ * out_parents / out_tokens / out_probs (device, room for w entries) and *out_count (device).
+ * n_bottom * k <= 4096 and w <= 256, else SP_E_CAPACITY.  Asynchronous on `stream`. */
+int sp_tree_expand(sp_stage* stage, int32_t req, int32_t n_bottom, const int32_t* bottom_nodes /*host*/,
+                   int32_t k, const int32_t* cand_tokens /*device*/, const float* cand_probs /*device*/,
+                   int32_t w, int32_t* out_parents /*device*/, int32_t* out_tokens /*device*/,
+                   float* out_probs /*device*/, int32_t* out_count /*device*/, sp_stream stream);
+
 /* ---- verification on the last stage (Algorithm 1, "verify new token"; Sec. 3.3.3) ----- */
 
 /* Next-token prediction of tree nodes from their outputs of the last decoder layer:

@@ -97,6 +97,7 @@ def load_library(path: Optional[str] = None) -> C.CDLL:
         "sp_stage_verify_head": [vp, C.POINTER(sp_head_weights), C.c_int32, i32p, i32p, i32p, vp, vp, vp, vp],
         "sp_request_set_root_pred": [vp, C.c_int32, C.c_int32, vp],
         "sp_tree_match": [vp, C.c_int32, i32p, vp, i32p, vp],
+        "sp_tree_expand": [vp, C.c_int32, C.c_int32, i32p, C.c_int32, vp, vp, C.c_int32, vp, vp, vp, vp, vp],
         "sp_tree_insert": [vp, C.c_int32, C.c_int32, i32p, i32p, f32p, i32p, vp],
         "sp_stage_forward": [vp, C.c_int32, i32p, i32p, i32p, vp, vp, vp],
         "sp_tree_prune": [vp, C.c_int32, C.c_int32, C.c_int32, i32p, i32p, vp],
@@ -293,6 +294,25 @@ class Stage:
                                              pred.data_ptr(), mx.data_ptr() if want_max else None, self._stream()),
                "sp_stage_verify_head")
         return (pred[:rows], mx[:rows]) if want_max else pred[:rows]
+
+    def tree_expand(self, req: int, bottom_nodes: Sequence[int], cand_tokens, cand_probs, w: int):
+        """cand_tokens (int32) / cand_probs (float32): device tensors [len(bottom_nodes), k].  Returns the
+        selected level as host lists (parents, tokens, probs), ready for tree_insert; waits for the stream."""
+        import torch
+        ba, bp = _i32(bottom_nodes)
+        assert cand_tokens.is_contiguous() and cand_tokens.dtype == torch.int32
+        assert cand_probs.is_contiguous() and cand_probs.dtype == torch.float32
+        k = int(cand_tokens.shape[1])
+        room = max(w, 1)
+        op = torch.empty(room, dtype=torch.int32, device=self.device)
+        ot = torch.empty(room, dtype=torch.int32, device=self.device)
+        oq = torch.empty(room, dtype=torch.float32, device=self.device)
+        oc = torch.zeros(1, dtype=torch.int32, device=self.device)
+        _check(self.lib.sp_tree_expand(self.handle, req, len(ba), bp, k, cand_tokens.data_ptr(), cand_probs.data_ptr(),
+                                       w, op.data_ptr(), ot.data_ptr(), oq.data_ptr(), oc.data_ptr(), self._stream()),
+               "sp_tree_expand")
+        n = int(oc.item())
+        return op[:n].tolist(), ot[:n].tolist(), oq[:n].tolist()
 
     def set_root_pred(self, req: int, token: int):
         _check(self.lib.sp_request_set_root_pred(self.handle, req, token, self._stream()), "sp_request_set_root_pred")

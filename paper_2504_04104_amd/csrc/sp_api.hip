@@ -678,6 +678,30 @@ int sp_stage_verify_head(sp_stage* s, const sp_head_weights* head, int32_t n_req
   return e == hipSuccess ? SP_OK : hip_fail(s, e);
 }
 
+int sp_tree_expand(sp_stage* s, int32_t req, int32_t n_bottom, const int32_t* bottom_nodes, int32_t k,
+                   const int32_t* cand_tokens, const float* cand_probs, int32_t w, int32_t* out_parents,
+                   int32_t* out_tokens, float* out_probs, int32_t* out_count, sp_stream stream) {
+  if (!s || !bottom_nodes || !cand_tokens || !cand_probs || !out_parents || !out_tokens || !out_probs || !out_count)
+    return SP_E_INVALID;
+  HostReq* r = get_req(s, req);
+  if (!r) return SP_E_BAD_REQ;
+  if (r->pending) return SP_E_PENDING;
+  if (n_bottom < 1 || n_bottom > SP_T || k < 1 || w < 0) return SP_E_INVALID;
+  if ((long long)n_bottom * k > SP_EXPAND_MAX || w > SP_T) return SP_E_CAPACITY;
+  ExpandArgs a;
+  a.req = req; a.n_bottom = n_bottom; a.k = k; a.w = w;
+  for (int i = 0; i < n_bottom; ++i) {
+    const int b = bottom_nodes[i];
+    // -1 (the root) only alone; otherwise live nodes in ascending order
+    if (b == -1 ? n_bottom != 1 : (b < 0 || b >= r->T)) return SP_E_BAD_NODE;
+    if (i > 0 && b <= bottom_nodes[i - 1]) return SP_E_INVALID;
+    a.bottom[i] = (short)b;
+  }
+  hipError_t e = sp_launch_tree_expand(s->d_tables, a, cand_tokens, cand_probs, out_parents, out_tokens, out_probs,
+                                       out_count, (hipStream_t)stream);
+  return e == hipSuccess ? SP_OK : hip_fail(s, e);
+}
+
 int sp_tree_match(sp_stage* s, int32_t n, const int32_t* req_ids, int32_t* nodes_dev, int32_t* nodes_host,
                   sp_stream stream) {
   if (!s || !req_ids || !nodes_dev) return SP_E_INVALID;

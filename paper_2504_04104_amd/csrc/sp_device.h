@@ -81,6 +81,16 @@ struct PruneBatch {
   int node[SP_BATCH];
 };
 
+#define SP_EXPAND_MAX 4096   // candidates of one fixed-width expansion (bottom tokens x k)
+
+struct ExpandArgs {      // by value
+  int req;
+  int n_bottom;
+  int k;
+  int w;
+  short bottom[SP_T];    // node whose children are proposed, ascending; -1 = the root (empty tree)
+};
+
 struct RowList {         // source rows of an in-place row compaction, by value
   int n_keep;
   int first_moved;

@@ -22,6 +22,9 @@ hipError_t sp_launch_tree_prune(ReqMeta* meta, ReqTables* tables, const PruneBat
 // out[i] (device) = verified root child of request reqs[i], or -1
 hipError_t sp_launch_tree_match(const ReqMeta* meta, const ReqTables* tables, int n, const int* reqs, int* out,
                                 hipStream_t st);
+hipError_t sp_launch_tree_expand(const ReqTables* tables, const ExpandArgs& a, const int* cand_tok,
+                                 const float* cand_prob, int* out_parent, int* out_token, float* out_prob,
+                                 int* out_count, hipStream_t st);
 hipError_t sp_launch_set_root_pred(ReqMeta* meta, int req, int token, hipStream_t st);
 hipError_t sp_launch_kv_compact(const ReqMeta* meta, const ReqTables* tables, const PruneBatch& b, KvGeom g,
                                 hipStream_t st);

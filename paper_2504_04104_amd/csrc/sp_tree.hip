@@ -315,6 +315,75 @@ hipError_t sp_launch_set_root_pred(ReqMeta* meta, int req, int token, hipStream_
   return hipGetLastError();
 }
 
+// -----------------------------------------------------------------------------
+// Fixed-width expansion (Sec. 3.4 "Fixed-width tree"): candidate c = (bottom token c / k,
+// proposal c % k) has cumulative probability P[ancestors, root first] * P[bottom] * p(c),
+// multiplied in that order in float32.  The w largest are kept (an earlier candidate wins a
+// tie) and come out in candidate order, which is parent order (Sec. 3.2 "Layer appending").
+// One workgroup; a candidate's rank is the number of candidates that beat it.
+__global__ void __launch_bounds__(256) k_tree_expand(const ReqTables* tables, ExpandArgs a, const int* cand_tok,
+                                                      const float* cand_prob, int* out_parent, int* out_token,
+                                                      float* out_prob, int* out_count) {
+  __shared__ float s_key[SP_EXPAND_MAX];
+  __shared__ unsigned char s_sel[SP_EXPAND_MAX];
+  __shared__ int s_cnt[256];
+  const ReqTables& t = tables[a.req];
+  const int C = a.n_bottom * a.k;
+  const int tid = threadIdx.x;
+  for (int c = tid; c < C; c += 256) {
+    const int node = a.bottom[c / a.k];
+    float base = 1.f;
+    if (node >= 0) {
+#pragma unroll
+      for (int w = 0; w < SP_W; ++w) {
+        unsigned long long bits = t.anc[node][w];
+        while (bits) {                                  // ascending index = from the root downwards
+          const int j = w * 64 + __ffsll((long long)bits) - 1;
+          bits &= bits - 1;
+          base = base * t.prob[j];
+        }
+      }
+    }
+    s_key[c] = cand_tok[c] < 0 ? -1.f : base * cand_prob[c];
+  }
+  __syncthreads();
+  for (int c = tid; c < C; c += 256) {
+    const float key = s_key[c];
+    int rank = 0;
+    for (int o = 0; o < C; ++o) {
+      const float ko = s_key[o];
+      rank += (ko > key || (ko == key && o < c)) ? 1 : 0;
+    }
+    s_sel[c] = (key >= 0.f && rank < a.w) ? 1 : 0;
+  }
+  __syncthreads();
+  // ordered compaction: thread t owns candidates [t*per, (t+1)*per)
+  const int per = (C + 255) / 256;
+  const int lo = min(tid * per, C), hi = min(lo + per, C);
+  int mine = 0;
+  for (int c = lo; c < hi; ++c) mine += s_sel[c];
+  s_cnt[tid] = mine;
+  __syncthreads();
+  int pos = 0;
+  for (int i = 0; i < tid; ++i) pos += s_cnt[i];
+  for (int c = lo; c < hi; ++c) {
+    if (!s_sel[c]) continue;
+    out_parent[pos] = a.bottom[c / a.k];
+    out_token[pos] = cand_tok[c];
+    out_prob[pos] = cand_prob[c];
+    ++pos;
+  }
+  if (tid == 255) *out_count = pos;
+}
+
+hipError_t sp_launch_tree_expand(const ReqTables* tables, const ExpandArgs& a, const int* cand_tok,
+                                 const float* cand_prob, int* out_parent, int* out_token, float* out_prob,
+                                 int* out_count, hipStream_t st) {
+  hipLaunchKernelGGL(k_tree_expand, dim3(1), dim3(256), 0, st, tables, a, cand_tok, cand_prob, out_parent, out_token,
+                     out_prob, out_count);
+  return hipGetLastError();
+}
+
 hipError_t sp_launch_tree_prune(ReqMeta* meta, ReqTables* tables, const PruneBatch& b, hipStream_t st) {
   hipLaunchKernelGGL(k_tree_prune, dim3(b.n), dim3(SP_T), 0, st, meta, tables, b);
   return hipGetLastError();

@@ -335,9 +335,16 @@ def run_verify(args):
     stage.stage_forward([0], [0], [n], x, y)
     t_head = timed(head_only, 30)
     hd_us, cnt = kernel_us(stage, head_only, B.K_VERIFY_HEAD)
+    # fixed-width expansion of a full level: 64 bottom tokens x 16 candidates, width 64 (Sec. 4.3's setting)
+    stage.request_init(0, 0, cap, P)
+    stage.tree_insert(0, [-1] * 64, list(range(64)), [0.5] * 64)
+    ct = torch.randint(0, V, (64, 16), device=DEV, dtype=torch.int32)
+    cp = torch.rand(64, 16, device=DEV, dtype=torch.float32)
+    t_expand = timed(lambda: stage.tree_expand(0, list(range(64)), ct, cp, 64), 30)
     hbytes = V * sh.d_model * 2
     res = {"run": "verify", "workload": "last stage of the 8B shape: 4 layers + output head, vocab 128256, 64 nodes",
            "ms_per_step": round(t * 1e3, 3), "tree_tokens_per_s": round(n / t, 1),
+           "expand_call_us_with_host_copy": round(t_expand * 1e6, 1),
            "head_call_us": round(t_head * 1e6, 1), "head_kernels_us": round(hd_us / cnt, 1),
            "head_weights_MB": round(hbytes / 1e6, 1),
            "head_GBps": round(hbytes / (hd_us / cnt * 1e-6) / 1e9, 1),

@@ -357,6 +357,48 @@ def test_verified_decoding_loop(shape, flags, tol):
     pair.close()
 
 
+# ---------------------------------------------------------------------------------------
+# fixed-width expansion
+def test_fixed_width_expansion_matches_oracle():
+    """Grow a tree level by level with sp_tree_expand (k candidates per bottom token, the w most
+    likely by cumulative probability kept, parent order) and compare every level with the oracle's
+    selection, exactly: parents, tokens and probability bits.  Includes ties (probabilities drawn
+    from a small set), absent candidates, w larger than the candidate count and the 4096 limit."""
+    from oracle.expand import expand_fixed_width
+    pair = Pair(MINI_F32, 31, {0: 6}, tree_room=300, oracle=True)
+    g = pair.gpu
+    rs = np.random.RandomState(31)
+    bottom = [-1]
+    for step, (k, w) in enumerate([(5, 9), (8, 3), (16, 40), (4, 64), (32, 64), (7, 30)]):
+        nb = len(bottom)
+        toks = rs.randint(0, 5000, (nb, k)).astype(np.int32)
+        toks[rs.rand(nb, k) < 0.1] = -1                                    # absent candidates
+        prs = (rs.randint(1, 9, (nb, k)) / 8.0).astype(np.float32)         # few distinct values: many ties
+        if step % 2 == 0:
+            prs = rs.uniform(0.01, 1.0, (nb, k)).astype(np.float32)
+        par, _, _, prob, _ = pair.ora.req[0].tree.view()
+        want = expand_fixed_width(par, prob, bottom, toks, prs, w)
+        got = g.tree_expand(0, bottom, torch.from_numpy(toks).cuda(), torch.from_numpy(prs).cuda(), w)
+        assert got[0] == want[0] and got[1] == want[1], (step, got[:2], want[:2])
+        assert np.array_equal(np.asarray(got[2], np.float32).view(np.uint32), np.asarray(want[2], np.float32).view(np.uint32))
+        assert len(got[0]) <= w and got[0] == sorted(got[0])
+        if not got[0]:
+            break
+        first = pair.insert(0, got[0], got[1], got[2])
+        pair.check_tables(0)
+        bottom = list(range(first, first + len(got[0])))
+    # the documented limits
+    T = pair.gpu.request_info(0)[1]
+    with pytest.raises(sp.SpError) as ei:
+        g.tree_expand(0, list(range(min(T, 129))), torch.zeros((min(T, 129), 32), dtype=torch.int32).cuda(),
+                      torch.ones((min(T, 129), 32)).cuda(), 8)
+    assert ei.value.status == -2                                           # SP_E_CAPACITY: 129 * 32 > 4096
+    with pytest.raises(sp.SpError) as ei:
+        g.tree_expand(0, [3, 2], torch.zeros((2, 4), dtype=torch.int32).cuda(), torch.ones((2, 4)).cuda(), 2)
+    assert ei.value.status == -1                                           # not ascending
+    pair.close()
+
+
 def test_error_codes():
     pair = Pair(MINI_F32, 17, {0: 10}, tree_room=30, oracle=False)
     g = pair.gpu
