@@ -30,9 +30,12 @@ class Pair:
     """A GPU stage and an oracle stage with identical weights and committed contexts."""
 
     def __init__(self, shape: wl.ModelShape, seed: int, prefixes: Dict[int, int], *, tree_room: int = 256 + 64,
-                 flags: int = 0, max_batch_nodes: int = 64, oracle: bool = True, vocab: int = 0):
+                 flags: int = 0, max_batch_nodes: int = 64, oracle: bool = True, vocab: int = 0,
+                 oracle_reqs: Optional[Sequence[int]] = None):
         self.shape, self.seed = shape, seed
         self.vocab = vocab
+        # the float64 oracle may follow a sample of the requests only (large batches)
+        self.oracle_reqs = None if oracle_reqs is None else set(oracle_reqs)
         self.weights = [wl.layer_weights(shape, seed, l) for l in range(shape.n_layers)]
         layers = [sp.pack_layer_weights(w, shape.dtype) for w in self.weights]
         if flags & sp.SP_FLAG_PACKED_WEIGHTS:
@@ -61,13 +64,13 @@ class Pair:
             for l in range(shape.n_layers):
                 sp.write_prefix(self.gpu, l, self.base[r], pk[l], pv[l])
             self.gpu.request_init(r, self.base[r], self.cap[r], P)
-            if self.ora is not None:
+            if self.ora is not None and (self.oracle_reqs is None or r in self.oracle_reqs):
                 self.ora.request_init(r, pk, pv, self.cap[r])
 
     # -- the same call on both sides ------------------------------------------------
     def insert(self, req: int, parents: Sequence[int], tokens=None, probs=None) -> int:
         first = self.gpu.tree_insert(req, parents, tokens, probs)
-        if self.ora is not None:
+        if self.ora is not None and (self.oracle_reqs is None or req in self.oracle_reqs):
             assert self.ora.tree_insert(req, parents, tokens, probs) == first
         return first
 

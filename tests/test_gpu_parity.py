@@ -237,6 +237,62 @@ def test_wide_batch(packed, batch):
     pair.close()
 
 
+def test_c4_full_prefix_first_steps():
+    """Config 4's launch shape: the 8B-shaped layer dimensions, a committed context of 32768 tokens
+    (each KV head's range cut into 32 chunks over the chip, merged by the second kernel), 1-8 new
+    nodes per step, prune + compaction after each.  One layer and the first steps of the schedule:
+    the float64 oracle gathers 33 MB per (node, head) at this length."""
+    w = wl.CONFIGS["C4"]
+    shape = wl.scaled(w.shape, n_layers=1)
+    say("C4 prefix, 1 layer")
+    pair = Pair(shape, w.seed, {0: w.prefix_len}, tree_room=64, flags=sp.SP_FLAG_PACKED_WEIGHTS)
+    steps = wl.streaming_schedule(w.seed, 3, max_new=8, cap=256, p_accept=0.7)
+    worst = 0.0
+    for s_, st in enumerate(steps):
+        n = len(st.parents)
+        first = pair.insert(0, st.parents)
+        x = wl.hidden_rows(shape, w.seed, ("s", s_), n)
+        y, ref = pair.forward([0], [first], [n], x)
+        worst = max(worst, rel_err(y, ref))
+        say("C4 step", s_, "nodes", n, "rel err", rel_err(y, ref))
+        if st.prune is not None:
+            pair.prune(0, st.prune.mode, st.prune.node, x_rows=y, row_nodes=list(range(first, first + n)))
+        pair.check_kv(0, TOL["bf16"])
+    assert worst <= TOL["bf16"]
+    pair.close()
+
+
+def test_c5_full_batch_cold_step_sampled():
+    """Config 5's cold step at full size: 32 requests with contexts of 512-4096 tokens and trees of
+    8-32 nodes forwarded in one call (several hundred rows: the many-row projection kernels, ragged
+    attention segments).  The GPU runs the whole batch; the oracle follows a sample of the requests
+    (first, last, the largest and the smallest tree), whose rows are compared element by element.
+    One layer: the batch shape, not the depth, is what this case adds."""
+    w = wl.CONFIGS["C5"]
+    shape = wl.scaled(w.shape, n_layers=1)
+    reqs = wl.batch_requests(w.seed, n_req=32, p_lo=512, p_hi=4096, t_lo=8, t_hi=32, max_levels=6)
+    sizes = [len(r.parents) for r in reqs]
+    sample = sorted({0, 31, int(np.argmax(sizes)), int(np.argmin(sizes))})
+    total = sum(sizes)
+    say("C5 cold batch:", total, "rows; oracle follows requests", sample)
+    pair = Pair(shape, w.seed, {r.req: r.prefix_len for r in reqs}, tree_room=64, max_batch_nodes=total,
+                flags=sp.SP_FLAG_PACKED_WEIGHTS, oracle_reqs=sample)
+    for r in reqs:
+        pair.insert(r.req, r.parents)
+    x = wl.hidden_rows(shape, w.seed, ("cold",), total)
+    y = to_np(pair.gpu.stage_forward([r.req for r in reqs], [0] * 32, sizes, to_dev(x, pair.gpu)))
+    row0 = np.concatenate([[0], np.cumsum(sizes)])
+    for r in sample:
+        ref = pair.ora.stage_forward(r, 0, x[row0[r]:row0[r + 1]])
+        e = rel_err(y[row0[r]:row0[r + 1]], ref)
+        say("C5 request", r, "nodes", sizes[r], "prefix", reqs[r].prefix_len, "rel err", e)
+        assert e <= TOL["bf16"]
+        pair.check_kv(r, TOL["bf16"])
+        pair.check_tables(r)
+    assert np.isfinite(y).all()
+    pair.close()
+
+
 # ---------------------------------------------------------------------------------------
 # verification on the last stage
 @pytest.mark.parametrize("flags", [0, sp.SP_FLAG_PACKED_WEIGHTS, sp.SP_FLAG_SIMPLE_KERNELS],
