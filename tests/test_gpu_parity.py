@@ -81,7 +81,7 @@ def test_mini_f32_gqa_forward_in_pieces():
     pair.close()
 
 
-@pytest.mark.parametrize("n", [1, 15, 16, 17, 33, 64, 65, 128, 130, 255])
+@pytest.mark.parametrize("n", [1, 15, 16, 17, 33, 64, 65, 128, 130, 255, 256])
 def test_row_counts_across_tile_edges(n):
     """M below, at and above the 16-row MFMA tile and the 64-row block."""
     shape = MINI_BF16
@@ -93,6 +93,47 @@ def test_row_counts_across_tile_edges(n):
     e = rel_err(y, ref)
     say("n", n, "rel err", e)
     assert e <= TOL["bf16"]
+    pair.close()
+
+
+def test_empty_and_degenerate_calls():
+    """Calls that carry no work leave everything as it was and report success: an insert of no
+    nodes, a forward / output head over no nodes (alone and as an empty request inside a batch), a
+    compaction without hidden rows, an expansion of width 0; a one-node tree accepted (the tree
+    becomes empty, the context grows by one) and a chain accepted at its leaf (the whole chain is
+    committed)."""
+    shape = MINI_BF16
+    pair = Pair(shape, 19, {0: 30, 1: 17}, vocab=128)
+    g = pair.gpu
+    assert g.tree_insert(0, []) == 0
+    x0 = torch.empty((0, shape.d_model), dtype=torch.bfloat16, device="cuda:0")
+    assert g.stage_forward([0], [0], [0], x0).shape[0] == 0
+    assert g.verify_head(pair.head, [0], [0], [0], x0).shape[0] == 0
+    assert g.tree_expand(0, [-1], torch.tensor([[5, 6]], dtype=torch.int32).cuda(), torch.tensor([[.5, .5]]).cuda(), 0) == ([], [], [])
+    pair.check_tables(0)
+    # request 1 has no new nodes in a batched call
+    pair.insert(0, [-1, 0, 1])
+    x = wl.hidden_rows(shape, 19, ("e",), 3)
+    y, ref = pair.forward([0, 1], [0, 0], [3, 0], x)
+    assert rel_err(y, ref) <= TOL["bf16"]
+    # a chain accepted at its leaf: three tokens committed, nothing left
+    live, commit = g.tree_prune(0, sp.SP_ACCEPT, 2)
+    pair.ora.accept(0, 2)
+    assert (live, commit) == (0, 3)
+    g.kv_compact(0)
+    pair.check_tables(0)
+    assert g.request_info(0)[:2] == (33, 0)
+    # a one-node tree
+    pair.insert(1, [-1])
+    x1 = wl.hidden_rows(shape, 19, ("e1",), 1)
+    y, ref = pair.forward([1], [0], [1], x1)
+    assert rel_err(y, ref) <= TOL["bf16"]
+    pair.prune(1, sp.SP_ACCEPT, 0)
+    assert g.request_info(1)[:2] == (18, 0)
+    # clearing an empty tree is allowed and changes nothing
+    pair.prune(1, sp.SP_CLEAR, 0)
+    assert g.request_info(1)[:2] == (18, 0)
+    assert g.tree_match([0, 1]) == [-1, -1]
     pair.close()
 
 
