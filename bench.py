@@ -40,6 +40,8 @@ def main() -> int:
     ap.add_argument("--kernels", action="store_true", help="also time every kernel kind (extra passes)")
     ap.add_argument("--unpacked", action="store_true",
                     help="keep the weights row-major instead of the load-time MFMA-fragment re-layout")
+    ap.add_argument("--roofline-sample", type=int, default=5,
+                    help="bracket one gate/up launch in this many with HIP events (default 5)")
     ap.add_argument("--calib-copy", action="store_true",
                     help="first run three plain 1 GiB device copies (a known-size kernel that scales rocprofv3's "
                          "FETCH_SIZE / WRITE_SIZE counters)")
@@ -106,7 +108,10 @@ def main() -> int:
 
     # ---- timed region: K steps, with the dominant kernel bracketed by HIP events ----
     L = sh.n_layers
-    stage.profile_begin(B.K_GEMM_GATEUP, args.steps * L)
+    # one gate/up launch in `sample` is bracketed by HIP events: the events open a gap of several
+    # microseconds around the launch they bracket, so bracketing every launch would slow the step it times
+    sample = max(1, args.roofline_sample)
+    stage.profile_begin(B.K_GEMM_GATEUP, args.steps * L, every=sample)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     for _ in range(args.steps):

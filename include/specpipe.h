@@ -303,6 +303,10 @@ typedef enum sp_kernel_kind {
   SP_K_TREE_INSERT = 9, SP_K_NORM = 10, SP_K_ROPE_KV = 11, SP_K_VERIFY_HEAD = 12, SP_K_KIND_COUNT = 13
 } sp_kernel_kind;
 int sp_profile_begin(sp_stage* stage, int32_t kind, int32_t max_launches);
+/* After sp_profile_begin: bracket only one launch in `every` of that kind (the events
+ * themselves open a gap of a few microseconds around the launch they bracket, so a timed
+ * run samples instead of bracketing every launch). */
+int sp_profile_sample_every(sp_stage* stage, int32_t every);
 int sp_profile_end(sp_stage* stage, int32_t* n_launches, float* total_ms);
 
 const char* sp_strerror(int status);

@@ -107,6 +107,7 @@ def load_library(path: Optional[str] = None) -> C.CDLL:
         "sp_tree_read": [vp, C.c_int32, C.POINTER(sp_tree_view), vp],
         "sp_request_info": [vp, C.c_int32, i32p, i32p, i32p],
         "sp_profile_begin": [vp, C.c_int32, C.c_int32],
+        "sp_profile_sample_every": [vp, C.c_int32],
         "sp_profile_end": [vp, i32p, f32p],
         "sp_last_hip_error": [vp],
         "sp_version": [],
@@ -333,8 +334,10 @@ class Stage:
         _check(self.lib.sp_request_info(self.handle, req, C.byref(p), C.byref(t), C.byref(f)), "sp_request_info")
         return p.value, t.value, f.value
 
-    def profile_begin(self, kind: int, max_launches: int):
+    def profile_begin(self, kind: int, max_launches: int, every: int = 1):
         _check(self.lib.sp_profile_begin(self.handle, kind, max_launches), "sp_profile_begin")
+        if every > 1:
+            _check(self.lib.sp_profile_sample_every(self.handle, every), "sp_profile_sample_every")
 
     def profile_end(self):
         n, ms = C.c_int32(), C.c_float()

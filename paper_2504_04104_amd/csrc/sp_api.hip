@@ -108,6 +108,7 @@ struct sp_stage {
   int last_hip = 0;
   // profiling
   int prof_kind = 0, prof_max = 0, prof_n = 0;
+  int prof_every = 1, prof_seen = 0;   // bracket one launch in prof_every of the profiled kind
   std::vector<hipEvent_t> prof_ev;
 };
 
@@ -124,7 +125,8 @@ struct ProfScope {
   hipStream_t st;
   bool on;
   ProfScope(sp_stage* s_, int kind, hipStream_t st_) : s(s_), st(st_) {
-    on = (s->prof_kind == kind && s->prof_n < s->prof_max);
+    on = false;
+    if (s->prof_kind == kind && s->prof_n < s->prof_max) on = (s->prof_seen++ % s->prof_every) == 0;
     if (on) (void)hipEventRecord(s->prof_ev[2 * s->prof_n], st);
   }
   ~ProfScope() {
@@ -728,6 +730,14 @@ int sp_profile_begin(sp_stage* s, int32_t kind, int32_t max_launches) {
     s->prof_ev.push_back(ev);
   }
   s->prof_kind = kind; s->prof_max = max_launches; s->prof_n = 0;
+  s->prof_every = 1; s->prof_seen = 0;
+  return SP_OK;
+}
+
+int sp_profile_sample_every(sp_stage* s, int32_t every) {
+  if (!s || every < 1) return SP_E_INVALID;
+  s->prof_every = every;
+  s->prof_seen = 0;
   return SP_OK;
 }
 
