@@ -190,6 +190,15 @@ int sp_tree_insert(sp_stage* stage, int32_t req, int32_t n_new, const int32_t* p
                    const int32_t* tokens /*host, nullable*/, const float* probs /*host, nullable*/,
                    int32_t* first_index_out /*host, nullable*/, sp_stream stream);
 
+/* The same for several requests in one launch (dynamic batching, Sec. 4 "Implementation"):
+ * request req_ids[i] appends n_new[i] nodes; parents / tokens / probs hold the nodes of all
+ * requests back to back in that order; first_index_out[i] = index of request i's first new
+ * node.  Every request is validated before anything changes.  Requests must be distinct. */
+int sp_tree_insert_batch(sp_stage* stage, int32_t n_req, const int32_t* req_ids /*host*/,
+                         const int32_t* n_new /*host*/, const int32_t* parents /*host*/,
+                         const int32_t* tokens /*host, nullable*/, const float* probs /*host, nullable*/,
+                         int32_t* first_index_out /*host, nullable*/, sp_stream stream);
+
 /* Node-wise computation (Algorithm 1 lines 1-3): runs every layer of the stage on
  * nodes [first_node[i], first_node[i]+n_nodes[i]) of request req_ids[i], i < n_req,
  * under the tree mask: a node attends to its request's committed context and to

@@ -99,6 +99,7 @@ def load_library(path: Optional[str] = None) -> C.CDLL:
         "sp_tree_match": [vp, C.c_int32, i32p, vp, i32p, vp],
         "sp_tree_expand": [vp, C.c_int32, C.c_int32, i32p, C.c_int32, vp, vp, C.c_int32, vp, vp, vp, vp, vp],
         "sp_tree_insert": [vp, C.c_int32, C.c_int32, i32p, i32p, f32p, i32p, vp],
+        "sp_tree_insert_batch": [vp, C.c_int32, i32p, i32p, i32p, i32p, f32p, i32p, vp],
         "sp_stage_forward": [vp, C.c_int32, i32p, i32p, i32p, vp, vp, vp],
         "sp_tree_prune": [vp, C.c_int32, C.c_int32, C.c_int32, i32p, i32p, vp],
         "sp_kv_compact": [vp, C.c_int32, vp, C.c_int32, i32p, i32p, i32p, vp],
@@ -213,6 +214,24 @@ class Stage:
         _check(self.lib.sp_tree_insert(self.handle, req, len(pa), pp, tp, fp, C.byref(first), self._stream()),
                "sp_tree_insert")
         return first.value
+
+    def tree_insert_batch(self, req_ids: Sequence[int], parents_per_req: Sequence[Sequence[int]],
+                          tokens_per_req: Optional[Sequence[Sequence[int]]] = None,
+                          probs_per_req: Optional[Sequence[Sequence[float]]] = None) -> List[int]:
+        """One launch for the new nodes of several requests; returns each request's first new index."""
+        ra, rp = _i32(req_ids)
+        na, npn = _i32([len(p) for p in parents_per_req])
+        pa, pp = _i32([x for p in parents_per_req for x in p])
+        ta, tp = _i32([x for t in tokens_per_req for x in t]) if tokens_per_req is not None else (None, None)
+        qa = fp = None
+        if probs_per_req is not None:
+            qa = np.ascontiguousarray(np.asarray([x for q in probs_per_req for x in q], dtype=np.float32))
+            fp = qa.ctypes.data_as(C.POINTER(C.c_float))
+        first = np.zeros(max(len(ra), 1), dtype=np.int32)
+        _check(self.lib.sp_tree_insert_batch(self.handle, len(ra), rp, npn, pp, tp, fp,
+                                             first.ctypes.data_as(C.POINTER(C.c_int32)), self._stream()),
+               "sp_tree_insert_batch")
+        return [int(v) for v in first[:len(ra)]]
 
     def stage_forward(self, req_ids: Sequence[int], first_node: Sequence[int], n_nodes: Sequence[int], x_in, x_out=None):
         ra, rp = _i32(req_ids)

@@ -310,34 +310,72 @@ int sp_request_info(const sp_stage* s, int32_t req, int32_t* prefix_len, int32_t
   return SP_OK;
 }
 
+int sp_tree_insert_batch(sp_stage* s, int32_t n_req, const int32_t* req_ids, const int32_t* n_new,
+                         const int32_t* parents, const int32_t* tokens, const float* probs,
+                         int32_t* first_index_out, sp_stream stream) {
+  if (!s || !req_ids || !n_new) return SP_E_INVALID;
+  if (n_req < 0 || n_req > SP_MAX_BATCH_REQ) return SP_E_CAPACITY;
+  // validate everything before anything changes
+  int total = 0;
+  for (int i = 0; i < n_req; ++i) {
+    HostReq* r = get_req(s, req_ids[i]);
+    if (!r) return SP_E_BAD_REQ;
+    if (n_new[i] < 0) return SP_E_INVALID;
+    if (r->pending) return SP_E_PENDING;
+    for (int j = 0; j < i; ++j) if (req_ids[j] == req_ids[i]) return SP_E_INVALID;
+    if (r->T + n_new[i] > s->cfg.max_tree_nodes || r->P + r->T + n_new[i] > r->cap) return SP_E_CAPACITY;
+    if (n_new[i] > 0 && !parents) return SP_E_INVALID;
+    for (int k = 0; k < n_new[i]; ++k)
+      if (parents[total + k] < -1 || parents[total + k] >= r->T + k) return SP_E_BAD_PARENT;
+    total += n_new[i];
+  }
+  hipStream_t st = (hipStream_t)stream;
+  // launches of at most SP_T new nodes each (one launch in every case the configs produce)
+  InsertArgs a;
+  a.n_req = 0;
+  a.row0[0] = 0;
+  int row = 0;
+  auto flush = [&]() -> hipError_t {
+    if (a.n_req == 0) return hipSuccess;
+    ProfScope scope(s, SP_K_TREE_INSERT, st);
+    hipError_t e = sp_launch_tree_insert(s->d_meta, s->d_tables, a, s->geom, st);
+    a.n_req = 0;
+    a.row0[0] = 0;
+    return e;
+  };
+  for (int i = 0; i < n_req; ++i) {
+    HostReq& r = s->reqs[req_ids[i]];
+    if (first_index_out) first_index_out[i] = r.T;
+    const int n = n_new[i];
+    if (n > 0) {
+      if (a.row0[a.n_req] + n > SP_T) {
+        hipError_t e = flush();
+        if (e != hipSuccess) return hip_fail(s, e);
+      }
+      const int r0 = a.row0[a.n_req];
+      a.req[a.n_req] = (short)req_ids[i];
+      a.t0[a.n_req] = (short)r.T;
+      a.first_slot[a.n_req] = r.base + r.P + r.T;
+      for (int k = 0; k < n; ++k) {
+        a.parent[r0 + k] = (short)parents[row + k];
+        a.token[r0 + k] = tokens ? tokens[row + k] : 0;
+        a.prob[r0 + k] = probs ? probs[row + k] : 0.f;
+        r.parent[r.T + k] = (short)parents[row + k];
+        r.fwd[r.T + k] = 0;
+      }
+      r.T += n;
+      a.row0[++a.n_req] = (short)(r0 + n);
+    }
+    row += n;
+  }
+  hipError_t e = flush();
+  return e == hipSuccess ? SP_OK : hip_fail(s, e);
+}
+
 int sp_tree_insert(sp_stage* s, int32_t req, int32_t n_new, const int32_t* parents, const int32_t* tokens,
                    const float* probs, int32_t* first_index_out, sp_stream stream) {
   if (!s) return SP_E_INVALID;
-  HostReq* r = get_req(s, req);
-  if (!r) return SP_E_BAD_REQ;
-  if (n_new < 0 || (n_new > 0 && !parents)) return SP_E_INVALID;
-  if (r->pending) return SP_E_PENDING;
-  if (r->T + n_new > s->cfg.max_tree_nodes || r->P + r->T + n_new > r->cap) return SP_E_CAPACITY;
-  for (int k = 0; k < n_new; ++k)
-    if (parents[k] < -1 || parents[k] >= r->T + k) return SP_E_BAD_PARENT;
-  if (first_index_out) *first_index_out = r->T;
-  if (n_new == 0) return SP_OK;
-  InsertArgs a;
-  for (int k = 0; k < n_new; ++k) {
-    a.parent[k] = (short)parents[k];
-    a.token[k] = tokens ? tokens[k] : 0;
-    a.prob[k] = probs ? probs[k] : 0.f;
-  }
-  hipError_t e;
-  {
-    ProfScope scope(s, SP_K_TREE_INSERT, (hipStream_t)stream);
-    e = sp_launch_tree_insert(s->d_meta, s->d_tables, req, n_new, a, s->geom, r->base + r->P + r->T,
-                              (hipStream_t)stream);
-  }
-  if (e != hipSuccess) return hip_fail(s, e);
-  for (int k = 0; k < n_new; ++k) { r->parent[r->T + k] = (short)parents[k]; r->fwd[r->T + k] = 0; }
-  r->T += n_new;
-  return SP_OK;
+  return sp_tree_insert_batch(s, 1, &req, &n_new, parents, tokens, probs, first_index_out, stream);
 }
 
 int sp_stage_forward(sp_stage* s, int32_t n_req, const int32_t* req_ids, const int32_t* first_node,

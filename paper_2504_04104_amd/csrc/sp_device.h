@@ -67,8 +67,15 @@ struct FwdBatch {
   int row0[SP_BATCH];
 };
 
-// Arguments of one insert, passed by value.
+// Arguments of one insert launch, passed by value: up to SP_T new nodes spread over up to
+// SP_BATCH requests; request i owns entries [row0[i], row0[i+1]) and appends them after its
+// t0[i] live nodes, in cache slots first_slot[i]...
 struct InsertArgs {
+  int n_req;
+  short req[SP_BATCH];
+  short t0[SP_BATCH];
+  short row0[SP_BATCH + 1];
+  long long first_slot[SP_BATCH];
   short parent[SP_T];
   int token[SP_T];
   float prob[SP_T];

@@ -16,8 +16,7 @@ hipError_t sp_launch_tables_clear(ReqMeta* meta, ReqTables* tables, int n_req, h
 hipError_t sp_launch_request_init(ReqMeta* meta, ReqTables* tables, int req, long long base, int cap, int P,
                                   hipStream_t st);
 // first_slot: cache slot of the first new node (host mirror: base + prefix_len + n_live)
-hipError_t sp_launch_tree_insert(ReqMeta* meta, ReqTables* tables, int req, int n_new, const InsertArgs& a,
-                                 KvGeom g, long long first_slot, hipStream_t st);
+hipError_t sp_launch_tree_insert(ReqMeta* meta, ReqTables* tables, const InsertArgs& a, KvGeom g, hipStream_t st);
 hipError_t sp_launch_tree_prune(ReqMeta* meta, ReqTables* tables, const PruneBatch& b, hipStream_t st);
 // out[i] (device) = verified root child of request reqs[i], or -1
 hipError_t sp_launch_tree_match(const ReqMeta* meta, const ReqTables* tables, int n, const int* reqs, int* out,

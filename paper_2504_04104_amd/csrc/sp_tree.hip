@@ -42,33 +42,35 @@ __global__ void k_request_init(ReqMeta* meta, ReqTables* tables, int req, long l
   }
 }
 
-// Layer appending.  Block 0: thread k owns new node T0+k.  Its ancestor row is its own
-// bit, the bits of the parents it reaches inside this call, and the stored row of the
-// first parent that existed before the call (nothing if it reaches the root).
-// Blocks 1..: one per (layer, K|V, head) plane; they clear the new nodes' cache rows,
-// so that every slot below prefix_len + n_live always holds finite numbers (a masked
-// key still enters the matrix-core product with weight zero).
-__global__ void __launch_bounds__(SP_T) k_tree_insert(ReqMeta* meta, ReqTables* tables, int req, int n_new,
-                                                       InsertArgs a, KvGeom g, long long first_slot) {
+// Layer appending for the requests of a call (blockIdx.y).  Block x = 0: thread k owns the
+// request's new node T0+k.  Its ancestor row is its own bit, the bits of the parents it
+// reaches inside this call, and the stored row of the first parent that existed before the
+// call (nothing if it reaches the root).  Blocks x = 1..: one per (layer, K|V, head) plane;
+// they clear the new nodes' cache rows, so that every slot below prefix_len + n_live always
+// holds finite numbers (a masked key still enters the matrix-core product with weight zero).
+__global__ void __launch_bounds__(SP_T) k_tree_insert(ReqMeta* meta, ReqTables* tables, InsertArgs a, KvGeom g) {
+  const int item = blockIdx.y;
+  const int req = a.req[item];
+  const int r0 = a.row0[item], n_new = a.row0[item + 1] - r0;
   if (blockIdx.x > 0) {
     uint4* rows = reinterpret_cast<uint4*>(g.kv + (size_t)(blockIdx.x - 1) * g.plane_bytes +
-                                           (size_t)first_slot * g.row_bytes);
+                                           (size_t)a.first_slot[item] * g.row_bytes);
     const int n16 = n_new * (g.row_bytes >> 4);
     for (int i = threadIdx.x; i < n16; i += blockDim.x) rows[i] = make_uint4(0u, 0u, 0u, 0u);
     return;
   }
   ReqTables& t = tables[req];
-  const int T0 = meta[req].T;
+  const int T0 = a.t0[item];
   const int k = threadIdx.x;
   if (k < n_new) {
     unsigned long long bits[SP_W] = {0ull, 0ull, 0ull, 0ull};
     const int self = T0 + k;
     set_bit(bits, self);
-    int cur = a.parent[k];
+    int cur = a.parent[r0 + k];
     int up = 0;
     while (cur >= T0) {
       set_bit(bits, cur);
-      cur = a.parent[cur - T0];
+      cur = a.parent[r0 + cur - T0];
       ++up;
     }
     int dep = up;
@@ -77,15 +79,14 @@ __global__ void __launch_bounds__(SP_T) k_tree_insert(ReqMeta* meta, ReqTables* 
       for (int w = 0; w < SP_W; ++w) bits[w] |= t.anc[cur][w];
       dep = t.depth[cur] + up + 1;
     }
-    t.parent[self] = a.parent[k];
+    t.parent[self] = a.parent[r0 + k];
     t.depth[self] = dep;
-    t.token[self] = a.token[k];
-    t.prob[self] = a.prob[k];
+    t.token[self] = a.token[r0 + k];
+    t.prob[self] = a.prob[r0 + k];
     t.pred[self] = -1;
 #pragma unroll
     for (int w = 0; w < SP_W; ++w) t.anc[self][w] = bits[w];
   }
-  __syncthreads();
   if (threadIdx.x == 0) meta[req].T = T0 + n_new;
 }
 
@@ -262,10 +263,9 @@ hipError_t sp_launch_request_init(ReqMeta* meta, ReqTables* tables, int req, lon
   hipLaunchKernelGGL(k_request_init, dim3(1), dim3(64), 0, st, meta, tables, req, base, cap, P);
   return hipGetLastError();
 }
-hipError_t sp_launch_tree_insert(ReqMeta* meta, ReqTables* tables, int req, int n_new, const InsertArgs& a,
-                                 KvGeom g, long long first_slot, hipStream_t st) {
-  hipLaunchKernelGGL(k_tree_insert, dim3(1 + g.n_layers * 2 * g.n_kv_heads), dim3(SP_T), 0, st, meta, tables, req,
-                     n_new, a, g, first_slot);
+hipError_t sp_launch_tree_insert(ReqMeta* meta, ReqTables* tables, const InsertArgs& a, KvGeom g, hipStream_t st) {
+  hipLaunchKernelGGL(k_tree_insert, dim3(1 + g.n_layers * 2 * g.n_kv_heads, a.n_req), dim3(SP_T), 0, st, meta, tables,
+                     a, g);
   return hipGetLastError();
 }
 // -----------------------------------------------------------------------------

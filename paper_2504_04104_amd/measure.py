@@ -218,7 +218,7 @@ def run_c5(args):
     def cold():
         for r in reqs:
             stage.request_init(r.req, base[r.req], r.prefix_len + room, r.prefix_len)
-            stage.tree_insert(r.req, r.parents)
+        stage.tree_insert_batch(ids, [r.parents for r in reqs])
         stage.stage_forward(ids, [0] * len(reqs), [len(r.parents) for r in reqs], x, y)
 
     def steady():
@@ -228,12 +228,10 @@ def run_c5(args):
             nodes = [st.prune.node if st.prune else 0 for st in row]
             stage.tree_prune_batch(ids, modes, nodes)
             stage.kv_compact_batch([i for i, m in zip(ids, modes) if m >= 0])
-            firsts, counts, act = [], [], []
-            for r, st in zip(reqs, row):
-                if st.parents:
-                    firsts.append(stage.tree_insert(r.req, st.parents))
-                    counts.append(len(st.parents))
-                    act.append(r.req)
+            act = [r.req for r, st in zip(reqs, row) if st.parents]
+            new = [st.parents for st in row if st.parents]
+            counts = [len(p) for p in new]
+            firsts = stage.tree_insert_batch(act, new) if act else []
             if act:
                 n = sum(counts)
                 stage.stage_forward(act, firsts, counts, x[:n], y[:n])

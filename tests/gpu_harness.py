@@ -74,6 +74,18 @@ class Pair:
             assert self.ora.tree_insert(req, parents, tokens, probs) == first
         return first
 
+    def insert_batch(self, reqs: Sequence[int], parents_per_req, tokens_per_req=None, probs_per_req=None):
+        """One launch for several requests on the GPU; one by one on the oracle."""
+        firsts = self.gpu.tree_insert_batch(reqs, parents_per_req, tokens_per_req, probs_per_req)
+        if self.ora is not None:
+            for i, r in enumerate(reqs):
+                if self.oracle_reqs is None or r in self.oracle_reqs:
+                    f = self.ora.tree_insert(r, parents_per_req[i],
+                                             None if tokens_per_req is None else tokens_per_req[i],
+                                             None if probs_per_req is None else probs_per_req[i])
+                    assert f == firsts[i]
+        return firsts
+
     def forward(self, reqs: Sequence[int], firsts: Sequence[int], counts: Sequence[int], x: np.ndarray):
         """x: [sum counts, d] float32 (already rounded to the storage type).  Returns (gpu, oracle)."""
         y = to_np(self.gpu.stage_forward(reqs, firsts, counts, to_dev(x, self.gpu)))

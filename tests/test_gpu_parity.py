@@ -229,12 +229,15 @@ def test_ragged_batch_mini():
             after = pair.tree_region(r.req, P_old, int(keep.sum()))
             assert torch.equal(after.view(torch.uint8), reg.index_select(3, sel).contiguous().view(torch.uint8))
             pair.check_tables(r.req)
-        firsts, counts, act_ids = [], [], []
-        for r, st in zip(reqs, row):
-            if st.parents:
-                firsts.append(pair.insert(r.req, st.parents))
-                counts.append(len(st.parents))
-                act_ids.append(r.req)
+        # batched insert: one launch for all requests with new nodes (tokens and probabilities too)
+        act_ids = [r.req for r, st in zip(reqs, row) if st.parents]
+        new = [st.parents for st in row if st.parents]
+        counts = [len(p) for p in new]
+        toks = [[1000 * s + 10 * i + k for k in range(len(p))] for i, p in enumerate(new)]
+        prbs = [[(k + 1) / 64.0 for k in range(len(p))] for p in new]
+        firsts = pair.insert_batch(act_ids, new, toks, prbs) if act_ids else []
+        for rid in act_ids:
+            pair.check_tables(rid)
         if act_ids:
             x = wl.hidden_rows(shape, 16, ("b", s), sum(counts))
             y, ref = pair.forward(act_ids, firsts, counts, x)
@@ -318,8 +321,8 @@ def test_c5_full_batch_cold_step_sampled():
     say("C5 cold batch:", total, "rows; oracle follows requests", sample)
     pair = Pair(shape, w.seed, {r.req: r.prefix_len for r in reqs}, tree_room=64, max_batch_nodes=total,
                 flags=sp.SP_FLAG_PACKED_WEIGHTS, oracle_reqs=sample)
-    for r in reqs:
-        pair.insert(r.req, r.parents)
+    # 574 new nodes in one call: the library cuts it into launches of at most 256
+    pair.insert_batch([r.req for r in reqs], [r.parents for r in reqs])
     x = wl.hidden_rows(shape, w.seed, ("cold",), total)
     y = to_np(pair.gpu.stage_forward([r.req for r in reqs], [0] * 32, sizes, to_dev(x, pair.gpu)))
     row0 = np.concatenate([[0], np.cumsum(sizes)])
