@@ -75,6 +75,7 @@ typedef enum sp_prune_mode { SP_ACCEPT = 0, SP_DROP = 1, SP_CLEAR = 2 } sp_prune
 /* sp_config.flags */
 #define SP_FLAG_SIMPLE_KERNELS 1u   /* use the plain (non-MFMA) kernels for every step */
 #define SP_FLAG_PACKED_WEIGHTS 2u   /* wqkv, wo, wgu, wd were re-laid by sp_pack_weights() (bf16 MFMA path only) */
+#define SP_FLAG_PAGED_KV 4u         /* requests hold their cache in pages of page_slots slots (see below) */
 
 typedef struct sp_config {
   int32_t n_layers;
@@ -91,6 +92,7 @@ typedef struct sp_config {
   int32_t max_batch_nodes; /* most rows (sum of n_nodes) one sp_stage_forward call may carry */
   int64_t kv_slots;        /* slots per (layer, K|V, head) plane of the slab */
   uint32_t flags;
+  int32_t page_slots;      /* SP_FLAG_PAGED_KV: slots per page, a power of two in [32, 4096] that divides kv_slots */
 } sp_config;
 
 /* Device pointers of one layer's weights. */
@@ -176,6 +178,25 @@ void sp_stage_destroy(sp_stage* stage);
  * called again to reset a request. */
 int sp_request_init(sp_stage* stage, int32_t req, int64_t slot_base, int32_t capacity,
                     int32_t prefix_len, sp_stream stream);
+
+/* Paged cache (SP_FLAG_PAGED_KV; SpecPipe-DB stores its cache PagedAttention-style, Sec. 4
+ * "Implementation").  The slab is cut into kv_slots / page_slots pages; the library hands
+ * them out: a request holds the pages of its first prefix_len + n_live logical slots, in
+ * any physical order.  Logical slot s of a request lives in physical slot
+ * page[s / page_slots] * page_slots + s % page_slots of every (layer, K|V, head) plane.
+ * sp_request_init takes slot_base = 0 and capacity = the most logical slots the request may
+ * reach; it takes the pages of the committed context, whose K and V the caller then writes
+ * at the physical slots sp_request_pages reports.  sp_tree_insert takes further pages as
+ * the tree grows (SP_E_CAPACITY if none is free: nothing changes), sp_kv_compact returns the
+ * pages past the compacted rows, sp_request_release returns all.  Page bookkeeping is host
+ * state; the device tables are updated in stream order, so one stream must carry all calls
+ * of a stage. */
+int sp_request_pages(const sp_stage* stage, int32_t req, int32_t* pages_out /*host, nullable*/,
+                     int32_t max_pages, int32_t* n_pages_out /*host, nullable*/);
+/* Ends a request (both storage modes): its pages, if any, return to the allocator. */
+int sp_request_release(sp_stage* stage, int32_t req, sp_stream stream);
+/* Pages not held by any request (SP_E_INVALID for a null stage). */
+int sp_stage_free_pages(const sp_stage* stage);
 
 /* ---- the hot path ------------------------------------------------------------ */
 

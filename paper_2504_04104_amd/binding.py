@@ -21,6 +21,7 @@ SP_F32, SP_BF16 = 0, 1
 SP_ACCEPT, SP_DROP, SP_CLEAR = 0, 1, 2
 SP_FLAG_SIMPLE_KERNELS = 1
 SP_FLAG_PACKED_WEIGHTS = 2
+SP_FLAG_PAGED_KV = 4
 
 # sp_kernel_kind
 K_GEMM_QKV, K_GEMM_O, K_GEMM_GATEUP, K_GEMM_DOWN = 1, 2, 3, 4
@@ -42,7 +43,7 @@ class sp_config(C.Structure):
                 ("n_kv_heads", C.c_int32), ("d_head", C.c_int32), ("d_ff", C.c_int32),
                 ("rms_eps", C.c_float), ("rope_theta", C.c_float), ("dtype", C.c_int32),
                 ("max_requests", C.c_int32), ("max_tree_nodes", C.c_int32), ("max_batch_nodes", C.c_int32),
-                ("kv_slots", C.c_int64), ("flags", C.c_uint32)]
+                ("kv_slots", C.c_int64), ("flags", C.c_uint32), ("page_slots", C.c_int32)]
 
 
 class sp_layer_weights(C.Structure):
@@ -99,6 +100,9 @@ def load_library(path: Optional[str] = None) -> C.CDLL:
         "sp_tree_match": [vp, C.c_int32, i32p, vp, i32p, vp],
         "sp_tree_expand": [vp, C.c_int32, C.c_int32, i32p, C.c_int32, vp, vp, C.c_int32, vp, vp, vp, vp, vp],
         "sp_tree_insert": [vp, C.c_int32, C.c_int32, i32p, i32p, f32p, i32p, vp],
+        "sp_request_pages": [vp, C.c_int32, i32p, C.c_int32, i32p],
+        "sp_request_release": [vp, C.c_int32, vp],
+        "sp_stage_free_pages": [vp],
         "sp_tree_insert_batch": [vp, C.c_int32, i32p, i32p, i32p, i32p, f32p, i32p, vp],
         "sp_stage_forward": [vp, C.c_int32, i32p, i32p, i32p, vp, vp, vp],
         "sp_tree_prune": [vp, C.c_int32, C.c_int32, C.c_int32, i32p, i32p, vp],
@@ -144,7 +148,7 @@ class Stage:
 
     def __init__(self, shape, layers: List[Dict[str, "object"]], *, kv_slots: int, max_requests: int = 1,
                  max_batch_nodes: int = 64, max_tree_nodes: int = SP_MAX_TREE_NODES, flags: int = 0,
-                 device: str = "cuda:0"):
+                 device: str = "cuda:0", page_slots: int = 0):
         import torch
         self.torch = torch
         self.lib = load_library()
@@ -154,7 +158,8 @@ class Stage:
         self.tdtype = torch.bfloat16 if shape.dtype == "bf16" else torch.float32
         self.cfg = sp_config(shape.n_layers, shape.d_model, shape.n_q_heads, shape.n_kv_heads, shape.d_head,
                              shape.d_ff, shape.rms_eps, shape.rope_theta, self.dtype, max_requests,
-                             max_tree_nodes, max_batch_nodes, kv_slots, flags)
+                             max_tree_nodes, max_batch_nodes, kv_slots, flags, page_slots)
+        self.page_slots = page_slots
         sz = sp_sizes()
         _check(self.lib.sp_stage_query_sizes(C.byref(self.cfg), C.byref(sz)), "sp_stage_query_sizes")
         self.sizes = sz
@@ -198,6 +203,28 @@ class Stage:
         return self.kv.view(self.tdtype).view(s.n_layers, 2, s.n_kv_heads, self.cfg.kv_slots, s.d_head)
 
     # -- the C ABI, one method per entry point --------------------------------------
+    def request_pages(self, req: int) -> List[int]:
+        """Paged cache: physical page of every logical page the request holds."""
+        n = C.c_int32()
+        _check(self.lib.sp_request_pages(self.handle, req, None, 0, C.byref(n)), "sp_request_pages")
+        out = np.zeros(max(n.value, 1), dtype=np.int32)
+        _check(self.lib.sp_request_pages(self.handle, req, out.ctypes.data_as(C.POINTER(C.c_int32)), n.value, None),
+               "sp_request_pages")
+        return [int(v) for v in out[:n.value]]
+
+    def request_release(self, req: int):
+        _check(self.lib.sp_request_release(self.handle, req, self._stream()), "sp_request_release")
+
+    def free_pages(self) -> int:
+        return int(self.lib.sp_stage_free_pages(self.handle))
+
+    def logical_slots(self, req: int, lo: int, hi: int):
+        """Physical slot index (tensor, on the device) of the request's logical slots [lo, hi) in paged mode."""
+        pages = self.request_pages(req)
+        pg = self.page_slots
+        idx = [pages[s // pg] * pg + s % pg for s in range(lo, hi)]
+        return self.torch.tensor(idx, dtype=self.torch.long, device=self.device)
+
     def request_init(self, req: int, slot_base: int, capacity: int, prefix_len: int):
         _check(self.lib.sp_request_init(self.handle, req, slot_base, capacity, prefix_len, self._stream()),
                "sp_request_init")

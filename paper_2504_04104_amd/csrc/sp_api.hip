@@ -25,6 +25,7 @@ struct HostReq {
   bool pending = false;         // a prune awaits its cache compaction
   int pend_mode = 0, pend_node = 0;
   short pend_tab_new[SP_T];     // old node -> new index, -1 gone
+  std::vector<int> pages;       // paged cache: physical page of every logical page the request holds
 };
 
 inline size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
@@ -87,7 +88,19 @@ int check_config(const sp_config* c) {
   if (c->d_model % 8 || c->d_ff % 8) return SP_E_UNSUPPORTED;
   if (c->d_head != 64 && c->d_head != 128) return SP_E_UNSUPPORTED;
   if (!(c->rms_eps > 0.f) || !(c->rope_theta > 1.f)) return SP_E_INVALID;
+  if (c->flags & SP_FLAG_PAGED_KV) {
+    // a page holds whole 32-slot attention tiles
+    const int pg = c->page_slots;
+    if (pg < 32 || pg > 4096 || (pg & (pg - 1))) return SP_E_INVALID;
+    if (c->kv_slots % pg) return SP_E_INVALID;
+  }
   return SP_OK;
+}
+
+inline bool is_paged(const sp_config& c) { return (c.flags & SP_FLAG_PAGED_KV) != 0; }
+inline size_t page_table_bytes(const sp_config& c) {
+  if (!is_paged(c)) return 0;
+  return align_up((size_t)c.max_requests * (size_t)(c.kv_slots / c.page_slots) * sizeof(int));
 }
 
 }  // namespace
@@ -102,6 +115,10 @@ struct sp_stage {
   Workspace ws;
   KvGeom geom;
   std::vector<HostReq> reqs;
+  // paged cache: the allocator lives on the host, the page tables on the device
+  int n_pages = 0;
+  int* d_page_table = nullptr;
+  std::vector<int> free_pages;
   bool fast = false;           // bf16 MFMA kernels in use
   bool packed = false;         // weights are in MFMA fragment order
   int n_cu = 256;              // compute units of the device
@@ -135,6 +152,25 @@ struct ProfScope {
 };
 
 size_t tables_meta_bytes(const sp_config& c) { return align_up((size_t)c.max_requests * sizeof(ReqMeta)); }
+
+// Paged cache: make request `req` hold the pages of its first `slots` logical slots.  Growth
+// takes pages from the free list and sends their ids to the device table; shrinking returns
+// pages (their table entries stay behind, unused).  Everything runs in stream order, so a page
+// can be handed to another request as soon as the host has let go of it.
+hipError_t pages_resize(sp_stage* s, int req, int slots, hipStream_t st) {
+  HostReq& r = s->reqs[req];
+  const int pg = s->cfg.page_slots;
+  const int want = (slots + pg - 1) / pg;
+  const int have = (int)r.pages.size();
+  if (want > have) {
+    for (int i = have; i < want; ++i) { r.pages.push_back(s->free_pages.back()); s->free_pages.pop_back(); }
+    return sp_launch_pages_set(s->d_page_table, s->n_pages, req, have, want - have, r.pages.data() + have, st);
+  }
+  for (int i = have - 1; i >= want; --i) s->free_pages.push_back(r.pages[i]);
+  r.pages.resize(want);
+  return hipSuccess;
+}
+inline int pages_for(const sp_stage* s, int slots) { return (slots + s->cfg.page_slots - 1) / s->cfg.page_slots; }
 
 HostReq* get_req(sp_stage* s, int req) {
   if (!s || req < 0 || req >= (int)s->reqs.size() || !s->reqs[req].active) return nullptr;
@@ -203,7 +239,8 @@ int sp_stage_query_sizes(const sp_config* cfg, sp_sizes* out) {
   out->kv_row_bytes = row;
   out->kv_plane_bytes = (size_t)cfg->kv_slots * row;
   out->kv_bytes = (size_t)cfg->n_layers * 2 * cfg->n_kv_heads * out->kv_plane_bytes;
-  out->tables_bytes = tables_meta_bytes(*cfg) + align_up((size_t)cfg->max_requests * sizeof(ReqTables));
+  out->tables_bytes = tables_meta_bytes(*cfg) + align_up((size_t)cfg->max_requests * sizeof(ReqTables)) +
+                      page_table_bytes(*cfg);
   out->workspace_bytes = carve(*cfg, nullptr).total;
   return SP_OK;
 }
@@ -239,6 +276,17 @@ int sp_stage_create(const sp_config* cfg, const sp_layer_weights* layers, const 
   s->geom.row_bytes = (int)sz.kv_row_bytes;
   s->geom.n_layers = cfg->n_layers;
   s->geom.n_kv_heads = cfg->n_kv_heads;
+  s->geom.page_table = nullptr; s->geom.pt_stride = 0; s->geom.pg_shift = 0;
+  if (is_paged(*cfg)) {
+    s->n_pages = (int)(cfg->kv_slots / cfg->page_slots);
+    s->d_page_table = (int*)((char*)buffers->tables + tables_meta_bytes(*cfg) +
+                             align_up((size_t)cfg->max_requests * sizeof(ReqTables)));
+    s->geom.page_table = s->d_page_table;
+    s->geom.pt_stride = s->n_pages;
+    while ((1 << s->geom.pg_shift) < cfg->page_slots) ++s->geom.pg_shift;
+    s->free_pages.resize(s->n_pages);
+    for (int i = 0; i < s->n_pages; ++i) s->free_pages[i] = s->n_pages - 1 - i;    // page 0 is handed out first
+  }
   s->reqs.resize(cfg->max_requests);
   // The MFMA kernels cover bf16 with d_head 128 and dimensions that fill their tiles.
   s->fast = cfg->dtype == SP_BF16 && !(cfg->flags & SP_FLAG_SIMPLE_KERNELS) && cfg->d_head == 128 &&
@@ -291,14 +339,50 @@ int sp_request_init(sp_stage* s, int32_t req, int64_t slot_base, int32_t capacit
   if (!s) return SP_E_INVALID;
   if (req < 0 || req >= (int)s->reqs.size()) return SP_E_BAD_REQ;
   if (slot_base < 0 || capacity < 1 || prefix_len < 1) return SP_E_INVALID;
-  if (prefix_len > capacity || slot_base + capacity > s->cfg.kv_slots) return SP_E_CAPACITY;
+  HostReq& r = s->reqs[req];
+  const bool paged = is_paged(s->cfg);
+  if (paged) {
+    // logical slots 0 .. capacity-1 on pages taken as the request grows; slot_base has no meaning
+    if (slot_base != 0) return SP_E_INVALID;
+    if (prefix_len > capacity || capacity > s->cfg.kv_slots) return SP_E_CAPACITY;
+    if (pages_for(s, prefix_len) > (int)(s->free_pages.size() + r.pages.size())) return SP_E_CAPACITY;
+  } else if (prefix_len > capacity || slot_base + capacity > s->cfg.kv_slots) {
+    return SP_E_CAPACITY;
+  }
   hipError_t e = sp_launch_request_init(s->d_meta, s->d_tables, req, slot_base, capacity, prefix_len,
                                         (hipStream_t)stream);
   if (e != hipSuccess) return hip_fail(s, e);
-  HostReq& r = s->reqs[req];
+  if (paged) {
+    if ((e = pages_resize(s, req, 0, (hipStream_t)stream)) != hipSuccess ||
+        (e = pages_resize(s, req, prefix_len, (hipStream_t)stream)) != hipSuccess)
+      return hip_fail(s, e);
+  }
   r.active = true; r.base = slot_base; r.cap = capacity; r.P = prefix_len; r.T = 0; r.pending = false;
   return SP_OK;
 }
+
+int sp_request_release(sp_stage* s, int32_t req, sp_stream stream) {
+  if (!s) return SP_E_INVALID;
+  HostReq* r = get_req(s, req);
+  if (!r) return SP_E_BAD_REQ;
+  if (is_paged(s->cfg)) (void)pages_resize(s, req, 0, (hipStream_t)stream);
+  r->active = false; r->pending = false; r->T = 0; r->P = 0;
+  return SP_OK;
+}
+
+int sp_request_pages(const sp_stage* s, int32_t req, int32_t* pages_out, int32_t max_pages, int32_t* n_pages_out) {
+  if (!s || req < 0 || req >= (int)s->reqs.size() || !s->reqs[req].active) return s ? SP_E_BAD_REQ : SP_E_INVALID;
+  if (!is_paged(s->cfg)) return SP_E_UNSUPPORTED;
+  const HostReq& r = s->reqs[req];
+  if (n_pages_out) *n_pages_out = (int32_t)r.pages.size();
+  if (pages_out) {
+    if (max_pages < (int)r.pages.size()) return SP_E_CAPACITY;
+    for (size_t i = 0; i < r.pages.size(); ++i) pages_out[i] = r.pages[i];
+  }
+  return SP_OK;
+}
+
+int sp_stage_free_pages(const sp_stage* s) { return s ? (int)s->free_pages.size() : SP_E_INVALID; }
 
 int sp_request_info(const sp_stage* s, int32_t req, int32_t* prefix_len, int32_t* n_live, int32_t* n_forwarded) {
   if (!s) return SP_E_INVALID;
@@ -330,6 +414,22 @@ int sp_tree_insert_batch(sp_stage* s, int32_t n_req, const int32_t* req_ids, con
     total += n_new[i];
   }
   hipStream_t st = (hipStream_t)stream;
+  if (is_paged(s->cfg)) {
+    // pages for the new cache rows, all or nothing
+    int need = 0;
+    for (int i = 0; i < n_req; ++i) {
+      const HostReq& r = s->reqs[req_ids[i]];
+      need += pages_for(s, r.P + r.T + n_new[i]) - (int)r.pages.size();
+    }
+    if (need > (int)s->free_pages.size()) return SP_E_CAPACITY;
+    for (int i = 0; i < n_req; ++i) {
+      const HostReq& r = s->reqs[req_ids[i]];
+      if (pages_for(s, r.P + r.T + n_new[i]) > (int)r.pages.size()) {
+        hipError_t e = pages_resize(s, req_ids[i], r.P + r.T + n_new[i], st);
+        if (e != hipSuccess) return hip_fail(s, e);
+      }
+    }
+  }
   // launches of at most SP_T new nodes each (one launch in every case the configs produce)
   InsertArgs a;
   a.n_req = 0;
@@ -589,7 +689,12 @@ int sp_kv_compact_batch(sp_stage* s, int32_t n, const int32_t* req_ids, sp_strea
     hipError_t e = sp_launch_kv_compact(s->d_meta, s->d_tables, b, s->geom, (hipStream_t)stream);
     if (e != hipSuccess) return hip_fail(s, e);
   }
-  for (int i = 0; i < n; ++i) s->reqs[req_ids[i]].pending = false;
+  for (int i = 0; i < n; ++i) {
+    HostReq& r = s->reqs[req_ids[i]];
+    r.pending = false;
+    // pages past the compacted rows go back to the allocator (work queued later runs after the gather)
+    if (is_paged(s->cfg)) (void)pages_resize(s, req_ids[i], r.P + r.T, (hipStream_t)stream);
+  }
   return SP_OK;
 }
 

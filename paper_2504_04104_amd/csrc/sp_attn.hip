@@ -35,7 +35,7 @@ struct AttnArgs {
   bf16_t* out;              // [M][n_q][DH]
 };
 
-template <int QT>
+template <int QT, bool PAGED>
 __global__ void __launch_bounds__(64 * AW) k_attn_bf16(AttnArgs a, AttnPlan plan) {
   // V tiles of the eight waves; the same bytes later carry the states being folded
   // (four waves x QT x 8 d-tiles x 64 lanes x 16 B = QT * 32 KB <= 8 * VT_BYTES for QT <= 2).
@@ -68,25 +68,33 @@ __global__ void __launch_bounds__(64 * AW) k_attn_bf16(AttnArgs a, AttnPlan plan
   const int w1 = min(c0 + 32 * (((wave + 1) * ntiles) / AW), c1);
   const int l15 = lane & 15, kg = lane >> 4;
 
-  const size_t base_b = (size_t)plan.seg_base[seg] * 256;
+  // contiguous cache: the request's range starts at its base slot; paged: logical slots go through
+  // the request's page table, one lookup per 32-slot tile (a tile never straddles a page)
+  const size_t base_b = PAGED ? 0 : (size_t)plan.seg_base[seg] * 256;
   const char* kplane = a.g.kv + ((size_t)(a.layer * 2 + 0) * a.n_kv + kvh) * a.g.plane_bytes + base_b;
   const char* vplane = a.g.kv + ((size_t)(a.layer * 2 + 1) * a.n_kv + kvh) * a.g.plane_bytes + base_b;
+  const int* pt = PAGED ? a.g.page_table + (size_t)plan.seg_req[seg] * a.g.pt_stride : nullptr;
+  const int pg_sh = PAGED ? a.g.pg_shift : 0, pg_mask = (1 << pg_sh) - 1;
+  const int page0 = PAGED ? pt[0] : 0;
+#define SP_PHYS(slot, pg) (PAGED ? (((slot) < span ? (pg) : page0) << pg_sh | ((slot) < span ? ((slot) & pg_mask) : 0)) \
+                                 : ((slot) < span ? (slot) : 0))
 
   // Loads of one 32-slot tile: K as MFMA A fragments (row l15 of each 16-slot half, 16 B at
   // d = s*32 + kg*8), V as plain 16-byte pieces (row i*4+kg, piece l15).  Slots past the
   // request's data are read from slot 0 (always valid) and masked later.
 #define SP_LOAD_TILE(S0)                                                                           \
   {                                                                                                \
+    const int pg_ = PAGED ? pt[((S0) < span ? (S0) : 0) >> pg_sh] : 0;                             \
     _Pragma("unroll") for (int t2 = 0; t2 < 2; ++t2) {                                             \
       int slot = (S0) + t2 * 16 + l15;                                                             \
-      slot = slot < span ? slot : 0;                                                               \
+      slot = SP_PHYS(slot, pg_);                                                                   \
       const char* kp = kplane + (size_t)slot * 256 + kg * 16;                                      \
       _Pragma("unroll") for (int s = 0; s < 4; ++s)                                                \
           kreg[t2][s] = *reinterpret_cast<const u32x4_t*>(kp + s * 64);                            \
     }                                                                                              \
     _Pragma("unroll") for (int i = 0; i < 8; ++i) {                                                \
       int slot = (S0) + i * 4 + kg;                                                                \
-      slot = slot < span ? slot : 0;                                                               \
+      slot = SP_PHYS(slot, pg_);                                                                   \
       vreg[i] = *reinterpret_cast<const u32x4_t*>(vplane + (size_t)slot * 256 + l15 * 16);         \
     }                                                                                              \
   }
@@ -234,6 +242,7 @@ __global__ void __launch_bounds__(64 * AW) k_attn_bf16(AttnArgs a, AttnPlan plan
     }
   }
 #undef SP_LOAD_TILE
+#undef SP_PHYS
 
   // ---- fold the eight wave states (fixed order, so results do not depend on timing) ----
 #pragma unroll
@@ -381,8 +390,14 @@ hipError_t sp_launch_attn_bf16(const bf16_t* q, const ReqTables* tables, KvGeom 
   a.out = out;
   dim3 grid(plan.total_items * n_kv);
   switch (plan.qt) {
-    case 1: hipLaunchKernelGGL(k_attn_bf16<1>, grid, dim3(64 * AW), 0, st, a, plan); break;
-    case 2: hipLaunchKernelGGL(k_attn_bf16<2>, grid, dim3(64 * AW), 0, st, a, plan); break;
+    case 1:
+      if (g.page_table) hipLaunchKernelGGL((k_attn_bf16<1, true>), grid, dim3(64 * AW), 0, st, a, plan);
+      else hipLaunchKernelGGL((k_attn_bf16<1, false>), grid, dim3(64 * AW), 0, st, a, plan);
+      break;
+    case 2:
+      if (g.page_table) hipLaunchKernelGGL((k_attn_bf16<2, true>), grid, dim3(64 * AW), 0, st, a, plan);
+      else hipLaunchKernelGGL((k_attn_bf16<2, false>), grid, dim3(64 * AW), 0, st, a, plan);
+      break;
     default: return hipErrorInvalidValue;
   }
   hipError_t e = hipGetLastError();

@@ -75,7 +75,7 @@ struct InsertArgs {
   short req[SP_BATCH];
   short t0[SP_BATCH];
   short row0[SP_BATCH + 1];
-  long long first_slot[SP_BATCH];
+  long long first_slot[SP_BATCH];   // base + prefix_len + t0 (logical slot prefix_len + t0 when paged)
   short parent[SP_T];
   int token[SP_T];
   float prob[SP_T];

@@ -9,7 +9,20 @@ struct KvGeom {
   int row_bytes;         // d_head * element size
   int n_layers;
   int n_kv_heads;
+  // Paged storage (SpecPipe-DB keeps its cache in pages, Sec. 4 "Implementation"): request r's
+  // logical slot s lives in physical slot page_table[r * pt_stride + (s >> pg_shift)] << pg_shift
+  // | (s & mask).  Null: a request owns the contiguous range that starts at its base slot.
+  const int* page_table;
+  int pt_stride;
+  int pg_shift;
 };
+
+// Physical slot of a request's logical slot (base is the request's first slot when contiguous, 0 when paged).
+__device__ __forceinline__ size_t sp_phys_slot(const KvGeom& g, int req, long long base, int lslot) {
+  if (!g.page_table) return (size_t)(base + lslot);
+  const int page = g.page_table[(size_t)req * g.pt_stride + (lslot >> g.pg_shift)];
+  return ((size_t)page << g.pg_shift) | (size_t)(lslot & ((1 << g.pg_shift) - 1));
+}
 
 // ---- tree tables -------------------------------------------------------------
 hipError_t sp_launch_tables_clear(ReqMeta* meta, ReqTables* tables, int n_req, hipStream_t st);
@@ -18,6 +31,8 @@ hipError_t sp_launch_request_init(ReqMeta* meta, ReqTables* tables, int req, lon
 // first_slot: cache slot of the first new node (host mirror: base + prefix_len + n_live)
 hipError_t sp_launch_tree_insert(ReqMeta* meta, ReqTables* tables, const InsertArgs& a, KvGeom g, hipStream_t st);
 hipError_t sp_launch_tree_prune(ReqMeta* meta, ReqTables* tables, const PruneBatch& b, hipStream_t st);
+hipError_t sp_launch_pages_set(int* page_table, int pt_stride, int req, int first, int n, const int* pages /*host*/,
+                               hipStream_t st);
 // out[i] (device) = verified root child of request reqs[i], or -1
 hipError_t sp_launch_tree_match(const ReqMeta* meta, const ReqTables* tables, int n, const int* reqs, int* out,
                                 hipStream_t st);

@@ -132,7 +132,7 @@ __global__ void __launch_bounds__(256) k_rope_kv(const float* part, int S, size_
   const int t = (threadIdx.x % tph) * 4;
   const int N = (n_q + 2 * n_kv) * d_head;
   const RowInfo ri = rows[row];
-  const size_t slot = (size_t)(ri.base + ri.P + ri.node);
+  const size_t slot = sp_phys_slot(g, ri.req, ri.base, ri.P + ri.node);
   const float* pr = part + (size_t)row * N + (size_t)head * d_head;
   const f32x4_t a = fold4(pr + t, S, part_stride), bb = fold4(pr + half + t, S, part_stride);
   if (head < n_q + n_kv) {

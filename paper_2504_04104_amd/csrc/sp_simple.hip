@@ -61,8 +61,10 @@ __global__ void __launch_bounds__(256) k_attn_simple(const T* q, const RowInfo* 
       const int j = s - ri.P;
       if (!((anc[j >> 6] >> (j & 63)) & 1ull)) continue;
     }
-    const T* k = reinterpret_cast<const T*>(kplane + (size_t)s * g.row_bytes);
-    const T* v = reinterpret_cast<const T*>(vplane + (size_t)s * g.row_bytes);
+    // kplane / vplane start at the request's base slot; a paged request has base 0
+    const size_t ps = g.page_table ? sp_phys_slot(g, ri.req, 0, s) : (size_t)s;
+    const T* k = reinterpret_cast<const T*>(kplane + ps * g.row_bytes);
+    const T* v = reinterpret_cast<const T*>(vplane + ps * g.row_bytes);
     float sc = 0.f;
 #pragma unroll 8
     for (int t = 0; t < DH; ++t) sc += s_q[wave][t] * Elt<T>::ld(k + t);

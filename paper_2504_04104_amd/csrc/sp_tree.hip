@@ -53,10 +53,14 @@ __global__ void __launch_bounds__(SP_T) k_tree_insert(ReqMeta* meta, ReqTables* 
   const int req = a.req[item];
   const int r0 = a.row0[item], n_new = a.row0[item + 1] - r0;
   if (blockIdx.x > 0) {
-    uint4* rows = reinterpret_cast<uint4*>(g.kv + (size_t)(blockIdx.x - 1) * g.plane_bytes +
-                                           (size_t)a.first_slot[item] * g.row_bytes);
-    const int n16 = n_new * (g.row_bytes >> 4);
-    for (int i = threadIdx.x; i < n16; i += blockDim.x) rows[i] = make_uint4(0u, 0u, 0u, 0u);
+    char* plane = g.kv + (size_t)(blockIdx.x - 1) * g.plane_bytes;
+    const int u16 = g.row_bytes >> 4;
+    const int n16 = n_new * u16;
+    for (int i = threadIdx.x; i < n16; i += blockDim.x) {
+      const int row = i / u16, u = i - row * u16;
+      const size_t slot = sp_phys_slot(g, req, 0, (int)a.first_slot[item] + row);   // first_slot includes the base
+      reinterpret_cast<uint4*>(plane + slot * g.row_bytes)[u] = make_uint4(0u, 0u, 0u, 0u);
+    }
     return;
   }
   ReqTables& t = tables[req];
@@ -195,9 +199,10 @@ __global__ void __launch_bounds__(SP_T) k_tree_prune(ReqMeta* meta, ReqTables* t
 // destinations in ascending batches; inside a batch every source is in registers
 // before the first store.  Later batches only read sources beyond the rows a batch
 // writes (src[j] >= j), so no row is overwritten before it is read.
+// phys (nullable): row index -> physical row of the stream (paged cache); else rows are consecutive.
 template <int R>
 __device__ __forceinline__ void gather_inplace(char* stream, size_t row_stride, int slice_bytes, int first,
-                                               int n_keep, const short* src) {
+                                               int n_keep, const short* src, const int* phys = nullptr) {
   const int U = slice_bytes >> 4;                 // 16-byte units per row slice
   const int rows_per_pass = blockDim.x / U;
   const int u = threadIdx.x % U, rr = threadIdx.x / U;
@@ -211,7 +216,8 @@ __device__ __forceinline__ void gather_inplace(char* stream, size_t row_stride, 
       const int s = in ? (int)src[dst] : 0;
       const bool mv = in && s != dst;
       // rows that stay (or lanes without a row) read the stream's first bytes and drop them
-      const uint4 v = *reinterpret_cast<const uint4*>(stream + (mv ? (size_t)s * row_stride + (size_t)u * 16 : 0));
+      const size_t srow = phys ? (size_t)phys[mv ? s : 0] : (size_t)s;
+      const uint4 v = *reinterpret_cast<const uint4*>(stream + (mv ? srow * row_stride + (size_t)u * 16 : 0));
       regs[i] = mv ? v : make_uint4(0u, 0u, 0u, 0u);
     }
     __syncthreads();
@@ -220,7 +226,8 @@ __device__ __forceinline__ void gather_inplace(char* stream, size_t row_stride, 
       const int dst = b0 + i * rows_per_pass + rr;
       if (active && dst < n_keep) {
         const int s = src[dst];
-        if (s != dst) *reinterpret_cast<uint4*>(stream + (size_t)dst * row_stride + (size_t)u * 16) = regs[i];
+        const size_t drow = phys ? (size_t)phys[dst] : (size_t)dst;
+        if (s != dst) *reinterpret_cast<uint4*>(stream + drow * row_stride + (size_t)u * 16) = regs[i];
       }
     }
     __syncthreads();
@@ -235,13 +242,20 @@ __global__ void __launch_bounds__(256) k_kv_compact(const ReqMeta* meta, const R
   const int req = b.req[item];
   const ReqTables& t = tables[req];
   __shared__ short s_src[SP_T];
+  __shared__ int s_phys[SP_T];
   const int n_keep = t.pend_n_kv_keep, first = t.pend_first_moved;
   for (int i = threadIdx.x; i < n_keep; i += blockDim.x) s_src[i] = t.kv_src[i];
+  if (g.page_table)       // physical slot of every row of the old tree region
+    for (int i = threadIdx.x; i < t.pend_T_old; i += blockDim.x) s_phys[i] = (int)sp_phys_slot(g, req, 0, t.pend_P_old + i);
   __syncthreads();
   if (first >= n_keep) return;
   const size_t plane = blockIdx.x;      // (layer*2 + kv) * n_kv_heads + head
-  char* stream = g.kv + plane * g.plane_bytes + (size_t)(meta[req].base + t.pend_P_old) * g.row_bytes;
-  gather_inplace<16>(stream, (size_t)g.row_bytes, g.row_bytes, first, n_keep, s_src);
+  if (g.page_table) {
+    gather_inplace<16>(g.kv + plane * g.plane_bytes, (size_t)g.row_bytes, g.row_bytes, first, n_keep, s_src, s_phys);
+  } else {
+    char* stream = g.kv + plane * g.plane_bytes + (size_t)(meta[req].base + t.pend_P_old) * g.row_bytes;
+    gather_inplace<16>(stream, (size_t)g.row_bytes, g.row_bytes, first, n_keep, s_src);
+  }
 }
 
 // grid = row_bytes / slice: one workgroup per 256-byte column slice of the rows.
@@ -382,6 +396,29 @@ hipError_t sp_launch_tree_expand(const ReqTables* tables, const ExpandArgs& a, c
   hipLaunchKernelGGL(k_tree_expand, dim3(1), dim3(256), 0, st, tables, a, cand_tok, cand_prob, out_parent, out_token,
                      out_prob, out_count);
   return hipGetLastError();
+}
+
+// Writes page ids into a request's page table (host-side allocator decisions, by value).
+struct PageSet {
+  int req;
+  int first;       // first logical page written
+  int n;
+  int page[512];
+};
+__global__ void k_pages_set(int* page_table, int pt_stride, PageSet p) {
+  for (int i = threadIdx.x; i < p.n; i += blockDim.x) page_table[(size_t)p.req * pt_stride + p.first + i] = p.page[i];
+}
+hipError_t sp_launch_pages_set(int* page_table, int pt_stride, int req, int first, int n, const int* pages,
+                               hipStream_t st) {
+  for (int done = 0; done < n; done += 512) {
+    PageSet p;
+    p.req = req; p.first = first + done; p.n = n - done < 512 ? n - done : 512;
+    for (int i = 0; i < p.n; ++i) p.page[i] = pages[done + i];
+    hipLaunchKernelGGL(k_pages_set, dim3(1), dim3(256), 0, st, page_table, pt_stride, p);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  }
+  return hipSuccess;
 }
 
 hipError_t sp_launch_tree_prune(ReqMeta* meta, ReqTables* tables, const PruneBatch& b, hipStream_t st) {

@@ -208,8 +208,13 @@ def run_c5(args):
         base[r.req] = off
         off += r.prefix_len + room
     total_nodes = sum(len(r.parents) for r in reqs)
+    pg = args.page_slots
+    if pg:          # paged cache: requests share a pool of pages instead of owning a range each
+        off = -(-off // pg) * pg
+        for r in reqs:
+            base[r.req] = 0
     stage = sp.Stage(sh, layers, kv_slots=off, max_requests=len(reqs), max_batch_nodes=max(64, total_nodes),
-                     flags=sp.SP_FLAG_PACKED_WEIGHTS)
+                     flags=sp.SP_FLAG_PACKED_WEIGHTS | (sp.SP_FLAG_PAGED_KV if pg else 0), page_slots=pg)
     fill_kv(stage, w.seed)
     x = torch.randn(total_nodes, sh.d_model, device=DEV).to(torch.bfloat16)
     y = torch.empty_like(x)
@@ -242,8 +247,11 @@ def run_c5(args):
     torch.cuda.synchronize()
     t0 = time.perf_counter(); cold(); torch.cuda.synchronize(); t_cold = time.perf_counter() - t0
     t0 = time.perf_counter(); toks = steady(); torch.cuda.synchronize(); t_steady = time.perf_counter() - t0
+    stage.profile_begin(B.K_ATTENTION, 4096)
+    cold(); steady()
+    n_att, att_ms = stage.profile_end()
     flops_cold = 2.0 * total_nodes * sh.params_per_layer * sh.n_layers
-    res = {"run": "c5", "workload": "32 requests, 8B-shaped 4-layer stage", "cold_nodes": total_nodes,
+    res = {"run": "c5", "page_slots": pg, "attention_us_per_launch_cold_and_steady": round(att_ms * 1e3 / max(n_att, 1), 1), "workload": "32 requests, 8B-shaped 4-layer stage", "cold_nodes": total_nodes,
            "cold_ms": round(t_cold * 1e3, 3), "cold_tree_tokens_per_s": round(total_nodes / t_cold, 1),
            "cold_gemm_TFLOPs": round(flops_cold / t_cold / 1e12, 1),
            "cold_mfma_frac": round(flops_cold / t_cold / 1e12 / MFMA_PEAK, 4),
@@ -353,6 +361,7 @@ def run_verify(args):
 
 def main():
     ap = argparse.ArgumentParser()
+    ap.add_argument("--page-slots", type=int, default=0, help="c5: keep the cache in pages of this many slots")
     ap.add_argument("--run", required=True, choices=["sweep", "c3", "c4", "c5", "compact", "verify"])
     ap.add_argument("--steps", type=int, default=0)
     args = ap.parse_args()

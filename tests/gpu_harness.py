@@ -31,7 +31,7 @@ class Pair:
 
     def __init__(self, shape: wl.ModelShape, seed: int, prefixes: Dict[int, int], *, tree_room: int = 256 + 64,
                  flags: int = 0, max_batch_nodes: int = 64, oracle: bool = True, vocab: int = 0,
-                 oracle_reqs: Optional[Sequence[int]] = None):
+                 oracle_reqs: Optional[Sequence[int]] = None, page_slots: int = 0):
         self.shape, self.seed = shape, seed
         self.vocab = vocab
         # the float64 oracle may follow a sample of the requests only (large batches)
@@ -43,13 +43,28 @@ class Pair:
         n_req = max(prefixes) + 1
         self.base: Dict[int, int] = {}
         self.cap: Dict[int, int] = {}
+        self.page_slots = page_slots
         off = 0
         for r in sorted(prefixes):
-            self.base[r] = off
+            self.base[r] = 0 if page_slots else off
             self.cap[r] = prefixes[r] + tree_room
-            off += self.cap[r]
-        self.gpu = sp.Stage(shape, layers, kv_slots=off, max_requests=n_req, max_batch_nodes=max_batch_nodes,
-                            flags=flags)
+            off += self.cap[r] if not page_slots else -(-self.cap[r] // page_slots) * page_slots
+        if page_slots:
+            # paged cache: two extra requests are set up and released first, so that the free list
+            # hands the real requests their pages out of physical order
+            flags |= sp.SP_FLAG_PAGED_KV
+            self.gpu = sp.Stage(shape, layers, kv_slots=off, max_requests=n_req + 2, max_batch_nodes=max_batch_nodes,
+                                flags=flags, page_slots=page_slots)
+            n_pages = off // page_slots
+            a = max(1, n_pages // 3)
+            self.gpu.request_init(n_req, 0, a * page_slots, a * page_slots)
+            self.gpu.request_init(n_req + 1, 0, a * page_slots, a * page_slots)
+            self.gpu.request_release(n_req)
+            self.gpu.request_release(n_req + 1)
+            assert self.gpu.free_pages() == n_pages
+        else:
+            self.gpu = sp.Stage(shape, layers, kv_slots=off, max_requests=n_req, max_batch_nodes=max_batch_nodes,
+                                flags=flags)
         self.ora = StageOracle(shape, self.weights) if oracle else None
         if vocab:
             # output head of the last stage, same numbers on both sides
@@ -61,9 +76,17 @@ class Pair:
             self.head = {"norm": torch.from_numpy(self.head_np["norm"]).to("cuda:0", td).contiguous(), "wvocab": wv}
         for r, P in prefixes.items():
             pk, pv = zip(*[wl.prefix_kv(shape, seed, l, P, req=r) for l in range(shape.n_layers)])
-            for l in range(shape.n_layers):
-                sp.write_prefix(self.gpu, l, self.base[r], pk[l], pv[l])
-            self.gpu.request_init(r, self.base[r], self.cap[r], P)
+            if page_slots:
+                self.gpu.request_init(r, 0, self.cap[r], P)          # takes the pages of the context
+                idx = self.gpu.logical_slots(r, 0, P)
+                kv = self.gpu.kv_view()
+                for l in range(shape.n_layers):
+                    kv[l, 0].index_copy_(1, idx, to_dev(pk[l], self.gpu).permute(1, 0, 2).contiguous())
+                    kv[l, 1].index_copy_(1, idx, to_dev(pv[l], self.gpu).permute(1, 0, 2).contiguous())
+            else:
+                for l in range(shape.n_layers):
+                    sp.write_prefix(self.gpu, l, self.base[r], pk[l], pv[l])
+                self.gpu.request_init(r, self.base[r], self.cap[r], P)
             if self.ora is not None and (self.oracle_reqs is None or r in self.oracle_reqs):
                 self.ora.request_init(r, pk, pv, self.cap[r])
 
@@ -133,8 +156,16 @@ class Pair:
 
     def tree_region(self, req: int, P: int, n: int) -> torch.Tensor:
         """Raw slab rows of tree slots [P, P+n): [layer, K|V, head, n, d_head] (a copy)."""
+        return self.rows(req, P, P + n)
+
+    def rows(self, req: int, lo: int, hi: int) -> torch.Tensor:
+        """The request's logical cache slots [lo, hi) of every plane (a copy), whatever the storage."""
+        if self.page_slots:
+            if hi <= lo:
+                return self.gpu.kv_view()[:, :, :, 0:0, :].clone()
+            return self.gpu.kv_view().index_select(3, self.gpu.logical_slots(req, lo, hi))
         b = self.base[req]
-        return self.gpu.kv_view()[:, :, :, b + P:b + P + n, :].clone()
+        return self.gpu.kv_view()[:, :, :, b + lo:b + hi, :].clone()
 
     def check_tables(self, req: int):
         v = self.gpu.tree_read(req)
@@ -172,7 +203,7 @@ class Pair:
         st = self.ora.req[req]
         P_old, T_old = st.P, st.tree.n - 1
         before = self.tree_region(req, P_old, T_old)
-        untouched = self.gpu.kv_view()[:, :, :, self.base[req]:self.base[req] + P_old, :].clone()
+        untouched = self.rows(req, 0, P_old)
         live, commit = self.gpu.tree_prune(req, mode, node)
         pr = (self.ora.accept(req, node) if mode == sp.SP_ACCEPT else
               self.ora.drop(req, node) if mode == sp.SP_DROP else self.ora.clear(req))
@@ -190,8 +221,12 @@ class Pair:
         expect = before.index_select(3, sel)                # oracle: rows[keep], stable
         assert expect.shape[3] == n_keep
         assert torch.equal(after.view(torch.uint8), expect.contiguous().view(torch.uint8))
-        now = self.gpu.kv_view()[:, :, :, self.base[req]:self.base[req] + P_old, :]
-        assert torch.equal(now.contiguous().view(torch.uint8), untouched.view(torch.uint8))
+        now = self.rows(req, 0, P_old)
+        assert torch.equal(now.contiguous().view(torch.uint8), untouched.contiguous().view(torch.uint8))
+        if self.page_slots:
+            # exactly the pages of the live slots stay with the request
+            live_slots = self.ora.req[req].P + self.ora.req[req].tree.n - 1
+            assert len(self.gpu.request_pages(req)) == -(-live_slots // self.page_slots)
         self.check_tables(req)
         if x_rows is not None:
             ref = self.ora.prune_hidden_rows(x_rows, row_nodes, pr)

@@ -137,6 +137,48 @@ def test_empty_and_degenerate_calls():
     pair.close()
 
 
+def test_paged_cache_f32_and_page_accounting():
+    """The plain (fp32) kernels on a paged cache, and the allocator's bookkeeping: pages follow the
+    live slots, an insert that would need more pages than are free fails without changing anything,
+    a release returns every page."""
+    shape = MINI_F32
+    PG = 32
+    pair = Pair(shape, 25, {0: 70, 1: 45}, tree_room=64, page_slots=PG)
+    g = pair.gpu
+    total_pages = g.sizes.kv_bytes // (shape.n_layers * 2 * shape.n_kv_heads * shape.d_head * 4) // PG
+    assert len(g.request_pages(0)) == 3 and len(g.request_pages(1)) == 2
+    assert g.free_pages() == total_pages - 5
+    assert sorted(g.request_pages(0) + g.request_pages(1)) != g.request_pages(0) + g.request_pages(1)   # out of order
+    par = wl.tree_uniform_parents(25, 30, 6, name=("pg",))
+    x = wl.hidden_rows(shape, 25, ("pg",), 30)
+    pair.insert(0, par)
+    assert len(g.request_pages(0)) == 4                                   # 70 + 30 slots
+    y, ref = pair.forward([0], [0], [30], x)
+    assert rel_err(y, ref) <= TOL["f32"]
+    pair.check_kv(0, TOL["f32"])
+    roots = [i for i, p in enumerate(par) if p < 0]
+    pair.prune(0, sp.SP_DROP, roots[0], x_rows=y, row_nodes=list(range(30)))
+    pair.check_kv(0, TOL["f32"])
+    # another request takes all free pages but one; request 1 then asks for two more
+    free = g.free_pages()
+    g.request_init(2, 0, (free - 1) * PG, (free - 1) * PG)
+    assert g.free_pages() == 1
+    with pytest.raises(sp.SpError) as ei:
+        g.tree_insert(1, [-1] * 64)                                       # 45 + 64 slots = 4 pages, 2 held
+    assert ei.value.status == -2                                          # SP_E_CAPACITY
+    assert g.free_pages() == 1 and g.request_info(1)[1] == 0 and len(g.request_pages(1)) == 2
+    pair.insert(1, [-1] * 40)                                             # 85 slots = 3 pages: takes the last one
+    assert g.free_pages() == 0
+    x1 = wl.hidden_rows(shape, 25, ("pg1",), 40)
+    y, ref = pair.forward([1], [0], [40], x1)
+    assert rel_err(y, ref) <= TOL["f32"]
+    g.request_release(2)
+    g.request_release(0)
+    g.request_release(1)
+    assert g.free_pages() == total_pages
+    pair.close()
+
+
 def test_tables_only_random_sequences():
     """Insert / accept / drop sequences up to the 256-node cap: tables bit-exact after every call."""
     pair = Pair(MINI_F32, 14, {0: 5}, tree_room=4096)
@@ -164,11 +206,13 @@ def test_tables_only_random_sequences():
     pair.close()
 
 
-def test_streaming_mini():
+@pytest.mark.parametrize("page_slots", [0, 32, 128], ids=["contiguous", "pages32", "pages128"])
+def test_streaming_mini(page_slots):
     """Config 4 in miniature: per step insert 1-8 nodes, forward only those, prune, compact
-    (cache and in-flight hidden rows); every step checked."""
+    (cache and in-flight hidden rows); every step checked.  Also with the cache in pages that
+    the request holds out of physical order and returns as the tree shrinks."""
     shape = MINI_BF16
-    pair = Pair(shape, 15, {0: 200}, tree_room=700, flags=sp.SP_FLAG_PACKED_WEIGHTS)
+    pair = Pair(shape, 15, {0: 200}, tree_room=700, flags=sp.SP_FLAG_PACKED_WEIGHTS, page_slots=page_slots)
     steps = wl.streaming_schedule(15, 40, max_new=8, cap=256, p_accept=0.7)
     worst = 0.0
     for s, st in enumerate(steps):
@@ -190,12 +234,14 @@ def test_streaming_mini():
     pair.close()
 
 
-def test_ragged_batch_mini():
+@pytest.mark.parametrize("page_slots", [0, 64], ids=["contiguous", "pages64"])
+def test_ragged_batch_mini(page_slots):
     """Config 5 in miniature: several requests with their own prefix and tree in one call;
-    block-diagonal masks; batched prune + compaction."""
+    block-diagonal masks; batched prune + compaction.  Also with a paged cache shared by the
+    requests (the storage of the multi-request version, Sec. 4 "Implementation")."""
     shape = MINI_GQA4
     reqs = wl.batch_requests(16, n_req=5, p_lo=40, p_hi=333, t_lo=3, t_hi=20, max_levels=5)
-    pair = Pair(shape, 16, {r.req: r.prefix_len for r in reqs}, max_batch_nodes=128)
+    pair = Pair(shape, 16, {r.req: r.prefix_len for r in reqs}, max_batch_nodes=128, page_slots=page_slots)
     for r in reqs:
         pair.insert(r.req, r.parents)
     counts = [len(r.parents) for r in reqs]
