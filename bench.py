@@ -40,6 +40,11 @@ def main() -> int:
     ap.add_argument("--kernels", action="store_true", help="also time every kernel kind (extra passes)")
     ap.add_argument("--unpacked", action="store_true",
                     help="keep the weights row-major instead of the load-time MFMA-fragment re-layout")
+    ap.add_argument("--no-graphs", action="store_true",
+                    help="keep sp_stage_forward from replaying HIP graphs of its launches (SP_FLAG_NO_GRAPHS)")
+    ap.add_argument("--graph", action="store_true",
+                    help="capture one step into a HIP graph and time replays (the step's device work is the "
+                         "same every step; the host-side argument checks then run once, at capture)")
     ap.add_argument("--roofline-sample", type=int, default=5,
                     help="bracket one gate/up launch in this many with HIP events (default 5)")
     ap.add_argument("--calib-copy", action="store_true",
@@ -73,6 +78,8 @@ def main() -> int:
     if not args.unpacked:
         layers = sp.pack_weights(sh, layers, dev)      # load-time re-layout, outside the timed region
         flags |= sp.SP_FLAG_PACKED_WEIGHTS
+    if args.no_graphs:
+        flags |= sp.SP_FLAG_NO_GRAPHS
     cap = P + 256 + 64
     stage = sp.Stage(sh, layers, kv_slots=cap, max_requests=1, max_batch_nodes=max(64, n), flags=flags)
     prefix = [wl.prefix_kv(sh, w.seed, l, P) for l in range(sh.n_layers)]
@@ -105,6 +112,19 @@ def main() -> int:
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
+    if args.graph:
+        graph = torch.cuda.CUDAGraph()
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            with torch.cuda.graph(graph, stream=side):
+                step()
+        torch.cuda.current_stream().wait_stream(side)
+        eager_step = step
+        step = graph.replay
+        for _ in range(3):
+            step()
+        torch.cuda.synchronize()
 
     # ---- timed region: K steps, with the dominant kernel bracketed by HIP events ----
     L = sh.n_layers
@@ -114,8 +134,17 @@ def main() -> int:
     stage.profile_begin(B.K_GEMM_GATEUP, args.steps * L, every=sample)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
-    for _ in range(args.steps):
-        step()
+    if args.graph:
+        # replays carry no events: every `sample`-th step is launched eagerly instead (same device work),
+        # and one of its gate/up launches is bracketed
+        for i in range(args.steps):
+            if i % sample == 0:
+                eager_step()
+            else:
+                step()
+    else:
+        for _ in range(args.steps):
+            step()
     t_enq = time.perf_counter()
     torch.cuda.synchronize()
     t2 = time.perf_counter()
@@ -139,6 +168,27 @@ def main() -> int:
     # whole-step view against the HBM floor: all stage weights once + the KV the attention reads
     step_bytes = sh.params_per_layer * 2 * L + L * (P + n) * sh.kv_bytes_per_token_per_layer
     step_frac = step_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS
+
+    # informational: the same step replayed from a HIP graph captured by the caller (no host work per step)
+    replay_ms = None
+    if not args.graph:
+        eager = eager_step if args.graph else step
+        gr = torch.cuda.CUDAGraph()
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            with torch.cuda.graph(gr, stream=side):
+                eager()
+        torch.cuda.current_stream().wait_stream(side)
+        for _ in range(5):
+            gr.replay()
+        torch.cuda.synchronize()
+        tg = time.perf_counter()
+        for _ in range(100):
+            gr.replay()
+        torch.cuda.synchronize()
+        replay_ms = round((time.perf_counter() - tg) * 10.0, 4)
+        del gr
 
     kernels = None
     if args.kernels:
@@ -187,6 +237,7 @@ def main() -> int:
                    "seed": w.seed, "tree_nodes": n, "prefix_len": P, "layers": L,
                    "weights_layout": "row-major" if args.unpacked else "mfma-fragment (sp_pack_weights)"},
         "step_latency_us": round(ms_per_step * 1e3, 1),
+        "whole_step_graph_replay_ms": replay_ms,
         "host_enqueue_us_per_step": round((t_enq - t1) * 1e6 / args.steps, 1),
         "step_hbm_floor_frac": round(step_frac, 4),
         "roofline": roofline,

@@ -75,6 +75,7 @@ typedef enum sp_prune_mode { SP_ACCEPT = 0, SP_DROP = 1, SP_CLEAR = 2 } sp_prune
 /* sp_config.flags */
 #define SP_FLAG_SIMPLE_KERNELS 1u   /* use the plain (non-MFMA) kernels for every step */
 #define SP_FLAG_PACKED_WEIGHTS 2u   /* wqkv, wo, wgu, wd were re-laid by sp_pack_weights() (bf16 MFMA path only) */
+#define SP_FLAG_NO_GRAPHS 8u        /* never replay HIP graphs inside sp_stage_forward (see there) */
 #define SP_FLAG_PAGED_KV 4u         /* requests hold their cache in pages of page_slots slots (see below) */
 
 typedef struct sp_config {
@@ -333,9 +334,11 @@ typedef enum sp_kernel_kind {
   SP_K_TREE_INSERT = 9, SP_K_NORM = 10, SP_K_ROPE_KV = 11, SP_K_VERIFY_HEAD = 12, SP_K_KIND_COUNT = 13
 } sp_kernel_kind;
 int sp_profile_begin(sp_stage* stage, int32_t kind, int32_t max_launches);
-/* After sp_profile_begin: bracket only one launch in `every` of that kind (the events
- * themselves open a gap of a few microseconds around the launch they bracket, so a timed
- * run samples instead of bracketing every launch). */
+/* After sp_profile_begin: sample.  Launches of that kind inside sp_stage_forward are taken
+ * call by call: every `every`-th call has all its launches of the kind bracketed, the other
+ * calls none (outside sp_stage_forward: one launch in `every`).  The events open a gap of a
+ * few microseconds around the launch they bracket and keep the call from replaying its
+ * graph, so a timed run samples instead of bracketing every launch. */
 int sp_profile_sample_every(sp_stage* stage, int32_t every);
 int sp_profile_end(sp_stage* stage, int32_t* n_launches, float* total_ms);
 

@@ -22,6 +22,7 @@ SP_ACCEPT, SP_DROP, SP_CLEAR = 0, 1, 2
 SP_FLAG_SIMPLE_KERNELS = 1
 SP_FLAG_PACKED_WEIGHTS = 2
 SP_FLAG_PAGED_KV = 4
+SP_FLAG_NO_GRAPHS = 8
 
 # sp_kernel_kind
 K_GEMM_QKV, K_GEMM_O, K_GEMM_GATEUP, K_GEMM_DOWN = 1, 2, 3, 4

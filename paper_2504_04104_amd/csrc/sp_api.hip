@@ -40,6 +40,7 @@ struct Workspace {
   void* act = nullptr;
   float* part = nullptr;
   float* attn_part = nullptr;
+  AttnPlan* plan = nullptr;            // device copy of the current call's plan
   size_t part_floats = 0;
   size_t attn_units = 0;
   size_t total = 0;
@@ -74,6 +75,7 @@ Workspace carve(const sp_config& c, char* base) {
   // split-KV attention partials: (max, sum, d_head outputs) per (row, head, chunk)
   w.attn_units = (MB > 64 ? MB : 64) * (size_t)c.n_q_heads * 32;
   w.attn_part = (float*)take(w.attn_units * (size_t)(c.d_head + 2) * sizeof(float));
+  w.plan = (AttnPlan*)take(sizeof(AttnPlan));
   w.total = off;
   return w;
 }
@@ -119,13 +121,26 @@ struct sp_stage {
   int n_pages = 0;
   int* d_page_table = nullptr;
   std::vector<int> free_pages;
+  // Forward calls of a shape seen before replay a HIP graph of their launches (all but the first
+  // and the last kernel, which carry the caller's pointers and the call's plan).
+  struct FwdGraph {
+    int M, qt, items, any_split, units;
+    int seen;
+    int S_last;                // split count of the last layer's down projection (the write-out folds it)
+    bool failed;
+    hipGraphExec_t exec;
+  };
+  std::vector<FwdGraph> graphs;
+  bool use_graphs = true;
   bool fast = false;           // bf16 MFMA kernels in use
   bool packed = false;         // weights are in MFMA fragment order
   int n_cu = 256;              // compute units of the device
   int last_hip = 0;
   // profiling
   int prof_kind = 0, prof_max = 0, prof_n = 0;
-  int prof_every = 1, prof_seen = 0;   // bracket one launch in prof_every of the profiled kind
+  // Sampling: launches of the profiled kind are counted in groups (the launches of one forward call);
+  // every prof_every-th group is bracketed, the others run untouched (and may replay a graph).
+  int prof_every = 1, prof_seen = 0, prof_group = 1;
   std::vector<hipEvent_t> prof_ev;
 };
 
@@ -143,7 +158,8 @@ struct ProfScope {
   bool on;
   ProfScope(sp_stage* s_, int kind, hipStream_t st_) : s(s_), st(st_) {
     on = false;
-    if (s->prof_kind == kind && s->prof_n < s->prof_max) on = (s->prof_seen++ % s->prof_every) == 0;
+    if (s->prof_kind == kind && s->prof_n < s->prof_max)
+      on = ((s->prof_seen++ / s->prof_group) % s->prof_every) == 0;
     if (on) (void)hipEventRecord(s->prof_ev[2 * s->prof_n], st);
   }
   ~ProfScope() {
@@ -298,6 +314,7 @@ int sp_stage_create(const sp_config* cfg, const sp_layer_weights* layers, const 
         hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && cus > 0)
       s->n_cu = cus;
   }
+  s->use_graphs = !(cfg->flags & SP_FLAG_NO_GRAPHS);
   s->packed = (cfg->flags & SP_FLAG_PACKED_WEIGHTS) != 0;
   if (s->packed && !s->fast) { delete s; return SP_E_UNSUPPORTED; }
   hipError_t e = sp_launch_tables_clear(s->d_meta, s->d_tables, cfg->max_requests, (hipStream_t)stream);
@@ -309,6 +326,7 @@ int sp_stage_create(const sp_config* cfg, const sp_layer_weights* layers, const 
 void sp_stage_destroy(sp_stage* stage) {
   if (!stage) return;
   for (hipEvent_t ev : stage->prof_ev) (void)hipEventDestroy(ev);
+  for (auto& g : stage->graphs) if (g.exec) (void)hipGraphExecDestroy(g.exec);
   delete stage;
 }
 
@@ -515,10 +533,17 @@ int sp_stage_forward(sp_stage* s, int32_t n_req, const int32_t* req_ids, const i
 #define SP_TRY(call) do { e = (call); if (e != hipSuccess) return hip_fail(s, e); } while (0)
 
   AttnPlan plan;
+  std::memset(&plan, 0, sizeof(plan));
+  plan.n_seg = b.n_req;
+  for (int i = 0; i < b.n_req; ++i) {              // which request and node each row belongs to
+    const HostReq& r = s->reqs[b.req[i]];
+    plan.seg_row0[i] = b.row0[i]; plan.seg_rows[i] = b.n[i]; plan.seg_req[i] = b.req[i];
+    plan.seg_first[i] = b.first[i]; plan.seg_P[i] = r.P; plan.seg_T[i] = r.T; plan.seg_base[i] = r.base;
+    plan.seg_chunks[i] = 1;
+  }
   if (s->fast) {
     // Split every request's cache range into chunks so that the grid fills the chip
     // and the partial results fit the workspace.
-    plan.n_seg = b.n_req;
     const int g = nq / nkv;
     int maxq = 0;
     for (int i = 0; i < b.n_req; ++i) if (b.n[i] * g > maxq) maxq = b.n[i] * g;
@@ -541,8 +566,6 @@ int sp_stage_forward(sp_stage* s, int32_t n_req, const int32_t* req_ids, const i
         chunks = (span + clen - 1) / clen;
         const int qblocks = (b.n[i] * g + qrows_per_block - 1) / qrows_per_block;
         plan.seg_item0[i] = items; plan.seg_chunks[i] = chunks; plan.seg_clen[i] = clen; plan.seg_qblocks[i] = qblocks;
-        plan.seg_row0[i] = b.row0[i]; plan.seg_rows[i] = b.n[i]; plan.seg_req[i] = b.req[i];
-        plan.seg_first[i] = b.first[i]; plan.seg_P[i] = r.P; plan.seg_T[i] = r.T; plan.seg_base[i] = r.base;
         plan.seg_unit0[i] = (int)units;
         items += chunks * qblocks;
         if (chunks > 1) { units += (size_t)chunks * b.n[i] * nq; split = 1; }
@@ -563,7 +586,6 @@ int sp_stage_forward(sp_stage* s, int32_t n_req, const int32_t* req_ids, const i
     if (units > w.attn_units) return SP_E_CAPACITY;
   }
 
-  int S_prev = 0;                                   // split count of the previous layer's down projection
   const size_t strideD = (size_t)M * d, strideQ = (size_t)M * nqkv;
   // projections: few rows stream the weights (HBM-bound); many rows use the register-blocked kernel
   const bool wide = s->fast && M > 128 && nqkv % 256 == 0 && d % 256 == 0 && F % 128 == 0 && dq % 128 == 0;
@@ -574,49 +596,122 @@ int sp_stage_forward(sp_stage* s, int32_t n_req, const int32_t* req_ids, const i
     return sp_launch_gemm_bf16((const bf16_t*)X, (const bf16_t*)Wm, s->packed, w.part, M, N_, K_, 16, w.part_floats,
                                S_, st);
   };
-  for (int l = 0; l < c.n_layers; ++l) {
-    const sp_layer_weights& L = s->W[l];
-    { ProfScope p(s, SP_K_NORM, st);
-      if (l == 0)
-        SP_TRY(sp_launch_enter_norm(dt, x_in, b, s->d_meta, s->d_tables, w.rows, w.cs, dh, c.rope_theta, w.h, L.norm1,
-                                    w.xn, M, d, c.rms_eps, st));
-      else
-        SP_TRY(sp_launch_add_norm(dt, w.h, w.part, S_prev, strideD, L.norm1, w.xn, M, d, c.rms_eps, st)); }
-    int S = 1;
-    { ProfScope p(s, SP_K_GEMM_QKV, st);
-      if (s->fast) SP_TRY(gemm(w.xn, L.wqkv, nqkv, d, &S));
-      else SP_TRY(sp_launch_gemm_simple(dt, w.xn, L.wqkv, w.part, M, nqkv, d, st)); }
-    { ProfScope p(s, SP_K_ROPE_KV, st);
-      SP_TRY(sp_launch_rope_kv(dt, w.part, S, strideQ, w.rows, w.cs, w.qbuf, s->geom, l, M, nq, nkv, dh, st)); }
-    if (s->fast) {
-      ProfScope p(s, SP_K_ATTENTION, st);
-      SP_TRY(sp_launch_attn_bf16((const bf16_t*)w.qbuf, s->d_tables, s->geom, l, plan, w.attn_part,
-                                 (bf16_t*)w.attn, M, nq, nkv, dh, st));
-    } else {
-      ProfScope p(s, SP_K_ATTENTION, st);
-      SP_TRY(sp_launch_attn_simple(dt, w.qbuf, w.rows, s->d_tables, s->geom, l, w.attn, M, nq, nkv, dh, st));
-    }
-    { ProfScope p(s, SP_K_GEMM_O, st);
-      S = 1;
-      if (s->fast) SP_TRY(gemm(w.attn, L.wo, d, dq, &S));
-      else SP_TRY(sp_launch_gemm_simple(dt, w.attn, L.wo, w.part, M, d, dq, st)); }
-    { ProfScope p(s, SP_K_NORM, st);
-      SP_TRY(sp_launch_add_norm(dt, w.h, w.part, S, strideD, L.norm2, w.xn, M, d, c.rms_eps, st)); }
-    { ProfScope p(s, SP_K_GEMM_GATEUP, st);
+  // Everything between the kernel that opens the call (rows enter, first RMSNorm, plan to device
+  // memory) and the one that writes the result out.  No argument of these launches depends on the
+  // caller's pointers or on the plan's contents, only on M and on the grid sizes the plan implies.
+  int S_last = 0;
+#define SP_STEP(call) do { hipError_t e_ = (call); if (e_ != hipSuccess) return e_; } while (0)
+  auto run_layers = [&]() -> hipError_t {
+    int S_prev = 0;                                 // split count of the previous layer's down projection
+    for (int l = 0; l < c.n_layers; ++l) {
+      const sp_layer_weights& L = s->W[l];
+      if (l > 0) {
+        ProfScope p(s, SP_K_NORM, st);
+        SP_STEP(sp_launch_add_norm(dt, w.h, w.part, S_prev, strideD, L.norm1, w.xn, M, d, c.rms_eps, st));
+      }
+      int S = 1;
+      { ProfScope p(s, SP_K_GEMM_QKV, st);
+        if (s->fast) SP_STEP(gemm(w.xn, L.wqkv, nqkv, d, &S));
+        else SP_STEP(sp_launch_gemm_simple(dt, w.xn, L.wqkv, w.part, M, nqkv, d, st)); }
+      { ProfScope p(s, SP_K_ROPE_KV, st);
+        SP_STEP(sp_launch_rope_kv(dt, w.part, S, strideQ, w.rows, w.cs, w.qbuf, s->geom, l, M, nq, nkv, dh, st)); }
       if (s->fast) {
-        if (wide) SP_TRY(sp_launch_gemm_wide_gateup((const bf16_t*)w.xn, (const bf16_t*)L.wgu, s->packed, (bf16_t*)w.act, M, F, d, st));
-        else SP_TRY(sp_launch_gemm_gateup_bf16((const bf16_t*)w.xn, (const bf16_t*)L.wgu, s->packed, (bf16_t*)w.act, M, F, d, st));
+        ProfScope p(s, SP_K_ATTENTION, st);
+        SP_STEP(sp_launch_attn_bf16((const bf16_t*)w.qbuf, s->d_tables, s->geom, l, plan, w.plan, w.attn_part,
+                                    (bf16_t*)w.attn, M, nq, nkv, dh, st));
       } else {
-        SP_TRY(sp_launch_gemm_simple(dt, w.xn, L.wgu, w.part, M, 2 * F, d, st));
-        SP_TRY(sp_launch_silu_mul(dt, w.part, w.act, M, F, st));
-      } }
-    { ProfScope p(s, SP_K_GEMM_DOWN, st);
-      S = 1;
-      if (s->fast) SP_TRY(gemm(w.act, L.wd, d, F, &S));
-      else SP_TRY(sp_launch_gemm_simple(dt, w.act, L.wd, w.part, M, d, F, st)); }
-    S_prev = S;
+        ProfScope p(s, SP_K_ATTENTION, st);
+        SP_STEP(sp_launch_attn_simple(dt, w.qbuf, w.rows, s->d_tables, s->geom, l, w.attn, M, nq, nkv, dh, st));
+      }
+      { ProfScope p(s, SP_K_GEMM_O, st);
+        S = 1;
+        if (s->fast) SP_STEP(gemm(w.attn, L.wo, d, dq, &S));
+        else SP_STEP(sp_launch_gemm_simple(dt, w.attn, L.wo, w.part, M, d, dq, st)); }
+      { ProfScope p(s, SP_K_NORM, st);
+        SP_STEP(sp_launch_add_norm(dt, w.h, w.part, S, strideD, L.norm2, w.xn, M, d, c.rms_eps, st)); }
+      { ProfScope p(s, SP_K_GEMM_GATEUP, st);
+        if (s->fast) {
+          if (wide) SP_STEP(sp_launch_gemm_wide_gateup((const bf16_t*)w.xn, (const bf16_t*)L.wgu, s->packed, (bf16_t*)w.act, M, F, d, st));
+          else SP_STEP(sp_launch_gemm_gateup_bf16((const bf16_t*)w.xn, (const bf16_t*)L.wgu, s->packed, (bf16_t*)w.act, M, F, d, st));
+        } else {
+          SP_STEP(sp_launch_gemm_simple(dt, w.xn, L.wgu, w.part, M, 2 * F, d, st));
+          SP_STEP(sp_launch_silu_mul(dt, w.part, w.act, M, F, st));
+        } }
+      { ProfScope p(s, SP_K_GEMM_DOWN, st);
+        S = 1;
+        if (s->fast) SP_STEP(gemm(w.act, L.wd, d, F, &S));
+        else SP_STEP(sp_launch_gemm_simple(dt, w.act, L.wd, w.part, M, d, F, st)); }
+      S_prev = S;
+    }
+    S_last = S_prev;
+    return hipSuccess;
+  };
+#undef SP_STEP
+
+  { ProfScope p(s, SP_K_NORM, st);
+    SP_TRY(sp_launch_enter_norm(dt, x_in, plan, s->fast ? w.plan : nullptr, s->d_meta, s->d_tables, w.rows, w.cs, dh,
+                                c.rope_theta, w.h, s->W[0].norm1, w.xn, M, d, c.rms_eps, st)); }
+
+  // A shape that comes back replays its graph; one seen for the second time is captured.  Not while a
+  // kernel kind is being timed (the events sit between the launches) and not inside a caller's capture.
+  sp_stage::FwdGraph* fg = nullptr;
+  bool timed = false;                               // an event bracket falls inside this call's layers
+  int n_kind = 0;                                   // launches of the timed kind among them
+  if (s->prof_kind != 0) {
+    const int k = s->prof_kind;
+    if (k == SP_K_GEMM_QKV || k == SP_K_GEMM_O || k == SP_K_GEMM_GATEUP || k == SP_K_GEMM_DOWN ||
+        k == SP_K_ATTENTION || k == SP_K_ROPE_KV) n_kind = c.n_layers;
+    else if (k == SP_K_NORM) n_kind = 2 * c.n_layers - 1;
+    if (n_kind > 0) {
+      // whole calls are sampled: align the count to this call's group of launches
+      s->prof_group = n_kind;
+      s->prof_seen = (s->prof_seen + n_kind - 1) / n_kind * n_kind;
+      timed = s->prof_n < s->prof_max && ((s->prof_seen / n_kind) % s->prof_every) == 0;
+    }
   }
-  SP_TRY(sp_launch_finish(dt, w.h, w.part, S_prev, strideD, x_out, M, d, st));
+  if (s->use_graphs && s->fast && !timed) {
+    hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(st, &cap) == hipSuccess && cap == hipStreamCaptureStatusNone) {
+      for (auto& g : s->graphs)
+        if (g.M == M && g.qt == plan.qt && g.items == plan.total_items && g.any_split == plan.any_split &&
+            g.units == plan.units_total) { fg = &g; break; }
+      if (!fg && s->graphs.size() < 256) {
+        s->graphs.push_back({M, plan.qt, plan.total_items, plan.any_split, plan.units_total, 0, 0, false, nullptr});
+        fg = &s->graphs.back();
+      }
+    }
+  }
+  bool done = false;
+  if (fg) {
+    ++fg->seen;
+    if (!fg->exec && !fg->failed && fg->seen >= 2) {
+      hipGraph_t graph = nullptr;
+      if (hipStreamBeginCapture(st, hipStreamCaptureModeThreadLocal) == hipSuccess) {
+        const hipError_t e_run = run_layers();
+        const hipError_t e_end = hipStreamEndCapture(st, &graph);
+        if (e_run == hipSuccess && e_end == hipSuccess && graph &&
+            hipGraphInstantiate(&fg->exec, graph, nullptr, nullptr, 0) == hipSuccess) {
+          fg->S_last = S_last;
+        } else {
+          fg->exec = nullptr;
+          fg->failed = true;
+          (void)hipGetLastError();
+        }
+        if (graph) (void)hipGraphDestroy(graph);
+      } else {
+        fg->failed = true;
+        (void)hipGetLastError();
+      }
+    }
+    if (fg->exec) {
+      SP_TRY(hipGraphLaunch(fg->exec, st));
+      S_last = fg->S_last;
+      s->prof_seen += n_kind;                       // the sampling cadence counts the replayed launches too
+      done = true;
+    }
+  }
+  if (!done) SP_TRY(run_layers());
+  SP_TRY(sp_launch_finish(dt, w.h, w.part, S_last, strideD, x_out, M, d, st));
 #undef SP_TRY
   for (int i = 0; i < b.n_req; ++i) {
     HostReq& r = s->reqs[b.req[i]];
@@ -805,8 +900,15 @@ int sp_stage_verify_head(sp_stage* s, const sp_head_weights* head, int32_t n_req
   Workspace& w = s->ws;
   hipError_t e;
   // final RMSNorm (the row descriptors and the float copy of x it also writes are scratch here)
-  e = sp_launch_enter_norm(c.dtype, x, b, s->d_meta, s->d_tables, w.rows, w.cs, c.d_head, c.rope_theta, w.h,
-                           head->norm, w.xn, M, d, c.rms_eps, st);
+  AttnPlan rows_of;                                   // only the segment fields are read
+  std::memset(&rows_of, 0, sizeof(rows_of));
+  rows_of.n_seg = b.n_req;
+  for (int i = 0; i < b.n_req; ++i) {
+    rows_of.seg_row0[i] = b.row0[i]; rows_of.seg_rows[i] = b.n[i]; rows_of.seg_req[i] = b.req[i];
+    rows_of.seg_first[i] = b.first[i];
+  }
+  e = sp_launch_enter_norm(c.dtype, x, rows_of, nullptr, s->d_meta, s->d_tables, w.rows, w.cs, c.d_head, c.rope_theta,
+                           w.h, head->norm, w.xn, M, d, c.rms_eps, st);
   if (e != hipSuccess) return hip_fail(s, e);
   ProfScope p(s, SP_K_VERIFY_HEAD, st);
   if (s->fast && V % 64 == 0 && d % 128 == 0) {
@@ -873,7 +975,7 @@ int sp_profile_begin(sp_stage* s, int32_t kind, int32_t max_launches) {
     s->prof_ev.push_back(ev);
   }
   s->prof_kind = kind; s->prof_max = max_launches; s->prof_n = 0;
-  s->prof_every = 1; s->prof_seen = 0;
+  s->prof_every = 1; s->prof_seen = 0; s->prof_group = 1;
   return SP_OK;
 }
 

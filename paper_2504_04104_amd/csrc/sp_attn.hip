@@ -30,13 +30,14 @@ struct AttnArgs {
   const ReqTables* tables;
   KvGeom g;
   int layer, n_q, n_kv;
-  float* part_o;            // [units][DH]
-  float* part_ml;           // [units][2]
+  float* part_o;            // [units][DH], followed by [units][2] (running max, sum)
   bf16_t* out;              // [M][n_q][DH]
+  const AttnPlan* plan;     // device copy of the call's plan (written by the kernel that opens the forward)
 };
 
 template <int QT, bool PAGED>
-__global__ void __launch_bounds__(64 * AW) k_attn_bf16(AttnArgs a, AttnPlan plan) {
+__global__ void __launch_bounds__(64 * AW) k_attn_bf16(AttnArgs a) {
+  const AttnPlan& plan = *a.plan;
   // V tiles of the eight waves; the same bytes later carry the states being folded
   // (four waves x QT x 8 d-tiles x 64 lanes x 16 B = QT * 32 KB <= 8 * VT_BYTES for QT <= 2).
   __shared__ __attribute__((aligned(16))) char s_v[AW * VT_BYTES];
@@ -291,6 +292,7 @@ __global__ void __launch_bounds__(64 * AW) k_attn_bf16(AttnArgs a, AttnPlan plan
   // ---- wave 0 writes the block's result --------------------------------------------
   // o[t][2G+h][i] is output column G*32 + 2*(4*kg+i) + h of query row t*16 + l15.
   const size_t unit0 = (size_t)plan.seg_unit0[seg] + (size_t)ch * seg_rows * a.n_q;
+  float* part_ml = a.part_o + (size_t)plan.units_total * DH;
 #pragma unroll
   for (int t = 0; t < QT; ++t) {
     if (!qrow_ok[t]) continue;
@@ -320,7 +322,7 @@ __global__ void __launch_bounds__(64 * AW) k_attn_bf16(AttnArgs a, AttnPlan plan
         *reinterpret_cast<f32x4_t*>(po + G * 32 + 8 * kg) = lo;
         *reinterpret_cast<f32x4_t*>(po + G * 32 + 8 * kg + 4) = hi;
       }
-      if (kg == 0) { a.part_ml[unit * 2] = mall[t]; a.part_ml[unit * 2 + 1] = lrun[t]; }
+      if (kg == 0) { part_ml[unit * 2] = mall[t]; part_ml[unit * 2 + 1] = lrun[t]; }
     }
   }
 }
@@ -328,7 +330,9 @@ __global__ void __launch_bounds__(64 * AW) k_attn_bf16(AttnArgs a, AttnPlan plan
 // One wave per (row, query head) of the requests that were cut into several chunks: combine the
 // chunk partials (log2-domain maxima).  Lane c first takes chunk c's (max, sum) and turns them into
 // the chunk's weight; the outputs are then accumulated chunk by chunk, two columns per lane.
-__global__ void __launch_bounds__(256) k_attn_merge(AttnArgs a, AttnPlan plan, int M) {
+__global__ void __launch_bounds__(256) k_attn_merge(AttnArgs a, int M) {
+  const AttnPlan& plan = *a.plan;
+  const float* part_ml = a.part_o + (size_t)plan.units_total * DH;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int item = blockIdx.x * 4 + wave;
   if (item >= M * a.n_q) return;
@@ -344,7 +348,7 @@ __global__ void __launch_bounds__(256) k_attn_merge(AttnArgs a, AttnPlan plan, i
     const int c = c0 + lane;
     float m = -INFINITY, l = 0.f;
     if (c < chunks) {
-      const float2 ml = *reinterpret_cast<const float2*>(a.part_ml + (u0 + c * stride) * 2);
+      const float2 ml = *reinterpret_cast<const float2*>(part_ml + (u0 + c * stride) * 2);
       m = ml.x; l = ml.y;
     }
     const float bm = wave_max(m);
@@ -381,27 +385,28 @@ __global__ void __launch_bounds__(256) k_attn_merge(AttnArgs a, AttnPlan plan, i
 }
 
 hipError_t sp_launch_attn_bf16(const bf16_t* q, const ReqTables* tables, KvGeom g, int layer, const AttnPlan& plan,
-                               float* part, bf16_t* out, int M, int n_q, int n_kv, int d_head, hipStream_t st) {
+                               const AttnPlan* plan_dev, float* part, bf16_t* out, int M, int n_q, int n_kv,
+                               int d_head, hipStream_t st) {
   if (d_head != DH || g.row_bytes != 256) return hipErrorInvalidValue;
   AttnArgs a;
   a.q = q; a.tables = tables; a.g = g; a.layer = layer; a.n_q = n_q; a.n_kv = n_kv;
   a.part_o = part;
-  a.part_ml = part + (size_t)plan.units_total * DH;
   a.out = out;
+  a.plan = plan_dev;
   dim3 grid(plan.total_items * n_kv);
   switch (plan.qt) {
     case 1:
-      if (g.page_table) hipLaunchKernelGGL((k_attn_bf16<1, true>), grid, dim3(64 * AW), 0, st, a, plan);
-      else hipLaunchKernelGGL((k_attn_bf16<1, false>), grid, dim3(64 * AW), 0, st, a, plan);
+      if (g.page_table) hipLaunchKernelGGL((k_attn_bf16<1, true>), grid, dim3(64 * AW), 0, st, a);
+      else hipLaunchKernelGGL((k_attn_bf16<1, false>), grid, dim3(64 * AW), 0, st, a);
       break;
     case 2:
-      if (g.page_table) hipLaunchKernelGGL((k_attn_bf16<2, true>), grid, dim3(64 * AW), 0, st, a, plan);
-      else hipLaunchKernelGGL((k_attn_bf16<2, false>), grid, dim3(64 * AW), 0, st, a, plan);
+      if (g.page_table) hipLaunchKernelGGL((k_attn_bf16<2, true>), grid, dim3(64 * AW), 0, st, a);
+      else hipLaunchKernelGGL((k_attn_bf16<2, false>), grid, dim3(64 * AW), 0, st, a);
       break;
     default: return hipErrorInvalidValue;
   }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess || !plan.any_split) return e;
-  hipLaunchKernelGGL(k_attn_merge, dim3((M * n_q + 3) / 4), dim3(256), 0, st, a, plan, M);
+  hipLaunchKernelGGL(k_attn_merge, dim3((M * n_q + 3) / 4), dim3(256), 0, st, a, M);
   return hipGetLastError();
 }

@@ -45,12 +45,36 @@ hipError_t sp_launch_kv_compact(const ReqMeta* meta, const ReqTables* tables, co
 hipError_t sp_launch_rows_compact(void* rows, size_t row_stride_bytes, int row_bytes, const RowList& l,
                                   hipStream_t st);
 
+// A forward call's requests (segments) and the split of its attention work, made on the host.
+struct AttnPlan {          // host-made split of a forward call's attention work
+  int n_seg;
+  int qt;                  // 16-row query tiles per wave: 1 or 2
+  int units_total;         // partial-result units: sum over split segments of chunks * rows * n_q
+  int total_items;         // sum over segments of q_blocks * chunks
+  int any_split;           // some segment has more than one chunk: the merge kernel must run
+  int seg_item0[SP_BATCH + 1];   // first work item of each segment
+  int seg_chunks[SP_BATCH];
+  int seg_clen[SP_BATCH];  // slots per chunk of the segment (multiple of 32)
+  int seg_qblocks[SP_BATCH];
+  int seg_unit0[SP_BATCH];
+  int seg_row0[SP_BATCH];  // first row of the call that belongs to the segment
+  int seg_rows[SP_BATCH];
+  int seg_req[SP_BATCH];
+  int seg_first[SP_BATCH]; // first node of the segment
+  int seg_P[SP_BATCH];     // host mirror of prefix length and live nodes
+  int seg_T[SP_BATCH];
+  long long seg_base[SP_BATCH];
+};
+
 // ---- elementwise / row kernels --------------------------------------------------
 // Rows enter the stage: row descriptors and rotary tables (cs: [rows][d_head], cos then sin),
 // h = x, xn = rmsnorm(h) * gain.
-hipError_t sp_launch_enter_norm(int dtype, const void* x, const FwdBatch& b, const ReqMeta* meta,
-                                const ReqTables* tables, RowInfo* rows, float* cs, int d_head, float theta, float* h,
-                                const void* gain, void* xn, int M, int d, float eps, hipStream_t st);
+// The segment fields of `plan` say which request and node each row belongs to; if plan_dev is given the
+// whole plan is also stored there for the attention kernels of the call.
+hipError_t sp_launch_enter_norm(int dtype, const void* x, const AttnPlan& plan, AttnPlan* plan_dev /*nullable*/,
+                                const ReqMeta* meta, const ReqTables* tables, RowInfo* rows, float* cs, int d_head,
+                                float theta, float* h, const void* gain, void* xn, int M, int d, float eps,
+                                hipStream_t st);
 
 // h += sum_s part[s]; xn = rmsnorm(h) * gain
 hipError_t sp_launch_add_norm(int dtype, float* h, const float* part, int S, size_t part_stride,
@@ -91,25 +115,7 @@ hipError_t sp_launch_pack_weights(const void* in, void* out, int N, int K, hipSt
 hipError_t sp_launch_attn_simple(int dtype, const void* q, const RowInfo* rows, const ReqTables* tables, KvGeom g,
                                  int layer, void* out, int M, int n_q, int n_kv, int d_head, hipStream_t st);
 
-struct AttnPlan {          // host-made split of a forward call's attention work
-  int n_seg;
-  int qt;                  // 16-row query tiles per wave: 1 or 2
-  int units_total;         // partial-result units: sum over split segments of chunks * rows * n_q
-  int total_items;         // sum over segments of q_blocks * chunks
-  int any_split;           // some segment has more than one chunk: the merge kernel must run
-  int seg_item0[SP_BATCH + 1];   // first work item of each segment
-  int seg_chunks[SP_BATCH];
-  int seg_clen[SP_BATCH];  // slots per chunk of the segment (multiple of 32)
-  int seg_qblocks[SP_BATCH];
-  int seg_unit0[SP_BATCH];
-  int seg_row0[SP_BATCH];  // first row of the call that belongs to the segment
-  int seg_rows[SP_BATCH];
-  int seg_req[SP_BATCH];
-  int seg_first[SP_BATCH]; // first node of the segment
-  int seg_P[SP_BATCH];     // host mirror of prefix length and live nodes
-  int seg_T[SP_BATCH];
-  long long seg_base[SP_BATCH];
-};
+// plan: host copy (grid sizes); plan_dev: the device copy the kernels read
 hipError_t sp_launch_attn_bf16(const bf16_t* q, const ReqTables* tables, KvGeom g, int layer, const AttnPlan& plan,
-                               float* part /*workspace*/, bf16_t* out, int M, int n_q, int n_kv, int d_head,
-                               hipStream_t st);
+                               const AttnPlan* plan_dev, float* part /*workspace*/, bf16_t* out, int M, int n_q,
+                               int n_kv, int d_head, hipStream_t st);

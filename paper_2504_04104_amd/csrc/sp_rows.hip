@@ -57,21 +57,32 @@ __device__ __forceinline__ f32x4_t fold4(const float* p, int S, size_t stride) {
 //          positions of tens of thousands keep full float accuracy in cos and sin.
 //   else:  h[row] += sum_s part[s][row].
 // Then xn[row] = h * rsqrt(mean(h^2)+eps) * gain.  The first two passes stay in registers.
+struct NoPlan { int unused; };
+template <bool FIRST> struct PlanArg { typedef NoPlan type; };
+template <> struct PlanArg<true> { typedef AttnPlan type; };
+
 template <typename T, bool FIRST>
 __global__ void __launch_bounds__(1024) k_add_norm(float* h, const float* part, int S, size_t part_stride,
-                                                    const T* gain, T* xn, int d, float eps, const T* x, FwdBatch b,
+                                                    const T* gain, T* xn, int d, float eps, const T* x,
+                                                    typename PlanArg<FIRST>::type b, AttnPlan* plan_dev,
                                                     const ReqMeta* meta, const ReqTables* tables, RowInfo* rows,
                                                     float* cs, int d_head, float theta) {
   __shared__ float s_red[16];
   const int row = blockIdx.x;
-  if (FIRST) {
+  if constexpr (FIRST) {
+    // the call's plan goes to device memory for the kernels that follow
+    if (plan_dev && row == 0) {
+      const uint32_t* src = reinterpret_cast<const uint32_t*>(&b);
+      uint32_t* dst = reinterpret_cast<uint32_t*>(plan_dev);
+      for (int i = threadIdx.x; i < (int)(sizeof(AttnPlan) / 4); i += blockDim.x) dst[i] = src[i];
+    }
     const int half = d_head >> 1;
     if ((int)threadIdx.x < half) {
       const int tt = threadIdx.x;
       int seg = 0;
-      while (seg + 1 < b.n_req && row >= b.row0[seg + 1]) ++seg;
-      const int req = b.req[seg];
-      const int node = b.first[seg] + (row - b.row0[seg]);
+      while (seg + 1 < b.n_seg && row >= b.seg_row0[seg + 1]) ++seg;
+      const int req = b.seg_req[seg];
+      const int node = b.seg_first[seg] + (row - b.seg_row0[seg]);
       const ReqMeta m = meta[req];
       const int pos = m.P + tables[req].depth[node];
       if (tt == 0) {
@@ -221,30 +232,32 @@ static inline int grid_for(size_t n, int block, int cap = 4096) {
   return (int)g;
 }
 
-hipError_t sp_launch_enter_norm(int dtype, const void* x, const FwdBatch& b, const ReqMeta* meta,
-                                const ReqTables* tables, RowInfo* rows, float* cs, int d_head, float theta, float* h,
-                                const void* gain, void* xn, int M, int d, float eps, hipStream_t st) {
+hipError_t sp_launch_enter_norm(int dtype, const void* x, const AttnPlan& plan, AttnPlan* plan_dev,
+                                const ReqMeta* meta, const ReqTables* tables, RowInfo* rows, float* cs, int d_head,
+                                float theta, float* h, const void* gain, void* xn, int M, int d, float eps,
+                                hipStream_t st) {
+  static_assert(sizeof(AttnPlan) % 4 == 0 && sizeof(AttnPlan) < 3900, "the plan travels as a kernel argument");
   if (dtype == 0)
     hipLaunchKernelGGL((k_add_norm<float, true>), dim3(M), dim3(1024), 0, st, h, nullptr, 0, 0, (const float*)gain,
-                       (float*)xn, d, eps, (const float*)x, b, meta, tables, rows, cs, d_head, theta);
+                       (float*)xn, d, eps, (const float*)x, plan, plan_dev, meta, tables, rows, cs, d_head, theta);
   else
     hipLaunchKernelGGL((k_add_norm<bf16_t, true>), dim3(M), dim3(1024), 0, st, h, nullptr, 0, 0,
-                       (const bf16_t*)gain, (bf16_t*)xn, d, eps, (const bf16_t*)x, b, meta, tables, rows, cs, d_head,
-                       theta);
+                       (const bf16_t*)gain, (bf16_t*)xn, d, eps, (const bf16_t*)x, plan, plan_dev, meta, tables, rows,
+                       cs, d_head, theta);
   return hipGetLastError();
 }
 
 hipError_t sp_launch_add_norm(int dtype, float* h, const float* part, int S, size_t part_stride, const void* gain,
                               void* xn, int M, int d, float eps, hipStream_t st) {
-  const FwdBatch none{};
+  const NoPlan none{0};
   if (dtype == 0)
     hipLaunchKernelGGL((k_add_norm<float, false>), dim3(M), dim3(1024), 0, st, h, part, S, part_stride,
-                       (const float*)gain, (float*)xn, d, eps, nullptr, none, nullptr, nullptr, nullptr, nullptr, 0,
-                       0.f);
+                       (const float*)gain, (float*)xn, d, eps, nullptr, none, nullptr, nullptr, nullptr, nullptr,
+                       nullptr, 0, 0.f);
   else
     hipLaunchKernelGGL((k_add_norm<bf16_t, false>), dim3(M), dim3(1024), 0, st, h, part, S, part_stride,
-                       (const bf16_t*)gain, (bf16_t*)xn, d, eps, nullptr, none, nullptr, nullptr, nullptr, nullptr, 0,
-                       0.f);
+                       (const bf16_t*)gain, (bf16_t*)xn, d, eps, nullptr, none, nullptr, nullptr, nullptr, nullptr,
+                       nullptr, 0, 0.f);
   return hipGetLastError();
 }
 

@@ -179,6 +179,38 @@ def test_paged_cache_f32_and_page_accounting():
     pair.close()
 
 
+def test_forward_replays_from_a_hip_graph():
+    """sp_stage_forward only enqueues kernels on the caller's stream (no allocation, no host wait, no
+    memset), so a caller may capture it into a HIP graph.  Replays are interleaved with eager calls and
+    host synchronisation, and each replay is compared with the eager result for the same input rows."""
+    shape = MINI_BF16
+    pair = Pair(shape, 26, {0: 90}, flags=sp.SP_FLAG_PACKED_WEIGHTS, oracle=True)
+    g = pair.gpu
+    n = 21
+    pair.insert(0, wl.tree_uniform_parents(26, n, 6, name=("g",)))
+    xs = [to_dev(wl.hidden_rows(shape, 26, ("g", i), n), g) for i in range(4)]
+    x = xs[0].clone()
+    y = torch.empty_like(x)
+    y_ref, ref = pair.forward([0], [0], [n], wl.hidden_rows(shape, 26, ("g", 0), n))     # eager, also warms up
+    assert rel_err(y_ref, ref) <= TOL["bf16"]
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            g.stage_forward([0], [0], [n], x, y)
+    torch.cuda.current_stream().wait_stream(side)
+    for i in (1, 2, 3, 0, 2):
+        x.copy_(xs[i])
+        graph.replay()
+        torch.cuda.synchronize()
+        got = y.clone()
+        eager = g.stage_forward([0], [0], [n], xs[i])                     # eager call between replays
+        torch.cuda.synchronize()
+        assert torch.equal(got.view(torch.int16), eager.view(torch.int16)), i
+    pair.close()
+
+
 def test_tables_only_random_sequences():
     """Insert / accept / drop sequences up to the 256-node cap: tables bit-exact after every call."""
     pair = Pair(MINI_F32, 14, {0: 5}, tree_room=4096)
