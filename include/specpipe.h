@@ -19,10 +19,13 @@
  *
  * Memory.  Every device byte is owned by the caller: weights, the KV slab, the
  * table arena and the workspace are passed in as device pointers and must stay
- * valid until sp_stage_destroy().  The library allocates no device memory and
- * creates no streams.  All device work of a call is enqueued on the stream
- * passed to it, in call order; calls return without waiting for the GPU unless
- * stated.  Host arrays passed in are read before the call returns.
+ * valid until sp_stage_destroy().  The library allocates no device memory of
+ * its own and creates no streams (the HIP graphs sp_stage_forward may build hold
+ * whatever the runtime needs for them).  All device work of a call is enqueued
+ * on the stream passed to it, in call order; calls return without waiting for
+ * the GPU unless stated.  Host arrays passed in are read before the call returns.
+ * One stream should carry all calls of a stage: the workspace, the page tables
+ * and the device copy of a call's plan are reused from call to call.
  *
  * KV slab layout (element type = config dtype), index order slowest to fastest:
  *     [layer][K=0|V=1][kv_head][slot][d_head]
@@ -227,7 +230,12 @@ int sp_tree_insert_batch(sp_stage* stage, int32_t n_req, const int32_t* req_ids 
  * itself and its ancestors.  x_in / x_out: device, [sum n_nodes][d_model] in the
  * config dtype, rows ordered by (position in req_ids, node index); they may alias.
  * The nodes' K and V rows are written to the slab.  A node's parent must have been
- * forwarded before or be part of this call (SP_E_ORDER).  A request may appear once. */
+ * forwarded before or be part of this call (SP_E_ORDER).  A request may appear once.
+ * Launch overhead: when a call has the same shape (rows, attention work items) as an
+ * earlier one, its launches except the first and the last are replayed from a HIP graph
+ * captured the second time that shape was seen; results are identical.  The call stays
+ * eager while the stream is being captured by the caller, while sp_profile_begin brackets
+ * fall into it, or with SP_FLAG_NO_GRAPHS. */
 int sp_stage_forward(sp_stage* stage, int32_t n_req, const int32_t* req_ids /*host*/,
                      const int32_t* first_node /*host*/, const int32_t* n_nodes /*host*/,
                      const void* x_in /*device*/, void* x_out /*device*/, sp_stream stream);

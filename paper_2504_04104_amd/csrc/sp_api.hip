@@ -1,5 +1,6 @@
 // Host side of the SpecPipe stage library: argument checks against a host mirror of
-// the tree, workspace carving, and the per-layer launch sequence.  No device memory
+// the tree, workspace carving, the page allocator of the paged cache, and the per-layer
+// launch sequence (replayed from a HIP graph for shapes seen before).  No device memory
 // is allocated here and nothing waits for the GPU except sp_tree_read and
 // sp_profile_end.
 #include <cmath>
