@@ -352,15 +352,16 @@ class Stage:
         assert cand_probs.is_contiguous() and cand_probs.dtype == torch.float32
         k = int(cand_tokens.shape[1])
         room = max(w, 1)
-        op = torch.empty(room, dtype=torch.int32, device=self.device)
-        ot = torch.empty(room, dtype=torch.int32, device=self.device)
-        oq = torch.empty(room, dtype=torch.float32, device=self.device)
-        oc = torch.zeros(1, dtype=torch.int32, device=self.device)
+        # one buffer for parents | tokens | probabilities (float bits) | count: one copy back to the host
+        out = torch.empty(3 * room + 1, dtype=torch.int32, device=self.device)
+        base = out.data_ptr()
         _check(self.lib.sp_tree_expand(self.handle, req, len(ba), bp, k, cand_tokens.data_ptr(), cand_probs.data_ptr(),
-                                       w, op.data_ptr(), ot.data_ptr(), oq.data_ptr(), oc.data_ptr(), self._stream()),
+                                       w, base, base + 4 * room, base + 8 * room, base + 12 * room, self._stream()),
                "sp_tree_expand")
-        n = int(oc.item())
-        return op[:n].tolist(), ot[:n].tolist(), oq[:n].tolist()
+        host = out.cpu().numpy()
+        n = int(host[3 * room])
+        return (host[:n].tolist(), host[room:room + n].tolist(),
+                host[2 * room:2 * room + n].view(np.float32).tolist())
 
     def set_root_pred(self, req: int, token: int):
         _check(self.lib.sp_request_set_root_pred(self.handle, req, token, self._stream()), "sp_request_set_root_pred")

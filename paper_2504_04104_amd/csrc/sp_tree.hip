@@ -334,52 +334,82 @@ hipError_t sp_launch_set_root_pred(ReqMeta* meta, int req, int token, hipStream_
 // proposal c % k) has cumulative probability P[ancestors, root first] * P[bottom] * p(c),
 // multiplied in that order in float32.  The w largest are kept (an earlier candidate wins a
 // tie) and come out in candidate order, which is parent order (Sec. 3.2 "Layer appending").
-// One workgroup; a candidate's rank is the number of candidates that beat it.
-__global__ void __launch_bounds__(256) k_tree_expand(const ReqTables* tables, ExpandArgs a, const int* cand_tok,
-                                                      const float* cand_prob, int* out_parent, int* out_token,
-                                                      float* out_prob, int* out_count) {
-  __shared__ float s_key[SP_EXPAND_MAX];
+// One workgroup of 1024 threads; a candidate's rank is the number of candidates that beat it.
+__global__ void __launch_bounds__(1024) k_tree_expand(const ReqTables* tables, ExpandArgs a, const int* cand_tok,
+                                                       const float* cand_prob, int* out_parent, int* out_token,
+                                                       float* out_prob, int* out_count) {
+  constexpr int PER = SP_EXPAND_MAX / 1024;          // candidates per thread at most
+  // sort key of a candidate: probability bits (non-negative floats order like their bit patterns) above
+  // the complemented index, so that one 64-bit comparison decides "beats": larger probability, or the
+  // same probability and an earlier place.  0 = absent.
+  __shared__ __attribute__((aligned(16))) unsigned long long s_key[SP_EXPAND_MAX];
   __shared__ unsigned char s_sel[SP_EXPAND_MAX];
-  __shared__ int s_cnt[256];
+  __shared__ int s_wave[16];
   const ReqTables& t = tables[a.req];
   const int C = a.n_bottom * a.k;
-  const int tid = threadIdx.x;
-  for (int c = tid; c < C; c += 256) {
-    const int node = a.bottom[c / a.k];
-    float base = 1.f;
-    if (node >= 0) {
+  const int C2 = (C + 1) & ~1;
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  for (int c = tid; c < C2; c += 1024) {
+    unsigned long long key = 0ull;
+    if (c < C && cand_tok[c] >= 0) {
+      const int node = a.bottom[c / a.k];
+      float base = 1.f;
+      if (node >= 0) {
 #pragma unroll
-      for (int w = 0; w < SP_W; ++w) {
-        unsigned long long bits = t.anc[node][w];
-        while (bits) {                                  // ascending index = from the root downwards
-          const int j = w * 64 + __ffsll((long long)bits) - 1;
-          bits &= bits - 1;
-          base = base * t.prob[j];
+        for (int w = 0; w < SP_W; ++w) {
+          unsigned long long bits = t.anc[node][w];
+          while (bits) {                              // ascending index = from the root downwards
+            const int j = w * 64 + __ffsll((long long)bits) - 1;
+            bits &= bits - 1;
+            base = base * t.prob[j];
+          }
         }
       }
+      const float cum = base * cand_prob[c];
+      // negative or NaN probabilities are outside the contract; they rank as absent
+      key = cum >= 0.f ? ((unsigned long long)__float_as_uint(cum + 0.f) << 32) | (unsigned long long)(0xffffffffu - (unsigned)c)
+                       : 0ull;
     }
-    s_key[c] = cand_tok[c] < 0 ? -1.f : base * cand_prob[c];
+    s_key[c] = key;
   }
   __syncthreads();
-  for (int c = tid; c < C; c += 256) {
-    const float key = s_key[c];
-    int rank = 0;
-    for (int o = 0; o < C; ++o) {
-      const float ko = s_key[o];
-      rank += (ko > key || (ko == key && o < c)) ? 1 : 0;
-    }
-    s_sel[c] = (key >= 0.f && rank < a.w) ? 1 : 0;
+  // rank of this thread's candidates (tid, tid + 1024, ...): one sweep over all keys, two per LDS read
+  const int per_rank = (C + 1023) / 1024;            // uniform: slots this launch uses
+  unsigned long long mykey[PER];
+  int rank[PER];
+#pragma unroll
+  for (int i = 0; i < PER; ++i) {
+    const int c = tid + i * 1024;
+    mykey[i] = c < C ? s_key[c] : ~0ull;
+    rank[i] = 0;
+  }
+  for (int o = 0; o < C2; o += 2) {
+    const unsigned long long k0 = s_key[o], k1 = s_key[o + 1];
+#pragma unroll
+    for (int i = 0; i < PER; ++i)
+      if (i < per_rank) rank[i] += (k0 > mykey[i] ? 1 : 0) + (k1 > mykey[i] ? 1 : 0);
+  }
+#pragma unroll
+  for (int i = 0; i < PER; ++i) {
+    const int c = tid + i * 1024;
+    if (c < C) s_sel[c] = (mykey[i] != 0ull && rank[i] < a.w) ? 1 : 0;
   }
   __syncthreads();
-  // ordered compaction: thread t owns candidates [t*per, (t+1)*per)
-  const int per = (C + 255) / 256;
+  // ordered compaction: thread t owns candidates [t*per, (t+1)*per); exclusive scan of the counts
+  const int per = (C + 1023) / 1024;
   const int lo = min(tid * per, C), hi = min(lo + per, C);
   int mine = 0;
   for (int c = lo; c < hi; ++c) mine += s_sel[c];
-  s_cnt[tid] = mine;
+  int incl = mine;
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) {
+    const int v = __shfl_up(incl, off, 64);
+    if (lane >= off) incl += v;
+  }
+  if (lane == 63) s_wave[wave] = incl;
   __syncthreads();
-  int pos = 0;
-  for (int i = 0; i < tid; ++i) pos += s_cnt[i];
+  int pos = incl - mine;
+  for (int w = 0; w < wave; ++w) pos += s_wave[w];
   for (int c = lo; c < hi; ++c) {
     if (!s_sel[c]) continue;
     out_parent[pos] = a.bottom[c / a.k];
@@ -387,13 +417,13 @@ __global__ void __launch_bounds__(256) k_tree_expand(const ReqTables* tables, Ex
     out_prob[pos] = cand_prob[c];
     ++pos;
   }
-  if (tid == 255) *out_count = pos;
+  if (tid == 1023) *out_count = pos;
 }
 
 hipError_t sp_launch_tree_expand(const ReqTables* tables, const ExpandArgs& a, const int* cand_tok,
                                  const float* cand_prob, int* out_parent, int* out_token, float* out_prob,
                                  int* out_count, hipStream_t st) {
-  hipLaunchKernelGGL(k_tree_expand, dim3(1), dim3(256), 0, st, tables, a, cand_tok, cand_prob, out_parent, out_token,
+  hipLaunchKernelGGL(k_tree_expand, dim3(1), dim3(1024), 0, st, tables, a, cand_tok, cand_prob, out_parent, out_token,
                      out_prob, out_count);
   return hipGetLastError();
 }
