@@ -361,6 +361,20 @@ __global__ void __launch_bounds__(256) k_attn_merge(AttnArgs a, int M) {
     lsum += wave_sum(wgt * l);
     const int nb = min(64, chunks - c0);
     int j = 0;
+    // sixteen chunks' partial rows in flight at a time: the loop is a chain of memory round trips otherwise
+    for (; j + 16 <= nb; j += 16) {
+      float o0[16], o1[16];
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        const float* po = a.part_o + (u0 + (size_t)(c0 + j + i) * stride) * DH;
+        o0[i] = po[lane]; o1[i] = po[64 + lane];
+      }
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        const float w1 = __shfl(wgt, j + i, 64);
+        acc0 += w1 * o0[i]; acc1 += w1 * o1[i];
+      }
+    }
     for (; j + 4 <= nb; j += 4) {
       float w4[4], o0[4], o1[4];
 #pragma unroll
