@@ -23,10 +23,12 @@ from .tree import SpecTree
 from .stage import (StageOracle, RequestState, rmsnorm, rope_rotate, silu, tree_attention,
                     decoder_layer)
 from .prune import (accept_masks, drop_masks, compact_rows, PruneResult)
-from .verify import lm_head_logits, greedy_token, greedy_token_fast, match_root_child
+from .verify import (lm_head_logits, greedy_token, greedy_token_fast, match_root_child, softmax_probs, top_p_set,
+                     relaxed_choice, top_p_choice)
 
 __all__ = [
     "SpecTree", "StageOracle", "RequestState", "rmsnorm", "rope_rotate", "silu",
     "tree_attention", "decoder_layer", "accept_masks", "drop_masks", "compact_rows",
     "PruneResult", "lm_head_logits", "greedy_token", "greedy_token_fast", "match_root_child",
+    "softmax_probs", "top_p_set", "relaxed_choice", "top_p_choice",
 ]

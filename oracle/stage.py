@@ -236,6 +236,25 @@ class StageOracle:
         par, _, tok, _, _ = st.tree.view()
         return match_root_child(par, tok, int(st.pred[0]))
 
+    def verify_lossy(self, req: int, h_root: np.ndarray, gain: np.ndarray, w_vocab: np.ndarray, mode: str,
+                     top_p: float = 1.0):
+        """Lossy verification of the root's children from the root's last-layer output h_root [d]
+        (Sec. 3.3.3): mode "relaxed" or "top_p".  Returns (node or -1, top-1 token, logits) and
+        records the top-1 token as the root's prediction."""
+        from .verify import lm_head_logits, greedy_token_fast, relaxed_choice, top_p_choice
+        st = self.req[req]
+        logits = lm_head_logits(np.asarray(h_root)[None, :], gain, w_vocab, self.shape.rms_eps)[0]
+        top1 = int(greedy_token_fast(logits[None, :])[0])
+        par, _, tok, prob, _ = st.tree.view()
+        if mode == "relaxed":
+            node = relaxed_choice(logits, par, tok)
+        elif mode == "top_p":
+            node = top_p_choice(logits, par, tok, prob, top_p)
+        else:
+            raise ValueError(mode)
+        st.pred[0] = top1
+        return node, top1, logits
+
     @staticmethod
     def prune_hidden_rows(rows: np.ndarray, row_nodes: Sequence[int], pr: PruneResult) -> np.ndarray:
         """E_i pruned by the table mask: a row stays iff its node (library numbering) stays."""

@@ -14,6 +14,20 @@ Pins (tests/test_oracle_verify.py): the head against Hugging Face's LlamaRMSNorm
 torch Linear in float64; argmax ties by hand-made rows; and the lossless property: a
 tree-speculative run with distractor tokens and misses emits exactly the token sequence
 of plain one-token-at-a-time greedy decoding.
+
+Lossy verification (Sec. 3.3.3, "Lossless and Lossy Acceleration", options (1) and (2)):
+  relaxed: among the candidate tokens (the root's children) take the one the large model
+           gives the highest probability -- every step verifies some child, no stall;
+  top-p:   a child is acceptable if its token lies in the large model's top-p set (tokens in
+           descending probability, the shortest prefix whose probabilities sum to >= p);
+           among the acceptable children the one with the highest draft probability wins.
+Readings where the paper is silent: equal probabilities are ordered by ascending token id,
+equal candidates by ascending node index; a step with no acceptable child is a miss exactly
+as in the lossless case (the model's top-1 token becomes the next level).
+Pins (tests/test_oracle_lossy.py): the top-p set against an exhaustive search over all subsets
+of a tiny vocabulary and against Hugging Face's TopPLogitsWarper; p -> 0 reduces top-p
+verification to the lossless match, p = 1 to "highest draft probability"; relaxed verification
+equals the lossless match whenever the top-1 token is among the candidates and never misses.
 """
 from __future__ import annotations
 
@@ -56,3 +70,53 @@ def match_root_child(parent: Sequence[int], token: Sequence[int], root_pred: int
         if p == -1 and int(t) == int(root_pred):
             return k
     return -1
+
+
+def softmax_probs(logits: np.ndarray) -> np.ndarray:
+    """Probabilities of one row of logits (float64, max subtracted)."""
+    z = np.asarray(logits, F64)
+    e = np.exp(z - np.max(z))
+    return e / np.sum(e)
+
+
+def top_p_set(probs: np.ndarray, p: float) -> list:
+    """Token ids of the top-p set, most probable first: tokens in descending probability (equal
+    probabilities by ascending id), cut after the first token at which the running sum reaches p."""
+    probs = np.asarray(probs, F64)
+    order = sorted(range(len(probs)), key=lambda v: (-probs[v], v))
+    out, run = [], 0.0
+    for v in order:
+        out.append(v)
+        run += probs[v]
+        if run >= p:
+            break
+    return out
+
+
+def relaxed_choice(logits: np.ndarray, parent: Sequence[int], token: Sequence[int]) -> int:
+    """Option (1): the root child whose token has the highest large-model probability (first one
+    among equals); -1 only if the root has no child.  Tokens outside the vocabulary never win."""
+    logits = np.asarray(logits, F64)
+    best, best_l = -1, -np.inf
+    for k, (par, t) in enumerate(zip(parent, token)):
+        if par != -1 or not (0 <= int(t) < len(logits)):
+            continue
+        if best == -1 or logits[int(t)] > best_l:
+            best, best_l = k, logits[int(t)]
+    return best
+
+
+def top_p_choice(logits: np.ndarray, parent: Sequence[int], token: Sequence[int], draft_prob: Sequence[float],
+                 p: float) -> int:
+    """Option (2): among the root children whose token is in the large model's top-p set, the one
+    with the highest draft probability (first one among equals); -1 if there is none."""
+    logits = np.asarray(logits, F64)
+    inside = set(top_p_set(softmax_probs(logits), p))
+    best, best_q = -1, -np.inf
+    for k, (par, t) in enumerate(zip(parent, token)):
+        if par != -1 or int(t) not in inside:
+            continue
+        q = float(np.float32(draft_prob[k]))
+        if best == -1 or q > best_q:
+            best, best_q = k, q
+    return best
