@@ -323,6 +323,29 @@ int sp_request_set_root_pred(sp_stage* stage, int32_t req, int32_t token, sp_str
 int sp_tree_match(sp_stage* stage, int32_t n, const int32_t* req_ids /*host*/, int32_t* nodes_dev /*device*/,
                   int32_t* nodes_host /*host, nullable*/, sp_stream stream);
 
+/* Lossy verification (Sec. 3.3.3, "Lossless and Lossy Acceleration").  x_root [n][d_model]
+ * (device, the stage's dtype) holds, for each listed request, the last decoder layer's output of
+ * the node that is now the root (the caller keeps that row of sp_stage_forward's x_out from the
+ * call that forwarded the node).  The large model's distribution after the root is
+ * softmax(RMSNorm(x_root) W_vocab^T); candidates are the root's children.
+ *   SP_VERIFY_RELAXED: the child whose token has the highest probability (the first such child);
+ *                      -1 only if the root has no child with a token inside the vocabulary.
+ *   SP_VERIFY_TOP_P:   children whose token is in the top-p set (tokens in descending probability,
+ *                      equal ones by ascending id, up to and including the one at which the running
+ *                      sum reaches top_p, 0 < top_p <= 1) are acceptable; of those the child with the
+ *                      highest draft probability (the first such child), -1 if none is acceptable.
+ * result_dev (device, 2n ints): [2i] = the verified node of req_ids[i] or -1, [2i+1] = the model's
+ * top-1 token, which is also stored as the root's prediction (so a miss continues as in the
+ * lossless flow: SP_CLEAR, then an insert of that token).  If result_host != NULL the 2n ints are
+ * also copied there asynchronously on `stream`.  The probabilities are formed in float32; a child
+ * whose cumulative mass lies within rounding of top_p may fall on either side.
+ * Errors: SP_E_INVALID (mode, top_p, repeated request), SP_E_BAD_REQ, SP_E_PENDING,
+ * SP_E_CAPACITY (n rows of vocab logits plus scratch exceed the workspace). */
+typedef enum sp_verify_mode { SP_VERIFY_RELAXED = 1, SP_VERIFY_TOP_P = 2 } sp_verify_mode;
+int sp_stage_verify_lossy(sp_stage* stage, const sp_head_weights* head, int32_t n, const int32_t* req_ids /*host*/,
+                          const void* x_root /*device*/, int32_t mode, float top_p, int32_t* result_dev /*device*/,
+                          int32_t* result_host /*host, nullable*/, sp_stream stream);
+
 /* ---- inspection ------------------------------------------------------------- */
 
 /* Copies a request's device tables to the host.  Waits for `stream`. */

@@ -19,6 +19,7 @@ SP_MAX_TREE_NODES = 256
 SP_MAX_BATCH_REQ = 64
 SP_F32, SP_BF16 = 0, 1
 SP_ACCEPT, SP_DROP, SP_CLEAR = 0, 1, 2
+SP_VERIFY_RELAXED, SP_VERIFY_TOP_P = 1, 2
 SP_FLAG_SIMPLE_KERNELS = 1
 SP_FLAG_PACKED_WEIGHTS = 2
 SP_FLAG_PAGED_KV = 4
@@ -97,6 +98,8 @@ def load_library(path: Optional[str] = None) -> C.CDLL:
         "sp_pack_matrix": [vp, vp, C.c_int32, C.c_int32, vp],
         "sp_request_init": [vp, C.c_int32, C.c_int64, C.c_int32, C.c_int32, vp],
         "sp_stage_verify_head": [vp, C.POINTER(sp_head_weights), C.c_int32, i32p, i32p, i32p, vp, vp, vp, vp],
+        "sp_stage_verify_lossy": [vp, C.POINTER(sp_head_weights), C.c_int32, i32p, vp, C.c_int32, C.c_float, vp,
+                                  i32p, vp],
         "sp_request_set_root_pred": [vp, C.c_int32, C.c_int32, vp],
         "sp_tree_match": [vp, C.c_int32, i32p, vp, i32p, vp],
         "sp_tree_expand": [vp, C.c_int32, C.c_int32, i32p, C.c_int32, vp, vp, C.c_int32, vp, vp, vp, vp, vp],
@@ -365,6 +368,24 @@ class Stage:
 
     def set_root_pred(self, req: int, token: int):
         _check(self.lib.sp_request_set_root_pred(self.handle, req, token, self._stream()), "sp_request_set_root_pred")
+
+    def verify_lossy(self, head: Dict[str, "object"], req_ids: Sequence[int], x_root, mode: int,
+                     top_p: float = 1.0) -> List[tuple]:
+        """x_root: device tensor [len(req_ids), d_model], the roots' last-layer outputs.  Returns
+        [(verified node or -1, top-1 token)] per request; waits for the stream."""
+        import torch
+        ra, rp = _i32(req_ids)
+        n = len(ra)
+        assert x_root.is_contiguous() and x_root.dtype == self.tdtype
+        dev = torch.empty(max(2 * n, 2), dtype=torch.int32, device=self.device)
+        host = torch.empty(max(2 * n, 2), dtype=torch.int32, pin_memory=True)
+        h = sp_head_weights(head["norm"].data_ptr(), head["wvocab"].data_ptr(), int(head["wvocab"].shape[0]), 0)
+        _check(self.lib.sp_stage_verify_lossy(self.handle, C.byref(h), n, rp, x_root.data_ptr(), int(mode),
+                                              float(top_p), dev.data_ptr(),
+                                              C.cast(host.data_ptr(), C.POINTER(C.c_int32)), self._stream()),
+               "sp_stage_verify_lossy")
+        torch.cuda.current_stream(self.device).synchronize()
+        return [(int(host[2 * i]), int(host[2 * i + 1])) for i in range(n)]
 
     def tree_match(self, req_ids: Sequence[int]) -> List[int]:
         """Verified root child per request (-1 = miss); waits for the stream."""

@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libspecpipe.so")
-SOURCES = ["sp_api.hip", "sp_tree.hip", "sp_rows.hip", "sp_simple.hip", "sp_gemm.hip", "sp_gemm_wide.hip", "sp_attn.hip"]
+SOURCES = ["sp_api.hip", "sp_tree.hip", "sp_rows.hip", "sp_simple.hip", "sp_gemm.hip", "sp_gemm_wide.hip", "sp_attn.hip", "sp_verify.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]

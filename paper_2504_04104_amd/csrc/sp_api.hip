@@ -926,6 +926,46 @@ int sp_stage_verify_head(sp_stage* s, const sp_head_weights* head, int32_t n_req
   return e == hipSuccess ? SP_OK : hip_fail(s, e);
 }
 
+int sp_stage_verify_lossy(sp_stage* s, const sp_head_weights* head, int32_t n, const int32_t* req_ids,
+                          const void* x_root, int32_t mode, float top_p, int32_t* result_dev, int32_t* result_host,
+                          sp_stream stream) {
+  if (!s || !head || !req_ids || !result_dev) return SP_E_INVALID;
+  if (!head->norm || !head->wvocab || head->vocab < 1) return SP_E_INVALID;
+  if (mode != SP_VERIFY_RELAXED && mode != SP_VERIFY_TOP_P) return SP_E_INVALID;
+  if (mode == SP_VERIFY_TOP_P && !(top_p > 0.f && top_p <= 1.f)) return SP_E_INVALID;   // also rejects NaN
+  const sp_config& c = s->cfg;
+  if (n < 0 || n > SP_MAX_BATCH_REQ || n > c.max_batch_nodes) return SP_E_CAPACITY;
+  for (int i = 0; i < n; ++i) {
+    HostReq* r = get_req(s, req_ids[i]);
+    if (!r) return SP_E_BAD_REQ;
+    if (r->pending) return SP_E_PENDING;
+    for (int j = 0; j < i; ++j) if (req_ids[j] == req_ids[i]) return SP_E_INVALID;
+  }
+  if (n == 0) return SP_OK;
+  if (!x_root) return SP_E_INVALID;
+  const int d = c.d_model, V = head->vocab;
+  Workspace& w = s->ws;
+  const size_t logit_floats = (size_t)n * V;
+  if (logit_floats + sp_lossy_scratch_floats(n, V) > w.part_floats) return SP_E_CAPACITY;
+  hipStream_t st = (hipStream_t)stream;
+  hipError_t e = sp_launch_row_norm(c.dtype, x_root, head->norm, w.xn, n, d, c.rms_eps, st);
+  if (e != hipSuccess) return hip_fail(s, e);
+  ProfScope p(s, SP_K_VERIFY_HEAD, st);
+  if (s->fast && V % 64 == 0 && d % 128 == 0) {
+    int S = 1;
+    e = sp_launch_gemm_bf16((const bf16_t*)w.xn, (const bf16_t*)head->wvocab, s->packed, w.part, n, V, d, 1,
+                            logit_floats, &S, st);
+  } else {
+    e = sp_launch_gemm_simple(c.dtype, w.xn, head->wvocab, w.part, n, V, d, st);
+  }
+  if (e == hipSuccess)
+    e = sp_launch_verify_lossy(s->d_meta, s->d_tables, w.part, n, req_ids, V, mode, top_p, w.part + logit_floats,
+                               result_dev, st);
+  if (e == hipSuccess && result_host)
+    e = hipMemcpyAsync(result_host, result_dev, sizeof(int32_t) * 2 * n, hipMemcpyDeviceToHost, st);
+  return e == hipSuccess ? SP_OK : hip_fail(s, e);
+}
+
 int sp_tree_expand(sp_stage* s, int32_t req, int32_t n_bottom, const int32_t* bottom_nodes, int32_t k,
                    const int32_t* cand_tokens, const float* cand_probs, int32_t w, int32_t* out_parents,
                    int32_t* out_tokens, float* out_probs, int32_t* out_count, sp_stream stream) {

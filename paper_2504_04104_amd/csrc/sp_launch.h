@@ -40,6 +40,16 @@ hipError_t sp_launch_tree_expand(const ReqTables* tables, const ExpandArgs& a, c
                                  const float* cand_prob, int* out_parent, int* out_token, float* out_prob,
                                  int* out_count, hipStream_t st);
 hipError_t sp_launch_set_root_pred(ReqMeta* meta, int req, int token, hipStream_t st);
+
+// ---- lossy verification (sp_verify.hip) -------------------------------------------
+// xn = rmsnorm(x) * gain for M rows (no residual stream, no row descriptors)
+hipError_t sp_launch_row_norm(int dtype, const void* x, const void* gain, void* xn, int M, int d, float eps,
+                              hipStream_t st);
+// floats of scratch sp_launch_verify_lossy needs for n rows of V logits
+size_t sp_lossy_scratch_floats(int n, int V);
+// mode 1 relaxed, 2 top-p; logits [n][V]; out[2i] = verified node of reqs[i] or -1, out[2i+1] = top-1 token
+hipError_t sp_launch_verify_lossy(ReqMeta* meta, const ReqTables* tables, const float* logits, int n, const int* reqs,
+                                  int V, int mode, float top_p, float* scratch, int* out, hipStream_t st);
 hipError_t sp_launch_kv_compact(const ReqMeta* meta, const ReqTables* tables, const PruneBatch& b, KvGeom g,
                                 hipStream_t st);
 hipError_t sp_launch_rows_compact(void* rows, size_t row_stride_bytes, int row_bytes, const RowList& l,

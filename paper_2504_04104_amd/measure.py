@@ -347,10 +347,18 @@ def run_verify(args):
     ct = torch.randint(0, V, (64, 16), device=DEV, dtype=torch.int32)
     cp = torch.rand(64, 16, device=DEV, dtype=torch.float32)
     t_expand = timed(lambda: stage.tree_expand(0, list(range(64)), ct, cp, 64), 30)
+    # lossy verification of a full level of 64 root children from the root's row (one row of logits)
+    stage.request_init(0, 0, cap, P)
+    stage.tree_insert(0, [-1] * 64, [int(v) for v in torch.randint(0, V, (64,)).tolist()], [0.5] * 64)
+    xr = y[:1].contiguous()
+    t_relaxed = timed(lambda: stage.verify_lossy(head, [0], xr, sp.SP_VERIFY_RELAXED, 1.0), 30)
+    t_top_p = timed(lambda: stage.verify_lossy(head, [0], xr, sp.SP_VERIFY_TOP_P, 0.9), 30)
     hbytes = V * sh.d_model * 2
     res = {"run": "verify", "workload": "last stage of the 8B shape: 4 layers + output head, vocab 128256, 64 nodes",
            "ms_per_step": round(t * 1e3, 3), "tree_tokens_per_s": round(n / t, 1),
            "expand_call_us_with_host_copy": round(t_expand * 1e6, 1),
+           "lossy_relaxed_call_us_with_host_wait": round(t_relaxed * 1e6, 1),
+           "lossy_top_p_call_us_with_host_wait": round(t_top_p * 1e6, 1),
            "head_call_us": round(t_head * 1e6, 1), "head_kernels_us": round(hd_us / cnt, 1),
            "head_weights_MB": round(hbytes / 1e6, 1),
            "head_GBps": round(hbytes / (hd_us / cnt * 1e-6) / 1e9, 1),

@@ -31,7 +31,7 @@ class Pair:
 
     def __init__(self, shape: wl.ModelShape, seed: int, prefixes: Dict[int, int], *, tree_room: int = 256 + 64,
                  flags: int = 0, max_batch_nodes: int = 64, oracle: bool = True, vocab: int = 0,
-                 oracle_reqs: Optional[Sequence[int]] = None, page_slots: int = 0):
+                 oracle_reqs: Optional[Sequence[int]] = None, page_slots: int = 0, head_gain: float = 1.0):
         self.shape, self.seed = shape, seed
         self.vocab = vocab
         # the float64 oracle may follow a sample of the requests only (large batches)
@@ -69,6 +69,8 @@ class Pair:
         if vocab:
             # output head of the last stage, same numbers on both sides
             self.head_np = wl.head_weights(shape, seed, vocab)
+            # a power of two keeps the gains exact in bf16; larger gains make the distribution peakier
+            self.head_np["norm"] = self.head_np["norm"] * np.asarray(head_gain, self.head_np["norm"].dtype)
             td = torch.bfloat16 if shape.dtype == "bf16" else torch.float32
             wv = torch.from_numpy(self.head_np["wvocab"]).to("cuda:0", td).contiguous()
             if flags & sp.SP_FLAG_PACKED_WEIGHTS:
@@ -153,6 +155,71 @@ class Pair:
                     self.ora.req[r].pred[f + 1 + i] = g
             row += n
         return pred, differ
+
+    def verify_lossy(self, reqs: Sequence[int], x_root: torch.Tensor, mode: str, top_p: float, tol: float):
+        """Relaxed / top-p verification of the roots' children on both sides, the oracle fed with the
+        GPU's own root rows.  The GPU forms logits in bf16/fp32 arithmetic and probabilities in
+        float32, the oracle everything in float64, so the comparison leaves a margin around each
+        decision: `tol` (relative to the largest |logit|) on logits, and the probability mass that
+        such a logit error can move around top_p.  Outside the margins the decisions must be
+        equal.  Returns the GPU's [(node, top1)] and how many requests had a decision inside a margin."""
+        from oracle.verify import softmax_probs
+        got = self.gpu.verify_lossy(self.head, reqs, x_root, sp.SP_VERIFY_RELAXED if mode == "relaxed" else sp.SP_VERIFY_TOP_P,
+                                    top_p)
+        rows = to_np(x_root).astype(np.float64)
+        marginal = 0
+        for i, r in enumerate(reqs):
+            node, top1 = got[i]
+            want, want_top1, logits = self.ora.verify_lossy(r, rows[i], self.head_np["norm"], self.head_np["wvocab"],
+                                                             mode, top_p)
+            scale = np.max(np.abs(logits))
+            eps = tol * scale
+            assert 0 <= top1 < self.vocab and logits[top1] >= logits.max() - eps, ("top-1 far from the maximum", r)
+            assert not (logits[top1] == logits.max() and top1 > want_top1)
+            self.ora.req[r].pred[0] = top1                       # the oracle follows the GPU's decision
+            par, _, tok, prob, _ = self.ora.req[r].tree.view()
+            cand = [k for k in range(len(par)) if par[k] == -1 and 0 <= tok[k] < self.vocab]
+            if mode == "relaxed":
+                if not cand:
+                    assert node == -1 == want
+                    continue
+                assert node in cand, (r, node)
+                best = max(logits[tok[k]] for k in cand)
+                assert logits[tok[node]] >= best - eps, ("candidate far from the best", r, node, want)
+                close = [k for k in cand if logits[tok[k]] >= best - 2 * eps]
+                if len(close) == 1:
+                    assert node == want, (r, node, want)
+                else:
+                    marginal += 1
+                    assert not (logits[tok[node]] == best and node > want)
+                continue
+            # The mass in front of a candidate's token, bracketed.  A logit error of eps moves a probability by
+            # a factor within exp(+-2 eps) (numerator and normaliser); as the masses in front of and behind the
+            # token add up to one, the smaller of the two bounds the shift.  Tokens whose logit is within 2 eps
+            # of the candidate's may also be counted on either side.
+            probs = softmax_probs(logits)
+            rank = sorted(range(self.vocab), key=lambda v: (-probs[v], v))
+            before = np.zeros(self.vocab)
+            before[rank] = np.concatenate(([0.0], np.cumsum(probs[rank])[:-1]))
+            sure_in, maybe = [], []
+            for k in cand:
+                t = tok[k]
+                near = float(np.sum(probs[np.abs(logits - logits[t]) <= 2 * eps])) - float(probs[t])
+                slack = 4 * eps * min(before[t], 1.0 - before[t]) + near + 1e-6
+                if before[t] + slack < top_p:
+                    sure_in.append(k)
+                elif before[t] - slack < top_p:
+                    maybe.append(k)
+            if not maybe:
+                assert node == want, (r, node, want)
+                continue
+            marginal += 1
+            if node == -1:
+                assert not sure_in, (r, want)
+            else:
+                assert node in sure_in or node in maybe, (r, node)
+                assert all(np.float32(prob[node]) >= np.float32(prob[k]) for k in sure_in), (r, node, want)
+        return got, marginal
 
     def tree_region(self, req: int, P: int, n: int) -> torch.Tensor:
         """Raw slab rows of tree slots [P, P+n): [layer, K|V, head, n, d_head] (a copy)."""

@@ -535,6 +535,66 @@ def test_verified_decoding_loop(shape, flags, tol):
     pair.close()
 
 
+# error of a single logit relative to the largest |logit|: fp32 accumulation order; bf16 rounding of the
+# normalised row (2^-9 per element, adding up like a random walk over d_model terms)
+TOL_LOGIT = {"f32": 1e-5, "bf16": 2e-3}
+
+
+@pytest.mark.parametrize("shape,flags,tol,V", [(MINI_F32, 0, "f32", 97), (MINI_BF16, 0, "bf16", 1088),
+                                               (MINI_BF16, sp.SP_FLAG_PACKED_WEIGHTS, "bf16", 4160),
+                                               (MINI_BF16, sp.SP_FLAG_SIMPLE_KERNELS, "bf16", 2113)],
+                         ids=["f32_v97", "bf16_v1088", "bf16_packed_v4160", "bf16_simple_v2113"])
+def test_lossy_verification(shape, flags, tol, V):
+    """Relaxed and top-p verification (Sec. 3.3.3) of the roots' children for three requests at once:
+    vocabularies of one slice, of several slices with a short last one, and of odd size; children with
+    duplicate tokens, a token outside the vocabulary, deeper nodes that must not count, a request
+    whose root has no child."""
+    pair = Pair(shape, 31, {0: 20, 1: 33, 2: 9}, vocab=V, head_gain=8.0)
+    rs = np.random.RandomState(31)
+    x_np = wl.hidden_rows(shape, 31, ("root",), 3)
+    x_root = to_dev(x_np, pair.gpu)
+    # the model's distribution after each root, to plant candidates at chosen places of the cumulative mass
+    from oracle.verify import lm_head_logits, softmax_probs
+    logits = lm_head_logits(x_np.astype(np.float64), pair.head_np["norm"], pair.head_np["wvocab"], shape.rms_eps)
+    order = np.argsort(-logits, axis=1, kind="stable")
+    for r, n_root in ((0, 9), (1, 14)):
+        before = np.concatenate(([0.0], np.cumsum(softmax_probs(logits[r])[order[r]])[:-1]))   # by rank
+        likely = [int(t) for t in order[r, 1:4]] + [int(order[r, 2])]             # near the top, one of them twice
+        middle = [int(order[r, int(np.argmin(np.abs(before - m)))]) for m in (0.75, 0.85)]
+        tail = [int(t) for t in order[r, V - (n_root - 7):]]                       # the least likely tokens
+        tokens = likely + middle + tail + [V + 5]                                 # and one outside the vocabulary
+        assert len(tokens) == n_root
+        rs.shuffle(tokens)
+        parents = [-1] * n_root
+        deeper = [int(order[r, 0])] * 3                                           # the top-1 token, but not under the root
+        pair.insert(r, parents + [0, 1, n_root], tokens + deeper,
+                    probs=[float(q) for q in rs.uniform(0.05, 0.95, n_root + 3).astype(np.float32)])
+    results = {}
+    n_marginal = 0
+    for mode, p in (("relaxed", 1.0), ("top_p", 0.55), ("top_p", 0.93), ("top_p", 0.999), ("top_p", 1e-6)):
+        got, marginal = pair.verify_lossy([0, 1, 2], x_root, mode, p, TOL_LOGIT[tol])
+        n_marginal += marginal
+        say("lossy", mode, p, got, "marginal", marginal)
+        results[(mode, p)] = got
+        assert got[2][0] == -1                                                    # no children
+        for r in (0, 1, 2):
+            assert pair.gpu.tree_read(r)["root_pred"] == got[r][1] == int(order[r, 0])
+    assert n_marginal <= 2                                                       # of 15 decisions; the others are compared exactly
+    assert all(results[("relaxed", 1.0)][r][0] >= 0 for r in (0, 1))             # relaxed never misses
+    assert all(results[("top_p", 1e-6)][r][0] == -1 for r in (0, 1))             # only the top-1 token passes
+    assert any(results[("top_p", 0.999)][r][0] != results[("relaxed", 1.0)][r][0] for r in (0, 1))
+    # a single request out of the three, in another order of arguments
+    one, _ = pair.verify_lossy([1], x_root[1:2].contiguous(), "top_p", 0.93, TOL_LOGIT[tol])
+    assert one[0] == results[("top_p", 0.93)][1]
+    with pytest.raises(sp.SpError):
+        pair.gpu.verify_lossy(pair.head, [0], x_root[:1].contiguous(), sp.SP_VERIFY_TOP_P, 0.0)
+    with pytest.raises(sp.SpError):
+        pair.gpu.verify_lossy(pair.head, [0, 0], x_root[:2].contiguous(), sp.SP_VERIFY_RELAXED, 1.0)
+    with pytest.raises(sp.SpError):
+        pair.gpu.verify_lossy(pair.head, [0], x_root[:1].contiguous(), 3, 0.5)
+    pair.close()
+
+
 # ---------------------------------------------------------------------------------------
 # fixed-width expansion
 def test_fixed_width_expansion_matches_oracle():
