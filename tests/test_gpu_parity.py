@@ -592,6 +592,16 @@ def test_lossy_verification(shape, flags, tol, V):
         pair.gpu.verify_lossy(pair.head, [0, 0], x_root[:2].contiguous(), sp.SP_VERIFY_RELAXED, 1.0)
     with pytest.raises(sp.SpError):
         pair.gpu.verify_lossy(pair.head, [0], x_root[:1].contiguous(), 3, 0.5)
+    with pytest.raises(sp.SpError) as ei:
+        pair.gpu.verify_lossy(pair.head, [7], x_root[:1].contiguous(), sp.SP_VERIFY_RELAXED, 1.0)
+    assert ei.value.status == -4                                                 # SP_E_BAD_REQ
+    assert pair.gpu.verify_lossy(pair.head, [], x_root[:1].contiguous(), sp.SP_VERIFY_RELAXED, 1.0) == []
+    # while a compaction is pending the tables are between two states: refused
+    pair.gpu.tree_prune(0, sp.SP_DROP, 0)
+    with pytest.raises(sp.SpError) as ei:
+        pair.gpu.verify_lossy(pair.head, [0], x_root[:1].contiguous(), sp.SP_VERIFY_RELAXED, 1.0)
+    assert ei.value.status == -7                                                 # SP_E_PENDING
+    pair.gpu.kv_compact(0)
     pair.close()
 
 
