@@ -28,7 +28,10 @@
 #define SP_GEMM_NCG_GATEUP 2
 #endif
 #ifndef SP_GEMM_TARGET_WGS
-#define SP_GEMM_TARGET_WGS 768    // split K until the grid has about this many workgroups
+#define SP_GEMM_TARGET_WGS 768    // one row tile: split K until the grid has about this many workgroups
+#endif
+#ifndef SP_GEMM_TARGET_WGS_ROWS
+#define SP_GEMM_TARGET_WGS_ROWS 512   // more row tiles: at most this many (two per CU)
 #endif
 
 // PACKED: the weights were re-laid at load time (sp_pack_weights) into MFMA fragment order --
@@ -239,8 +242,14 @@ hipError_t sp_launch_gemm_bf16(const bf16_t* X, const bf16_t* W, bool packed, fl
   row_blocks(M, &MT, &mblocks);
   const int chunks = K / (MT == 8 ? 128 : SP_GEMM_KC_PLAIN);
   const int tiles = N / TILE;
-  // enough workgroups to keep every CU streaming, within the partial-sum buffer
-  int S = (SP_GEMM_TARGET_WGS + tiles * mblocks - 1) / (tiles * mblocks);
+  // Enough workgroups to keep every CU streaming, within the partial-sum buffer.
+  // With one row tile the partial sums are small and three workgroups per CU stream best.  With more
+  // rows every slice costs M*N*4 bytes written here and read again by the kernel that folds them, which
+  // outweighs the finer split: at most two workgroups per CU (measured on the whole 64-row step:
+  // 0.608 ms against 0.617 ms; a count between two and three per CU, which leaves the CUs unevenly
+  // loaded, 0.638 ms; two waves per column group with half the slices again: 0.612 ms).
+  int S = MT == 1 ? (SP_GEMM_TARGET_WGS + tiles * mblocks - 1) / (tiles * mblocks)
+                  : SP_GEMM_TARGET_WGS_ROWS / (tiles * mblocks);
   if (S > max_split) S = max_split;
   if (S > chunks) S = chunks;
   while (S > 1 && (size_t)S * M * N > part_capacity_floats) --S;
