@@ -70,6 +70,9 @@ def main() -> int:
     n = args.nodes or w.n_nodes
     P = w.prefix_len
     dev = "cuda:0"
+    # A stream of the caller's own, as a serving loop would use: sp_stage_forward can only capture and
+    # replay the graph of its launches on a stream that may be captured, which the default stream is not.
+    torch.cuda.set_stream(torch.cuda.Stream(device=dev))
     t0 = time.time()
     with ThreadPoolExecutor(4) as ex:
         weights = list(ex.map(lambda l: wl.layer_weights(sh, w.seed, l), range(sh.n_layers)))

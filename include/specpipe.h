@@ -234,8 +234,9 @@ int sp_tree_insert_batch(sp_stage* stage, int32_t n_req, const int32_t* req_ids 
  * Launch overhead: when a call has the same shape (rows, attention work items) as an
  * earlier one, its launches except the first and the last are replayed from a HIP graph
  * captured the second time that shape was seen; results are identical.  The call stays
- * eager while the stream is being captured by the caller, while sp_profile_begin brackets
- * fall into it, or with SP_FLAG_NO_GRAPHS. */
+ * eager on a stream that cannot be captured (the default stream: pass a stream of your
+ * own), while the stream is being captured by the caller, while sp_profile_begin
+ * brackets fall into it, or with SP_FLAG_NO_GRAPHS. */
 int sp_stage_forward(sp_stage* stage, int32_t n_req, const int32_t* req_ids /*host*/,
                      const int32_t* first_node /*host*/, const int32_t* n_nodes /*host*/,
                      const void* x_in /*device*/, void* x_out /*device*/, sp_stream stream);

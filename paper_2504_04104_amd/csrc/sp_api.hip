@@ -767,7 +767,9 @@ int sp_tree_prune(sp_stage* s, int32_t req, int32_t mode, int32_t node, int32_t*
   return sp_tree_prune_batch(s, 1, &req, &mode, &node, n_live_out, n_commit_out, stream);
 }
 
-int sp_kv_compact_batch(sp_stage* s, int32_t n, const int32_t* req_ids, sp_stream stream) {
+// rows / list (nullable, one request only): hidden rows compacted by the same launch as the cache
+static int compact_batch(sp_stage* s, int32_t n, const int32_t* req_ids, void* rows, const RowList* list,
+                         sp_stream stream) {
   if (!s || !req_ids) return SP_E_INVALID;
   if (n < 0 || n > SP_MAX_BATCH_REQ) return SP_E_CAPACITY;
   PruneBatch b;
@@ -782,7 +784,8 @@ int sp_kv_compact_batch(sp_stage* s, int32_t n, const int32_t* req_ids, sp_strea
   if (n == 0) return SP_OK;
   {
     ProfScope scope(s, SP_K_KV_COMPACT, (hipStream_t)stream);
-    hipError_t e = sp_launch_kv_compact(s->d_meta, s->d_tables, b, s->geom, (hipStream_t)stream);
+    const size_t rb = (size_t)s->cfg.d_model * elt_bytes(s->cfg.dtype);
+    hipError_t e = sp_launch_kv_compact(s->d_meta, s->d_tables, b, s->geom, rows, rb, (int)rb, list, (hipStream_t)stream);
     if (e != hipSuccess) return hip_fail(s, e);
   }
   for (int i = 0; i < n; ++i) {
@@ -792,6 +795,10 @@ int sp_kv_compact_batch(sp_stage* s, int32_t n, const int32_t* req_ids, sp_strea
     if (is_paged(s->cfg)) (void)pages_resize(s, req_ids[i], r.P + r.T, (hipStream_t)stream);
   }
   return SP_OK;
+}
+
+int sp_kv_compact_batch(sp_stage* s, int32_t n, const int32_t* req_ids, sp_stream stream) {
+  return compact_batch(s, n, req_ids, nullptr, nullptr, stream);
 }
 
 int sp_kv_compact(sp_stage* s, int32_t req, void* x_rows, int32_t n_rows, const int32_t* row_nodes,
@@ -823,14 +830,10 @@ int sp_kv_compact(sp_stage* s, int32_t req, void* x_rows, int32_t n_rows, const 
     }
     if (!moved) list.first_moved = list.n_keep;
   }
-  int rc = sp_kv_compact_batch(s, 1, &req, stream);
+  const bool move_rows = x_rows && list.first_moved < list.n_keep;
+  int rc = compact_batch(s, 1, &req, move_rows ? x_rows : nullptr, move_rows ? &list : nullptr, stream);
   if (rc != SP_OK) return rc;
   if (x_rows) {
-    if (list.first_moved < list.n_keep) {
-      const size_t rb = (size_t)s->cfg.d_model * elt_bytes(s->cfg.dtype);
-      hipError_t e = sp_launch_rows_compact(x_rows, rb, (int)rb, list, (hipStream_t)stream);
-      if (e != hipSuccess) return hip_fail(s, e);
-    }
     if (n_rows_out) *n_rows_out = list.n_keep;
   } else if (n_rows_out) {
     *n_rows_out = 0;

@@ -51,9 +51,8 @@ size_t sp_lossy_scratch_floats(int n, int V);
 hipError_t sp_launch_verify_lossy(ReqMeta* meta, const ReqTables* tables, const float* logits, int n, const int* reqs,
                                   int V, int mode, float top_p, float* scratch, int* out, hipStream_t st);
 hipError_t sp_launch_kv_compact(const ReqMeta* meta, const ReqTables* tables, const PruneBatch& b, KvGeom g,
-                                hipStream_t st);
-hipError_t sp_launch_rows_compact(void* rows, size_t row_stride_bytes, int row_bytes, const RowList& l,
-                                  hipStream_t st);
+                                void* rows /*nullable: hidden rows of the one request, same launch*/,
+                                size_t row_stride_bytes, int row_bytes, const RowList* l, hipStream_t st);
 
 // A forward call's requests (segments) and the split of its attention work, made on the host.
 struct AttnPlan {          // host-made split of a forward call's attention work

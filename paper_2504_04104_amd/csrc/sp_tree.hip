@@ -234,14 +234,35 @@ __device__ __forceinline__ void gather_inplace(char* stream, size_t row_stride, 
   }
 }
 
-// grid = (layers * 2 * kv_heads, batch items): one workgroup per (plane, request).
+// Column slices of in-flight hidden rows that ride along with a cache compaction (one request):
+// workgroups past the cache planes take one slice each.
+struct RowsJob {
+  char* rows;              // nullptr: none
+  size_t row_stride;
+  int n_slices, slice_bytes, last_slice_bytes;
+};
+
+__device__ __forceinline__ void rows_compact_slice(const RowsJob& j, const RowList& l, int slice, short* s_src) {
+  for (int i = threadIdx.x; i < l.n_keep; i += blockDim.x) s_src[i] = l.src[i];
+  __syncthreads();
+  gather_inplace<16>(j.rows + (size_t)slice * j.slice_bytes, j.row_stride,
+                     slice == j.n_slices - 1 ? j.last_slice_bytes : j.slice_bytes, l.first_moved, l.n_keep, s_src);
+}
+
+// grid = (layers * 2 * kv_heads [+ row slices], batch items): one workgroup per (plane, request).
+template <bool WITH_ROWS>
 __global__ void __launch_bounds__(256) k_kv_compact(const ReqMeta* meta, const ReqTables* tables, PruneBatch b,
-                                                     KvGeom g) {
+                                                     KvGeom g, RowsJob rj, RowList rl) {
+  __shared__ short s_src[SP_T];
+  const int planes = g.n_layers * 2 * g.n_kv_heads;
+  if (WITH_ROWS && (int)blockIdx.x >= planes) {
+    rows_compact_slice(rj, rl, blockIdx.x - planes, s_src);
+    return;
+  }
   const int item = blockIdx.y;
   if (b.mode[item] < 0) return;
   const int req = b.req[item];
   const ReqTables& t = tables[req];
-  __shared__ short s_src[SP_T];
   __shared__ int s_phys[SP_T];
   const int n_keep = t.pend_n_kv_keep, first = t.pend_first_moved;
   for (int i = threadIdx.x; i < n_keep; i += blockDim.x) s_src[i] = t.kv_src[i];
@@ -256,15 +277,6 @@ __global__ void __launch_bounds__(256) k_kv_compact(const ReqMeta* meta, const R
     char* stream = g.kv + plane * g.plane_bytes + (size_t)(meta[req].base + t.pend_P_old) * g.row_bytes;
     gather_inplace<16>(stream, (size_t)g.row_bytes, g.row_bytes, first, n_keep, s_src);
   }
-}
-
-// grid = row_bytes / slice: one workgroup per 256-byte column slice of the rows.
-__global__ void __launch_bounds__(256) k_rows_compact(char* rows, size_t row_stride, int slice_bytes, RowList l) {
-  __shared__ short s_src[SP_T];
-  for (int i = threadIdx.x; i < l.n_keep; i += blockDim.x) s_src[i] = l.src[i];
-  __syncthreads();
-  gather_inplace<16>(rows + (size_t)blockIdx.x * slice_bytes, row_stride, slice_bytes, l.first_moved, l.n_keep,
-                     s_src);
 }
 
 // ---- launchers -------------------------------------------------------------------
@@ -455,26 +467,29 @@ hipError_t sp_launch_tree_prune(ReqMeta* meta, ReqTables* tables, const PruneBat
   hipLaunchKernelGGL(k_tree_prune, dim3(b.n), dim3(SP_T), 0, st, meta, tables, b);
   return hipGetLastError();
 }
-hipError_t sp_launch_kv_compact(const ReqMeta* meta, const ReqTables* tables, const PruneBatch& b, KvGeom g,
-                                hipStream_t st) {
-  hipLaunchKernelGGL(k_kv_compact, dim3(g.n_layers * 2 * g.n_kv_heads, b.n), dim3(256), 0, st, meta, tables, b, g);
-  return hipGetLastError();
+static RowsJob rows_job(void* rows, size_t row_stride_bytes, int row_bytes) {
+  // slices of 256 bytes and a last narrower one (a multiple of 16 by construction: d_model % 8 == 0)
+  RowsJob j;
+  j.rows = (char*)rows;
+  j.row_stride = row_stride_bytes;
+  j.slice_bytes = 256;
+  j.n_slices = (row_bytes + 255) / 256;
+  j.last_slice_bytes = row_bytes - (j.n_slices - 1) * 256;
+  return j;
 }
-hipError_t sp_launch_rows_compact(void* rows, size_t row_stride_bytes, int row_bytes, const RowList& l,
-                                  hipStream_t st) {
-  // slices of 256 bytes; a last narrower slice is handled by a second launch
-  const int slice = 256;
-  const int full = row_bytes / slice;
-  if (full > 0) {
-    hipLaunchKernelGGL(k_rows_compact, dim3(full), dim3(256), 0, st, (char*)rows, row_stride_bytes, slice, l);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
+// rows != nullptr (one request only): the hidden rows are compacted by the same launch
+hipError_t sp_launch_kv_compact(const ReqMeta* meta, const ReqTables* tables, const PruneBatch& b, KvGeom g,
+                                void* rows, size_t row_stride_bytes, int row_bytes, const RowList* l, hipStream_t st) {
+  const int planes = g.n_layers * 2 * g.n_kv_heads;
+  if (rows && l && b.n == 1) {
+    const RowsJob j = rows_job(rows, row_stride_bytes, row_bytes);
+    hipLaunchKernelGGL(k_kv_compact<true>, dim3(planes + j.n_slices, 1), dim3(256), 0, st, meta, tables, b, g, j, *l);
+  } else {
+    RowsJob j;
+    j.rows = nullptr; j.row_stride = 0; j.n_slices = 0; j.slice_bytes = 0; j.last_slice_bytes = 0;
+    RowList none;
+    none.n_keep = 0; none.first_moved = 0;
+    hipLaunchKernelGGL(k_kv_compact<false>, dim3(planes, b.n), dim3(256), 0, st, meta, tables, b, g, j, none);
   }
-  const int rest = row_bytes - full * slice;      // multiple of 16 by construction (d_model % 8 == 0)
-  if (rest > 0) {
-    hipLaunchKernelGGL(k_rows_compact, dim3(1), dim3(256), 0, st, (char*)rows + (size_t)full * slice,
-                       row_stride_bytes, rest, l);
-    return hipGetLastError();
-  }
-  return hipSuccess;
+  return hipGetLastError();
 }

@@ -373,6 +373,8 @@ def main():
     ap.add_argument("--run", required=True, choices=["sweep", "c3", "c4", "c5", "compact", "verify"])
     ap.add_argument("--steps", type=int, default=0)
     args = ap.parse_args()
+    # a stream of our own: the forward call replays HIP graphs of its launches only on a stream that can be captured
+    torch.cuda.set_stream(torch.cuda.Stream(device=DEV))
     {"sweep": run_sweep, "c3": run_c3, "c4": run_c4, "c5": run_c5, "compact": run_compact, "verify": run_verify}[args.run](args)
 
 
