@@ -162,7 +162,7 @@ def main() -> int:
     achieved = gu_bytes / (gu_us * 1e-6) / 1e9
     # HBM bytes per launch from rocprofv3 PMC runs of this same command (FETCH_SIZE x 2.00 + WRITE_SIZE x 1.00,
     # factors from a 1 GiB copy; profiles/pmc_hbm_traffic_stage_step_c2.txt).  Only valid for the profiled shape.
-    traffic = 243.05e6 if (args.workload == "C2" and n == 64) else None
+    traffic = 242.63e6 if (args.workload == "C2" and n == 64) else None
     roofline = {"bound": "hbm", "kernel": "gemm_gateup (k_gemm_bf16 GATEUP)", "achieved": round(achieved, 1),
                 "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
                 "traffic": traffic, "avg_launch_us": round(gu_us, 2), "launches": n_launch,
