@@ -11,6 +11,19 @@ import paper_2504_04104_amd as sp
 from oracle import StageOracle
 
 
+_OWN_STREAM = None
+
+
+def use_own_stream():
+    """The GPU tests run on a stream of their own, as bench.py does: the forward call captures and replays
+    HIP graphs of its launches only on a stream that can be captured, and the parity tests should see that
+    path whenever a shape comes back (streaming steps, repeated forwards)."""
+    global _OWN_STREAM
+    if _OWN_STREAM is None and torch.cuda.is_available():
+        _OWN_STREAM = torch.cuda.Stream(device="cuda:0")
+        torch.cuda.set_stream(_OWN_STREAM)
+
+
 def rel_err(gpu: np.ndarray, ref: np.ndarray) -> float:
     """max |gpu - ref| / max |ref| over a tensor."""
     ref = np.asarray(ref, np.float64)
@@ -32,6 +45,7 @@ class Pair:
     def __init__(self, shape: wl.ModelShape, seed: int, prefixes: Dict[int, int], *, tree_room: int = 256 + 64,
                  flags: int = 0, max_batch_nodes: int = 64, oracle: bool = True, vocab: int = 0,
                  oracle_reqs: Optional[Sequence[int]] = None, page_slots: int = 0, head_gain: float = 1.0):
+        use_own_stream()
         self.shape, self.seed = shape, seed
         self.vocab = vocab
         # the float64 oracle may follow a sample of the requests only (large batches)

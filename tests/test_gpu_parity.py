@@ -211,6 +211,35 @@ def test_forward_replays_from_a_hip_graph():
     pair.close()
 
 
+def test_forward_graph_of_its_own_matches_eager_calls():
+    """On a stream that can be captured the forward call replays a graph of its own launches from the
+    second time a shape is seen.  The same steps on a stage that may not (SP_FLAG_NO_GRAPHS) must give
+    the same bits, call after call, with other shapes and a prune in between."""
+    shape = MINI_GQA4
+    a = Pair(shape, 27, {0: 70}, flags=sp.SP_FLAG_PACKED_WEIGHTS, oracle=False)
+    b = Pair(shape, 27, {0: 70}, flags=sp.SP_FLAG_PACKED_WEIGHTS | sp.SP_FLAG_NO_GRAPHS, oracle=False)
+    assert torch.cuda.current_stream() != torch.cuda.default_stream()
+    par = wl.tree_uniform_parents(27, 19, 5, name=("r",))
+    for rep in range(5):
+        outs = []
+        for pair in (a, b):
+            g = pair.gpu
+            g.request_init(0, pair.base[0], pair.cap[0], 70)
+            g.tree_insert(0, par)
+            x = to_dev(wl.hidden_rows(shape, 27, ("r", rep), 19), g)
+            y = g.stage_forward([0], [0], [19], x)                      # shape seen again: replayed on `a`
+            g.tree_insert(0, [3, 3, 7])
+            y2 = g.stage_forward([0], [19], [3], to_dev(wl.hidden_rows(shape, 27, ("r2", rep), 3), g))
+            g.tree_prune(0, sp.SP_DROP, 2)
+            g.kv_compact(0)
+            outs.append((y.clone(), y2.clone(), pair.rows(0, 0, 70 + 22)))
+        torch.cuda.synchronize()
+        for u, v in zip(outs[0], outs[1]):
+            assert torch.equal(u.view(torch.int16), v.view(torch.int16)), rep
+    a.close()
+    b.close()
+
+
 def test_tables_only_random_sequences():
     """Insert / accept / drop sequences up to the 256-node cap: tables bit-exact after every call."""
     pair = Pair(MINI_F32, 14, {0: 5}, tree_room=4096)
