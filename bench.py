@@ -230,7 +230,8 @@ def main() -> int:
                "seconds": round(c1 - c0, 2), "gpu_vs_oracle_rel_err": rel}
 
     out = {
-        "metric": "8B-shape 4-layer stage step: tree tokens/s (step latency in ms_per_step)",
+        "metric": ("8B-shape 4-layer" if args.workload == "C2" else "70B-shape 10-layer") +
+                  " stage step: tree tokens/s (step latency in ms_per_step)",
         "value": round(tok_per_s, 1), "unit": "tree tokens/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
