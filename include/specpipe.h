@@ -311,6 +311,25 @@ int sp_stage_verify_head(sp_stage* stage, const sp_head_weights* head, int32_t n
                          int32_t* pred_out /*device, nullable*/, float* max_out /*device, nullable*/,
                          sp_stream stream);
 
+/* For callers that cannot allocate device memory or hand over a workspace at the time of the call
+ * (code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc):
+ * sp_stage_verify_head with its intermediate buffers -- row descriptors, the normalised rows and the
+ * per-tile (value, index) pairs or logits -- in a fixed array of SP_NOALLOC_SCRATCH_BYTES inside the
+ * library's device image instead of the stage's workspace.  Same arguments, same results, same
+ * errors, plus SP_E_CAPACITY when the call carries more than SP_NOALLOC_MAX_ROWS rows or its buffers
+ * (rows * d_model * 6 bytes in bf16, plus rows * vocab / 32 floats on the matrix-core path or
+ * rows * vocab floats otherwise) exceed the array.  Calls no allocating routine.  Every GPU the
+ * library has created a stage on holds one such array until the process ends; all calls on a GPU
+ * share it, each call overwrites what it reads before reading it (nothing has to start at zero),
+ * and calls that overlap on one GPU (different streams) race. */
+#define SP_NOALLOC_MAX_ROWS 64
+#define SP_NOALLOC_SCRATCH_BYTES (8u << 20)
+int sp_stage_verify_head_noalloc(sp_stage* stage, const sp_head_weights* head, int32_t n_req,
+                                 const int32_t* req_ids /*host*/, const int32_t* first_node /*host*/,
+                                 const int32_t* n_nodes /*host*/, const void* x /*device*/,
+                                 int32_t* pred_out /*device, nullable*/, float* max_out /*device, nullable*/,
+                                 sp_stream stream);
+
 /* Declares the model's token after the committed context of a request whose tree the
  * last stage has not fed yet (after prefill or a stall).  Later it follows the accepts. */
 int sp_request_set_root_pred(sp_stage* stage, int32_t req, int32_t token, sp_stream stream);

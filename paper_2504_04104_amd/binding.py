@@ -98,6 +98,7 @@ def load_library(path: Optional[str] = None) -> C.CDLL:
         "sp_pack_matrix": [vp, vp, C.c_int32, C.c_int32, vp],
         "sp_request_init": [vp, C.c_int32, C.c_int64, C.c_int32, C.c_int32, vp],
         "sp_stage_verify_head": [vp, C.POINTER(sp_head_weights), C.c_int32, i32p, i32p, i32p, vp, vp, vp, vp],
+        "sp_stage_verify_head_noalloc": [vp, C.POINTER(sp_head_weights), C.c_int32, i32p, i32p, i32p, vp, vp, vp, vp],
         "sp_stage_verify_lossy": [vp, C.POINTER(sp_head_weights), C.c_int32, i32p, vp, C.c_int32, C.c_float, vp,
                                   i32p, vp],
         "sp_request_set_root_pred": [vp, C.c_int32, C.c_int32, vp],
@@ -329,10 +330,22 @@ class Stage:
 
     # -- verification on the last stage ------------------------------------------------------
     def verify_head(self, head: Dict[str, "object"], req_ids: Sequence[int], first_node: Sequence[int],
-                    n_nodes: Sequence[int], x, want_max: bool = False):
+                    n_nodes: Sequence[int], x, want_max: bool = False, noalloc: bool = False, out=None):
         """head: {"norm": tensor [d], "wvocab": tensor [V, d] (re-laid if the stage uses packed weights)}.
-        Returns the device tensor of predictions (int32 per row) and, if asked, the winning logits."""
+        Returns the device tensor of predictions (int32 per row) and, if asked, the winning logits.
+        noalloc: call sp_stage_verify_head_noalloc (scratch inside the library) with the caller's
+        output tensors out = (pred int32 [rows], max float32 [rows] or None)."""
         import torch
+        if noalloc:
+            ra, rp = _i32(req_ids)
+            fa, fp = _i32(first_node)
+            na, npn = _i32(n_nodes)
+            pred, mx = out
+            h = sp_head_weights(head["norm"].data_ptr(), head["wvocab"].data_ptr(), int(head["wvocab"].shape[0]), 0)
+            _check(self.lib.sp_stage_verify_head_noalloc(self.handle, C.byref(h), len(ra), rp, fp, npn, x.data_ptr(),
+                                                         pred.data_ptr(), mx.data_ptr() if mx is not None else None,
+                                                         self._stream()), "sp_stage_verify_head_noalloc")
+            return pred, mx
         ra, rp = _i32(req_ids)
         fa, fp = _i32(first_node)
         na, npn = _i32(n_nodes)

@@ -108,6 +108,14 @@ inline size_t page_table_bytes(const sp_config& c) {
 
 }  // namespace
 
+// Scratch of the allocation-free entry point (sp_stage_verify_head_noalloc): a fixed array in the
+// library's own device image, so that a call needs no workspace from anybody.  Every GPU the library
+// runs on holds one copy at its own address; the name below is only a host-side handle, the address
+// is asked for once per device (sp_stage_create) and kept in g_noalloc_scratch[device].
+#define SP_NOALLOC_MAX_DEVICES 64
+static __device__ __align__(256) unsigned char sp_noalloc_scratch[SP_NOALLOC_SCRATCH_BYTES];
+static void* g_noalloc_scratch[SP_NOALLOC_MAX_DEVICES];
+
 struct sp_stage {
   sp_config cfg;
   std::vector<sp_layer_weights> W;
@@ -136,6 +144,7 @@ struct sp_stage {
   bool fast = false;           // bf16 MFMA kernels in use
   bool packed = false;         // weights are in MFMA fragment order
   int n_cu = 256;              // compute units of the device
+  int device = 0;              // the device that was current at sp_stage_create
   int last_hip = 0;
   // profiling
   int prof_kind = 0, prof_max = 0, prof_n = 0;
@@ -311,9 +320,16 @@ int sp_stage_create(const sp_config* cfg, const sp_layer_weights* layers, const 
             (cfg->n_q_heads * cfg->d_head) % 256 == 0;
   {
     int dev = 0, cus = 0;
-    if (hipGetDevice(&dev) == hipSuccess &&
-        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && cus > 0)
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= SP_NOALLOC_MAX_DEVICES) { delete s; return SP_E_HIP; }
+    s->device = dev;
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && cus > 0)
       s->n_cu = cus;
+    if (!g_noalloc_scratch[dev]) {
+      // this device's copy of the static scratch array (the device is current here)
+      void* p = nullptr;
+      if (hipGetSymbolAddress(&p, HIP_SYMBOL(sp_noalloc_scratch)) != hipSuccess || !p) { delete s; return SP_E_HIP; }
+      g_noalloc_scratch[dev] = p;
+    }
   }
   s->use_graphs = !(cfg->flags & SP_FLAG_NO_GRAPHS);
   s->packed = (cfg->flags & SP_FLAG_PACKED_WEIGHTS) != 0;
@@ -871,9 +887,20 @@ int sp_request_set_root_pred(sp_stage* s, int32_t req, int32_t token, sp_stream 
   return e == hipSuccess ? SP_OK : hip_fail(s, e);
 }
 
-int sp_stage_verify_head(sp_stage* s, const sp_head_weights* head, int32_t n_req, const int32_t* req_ids,
-                         const int32_t* first_node, const int32_t* n_nodes, const void* x, int32_t* pred_out,
-                         float* max_out, sp_stream stream) {
+// Device buffers the output head works in: the stage's workspace, or the static scratch array.
+struct HeadScratch {
+  RowInfo* rows;
+  float* cs;
+  float* h;
+  void* xn;
+  float* part;
+  size_t part_floats;
+  int max_rows;
+};
+
+static int verify_head_on(sp_stage* s, const HeadScratch& w, const sp_head_weights* head, int32_t n_req,
+                          const int32_t* req_ids, const int32_t* first_node, const int32_t* n_nodes, const void* x,
+                          int32_t* pred_out, float* max_out, sp_stream stream) {
   if (!s || !head || !req_ids || !first_node || !n_nodes) return SP_E_INVALID;
   if (!head->norm || !head->wvocab || head->vocab < 1) return SP_E_INVALID;
   if (n_req < 0 || n_req > SP_MAX_BATCH_REQ) return SP_E_CAPACITY;
@@ -896,12 +923,11 @@ int sp_stage_verify_head(sp_stage* s, const sp_head_weights* head, int32_t n_req
     ++b.n_req;
     rows += n_nodes[i];
   }
-  if (rows > c.max_batch_nodes) return SP_E_CAPACITY;
+  if (rows > w.max_rows) return SP_E_CAPACITY;
   if (rows == 0) return SP_OK;
   if (!x) return SP_E_INVALID;
   b.n_rows = rows;
   const int M = rows, d = c.d_model, V = head->vocab;
-  Workspace& w = s->ws;
   hipError_t e;
   // final RMSNorm (the row descriptors and the float copy of x it also writes are scratch here)
   AttnPlan rows_of;                                   // only the segment fields are read
@@ -927,6 +953,38 @@ int sp_stage_verify_head(sp_stage* s, const sp_head_weights* head, int32_t n_req
     if (e == hipSuccess) e = sp_launch_argmax_rows(false, w.part, V, b, s->d_tables, pred_out, max_out, st);
   }
   return e == hipSuccess ? SP_OK : hip_fail(s, e);
+}
+
+int sp_stage_verify_head(sp_stage* s, const sp_head_weights* head, int32_t n_req, const int32_t* req_ids,
+                         const int32_t* first_node, const int32_t* n_nodes, const void* x, int32_t* pred_out,
+                         float* max_out, sp_stream stream) {
+  if (!s) return SP_E_INVALID;
+  const Workspace& ws = s->ws;
+  const HeadScratch w = {ws.rows, ws.cs, ws.h, ws.xn, ws.part, ws.part_floats, s->cfg.max_batch_nodes};
+  return verify_head_on(s, w, head, n_req, req_ids, first_node, n_nodes, x, pred_out, max_out, stream);
+}
+
+int sp_stage_verify_head_noalloc(sp_stage* s, const sp_head_weights* head, int32_t n_req, const int32_t* req_ids,
+                                 const int32_t* first_node, const int32_t* n_nodes, const void* x,
+                                 int32_t* pred_out, float* max_out, sp_stream stream) {
+  if (!s) return SP_E_INVALID;
+  char* base = (char*)g_noalloc_scratch[s->device];     // this device's copy, looked up at sp_stage_create
+  if (!base) return SP_E_INVALID;
+  const sp_config& c = s->cfg;
+  // fixed carve for SP_NOALLOC_MAX_ROWS rows; whatever is left holds the (value, index) pairs or the logits
+  const size_t R = SP_NOALLOC_MAX_ROWS;
+  size_t off = 0;
+  auto take = [&](size_t bytes) { char* p = base + off; off += align_up(bytes); return (void*)p; };
+  HeadScratch w;
+  w.rows = (RowInfo*)take(R * sizeof(RowInfo));
+  w.cs = (float*)take(R * c.d_head * sizeof(float));
+  w.h = (float*)take(R * c.d_model * sizeof(float));
+  w.xn = take(R * c.d_model * (size_t)elt_bytes(c.dtype));
+  if (off + 256 > SP_NOALLOC_SCRATCH_BYTES) return SP_E_CAPACITY;      // d_model too large for the array
+  w.part = (float*)(base + off);
+  w.part_floats = (SP_NOALLOC_SCRATCH_BYTES - off) / sizeof(float);
+  w.max_rows = (int)R < c.max_batch_nodes ? (int)R : c.max_batch_nodes;
+  return verify_head_on(s, w, head, n_req, req_ids, first_node, n_nodes, x, pred_out, max_out, stream);
 }
 
 int sp_stage_verify_lossy(sp_stage* s, const sp_head_weights* head, int32_t n, const int32_t* req_ids,
