@@ -66,14 +66,15 @@ def tree_attention(q: np.ndarray, K: np.ndarray, V: np.ndarray,
     scale = 1.0 / np.sqrt(F64(dh))
     for i in range(n):
         vis = np.asarray(visible[i], dtype=np.int64)
-        for h in range(hq):
-            kh = K[vis, h // g, :]                       # [len, d_h]
-            vh = V[vis, h // g, :]
-            s = (kh @ q[i, h, :]) * scale
-            s = s - s.max()
-            p = np.exp(s)
-            p = p / p.sum()
-            out[i, h, :] = p @ vh
+        for kv in range(hkv):
+            kh = K[vis, kv, :]                           # [len, d_h]: the keys node i may see, this KV head
+            vh = V[vis, kv, :]
+            for h in range(kv * g, (kv + 1) * g):        # the query heads that read this KV head
+                s = (kh @ q[i, h, :]) * scale
+                s = s - s.max()
+                p = np.exp(s)
+                p = p / p.sum()
+                out[i, h, :] = p @ vh
     return out
 
 
@@ -158,7 +159,10 @@ class StageOracle:
         return first
 
     # -- node-wise computation on nodes [first, first+n) (library numbering) ---
-    def stage_forward(self, req: int, first: int, x: np.ndarray) -> np.ndarray:
+    def stage_forward(self, req: int, first: int, x: np.ndarray, mask: Optional[np.ndarray] = None) -> np.ndarray:
+        """mask: attend under this matrix instead of the tree's own M (same indexing, root = 0).
+        Positions still come from the true tree.  Tests use it to plant a wrong mask in the oracle
+        and measure how far the outputs move."""
         sh = self.shape
         st = self.req[req]
         x = np.asarray(x, F64)
@@ -170,7 +174,8 @@ class StageOracle:
         pos = (st.P - 1) + depth[idx]
         slots = (st.P - 1) + idx
         committed = np.arange(st.P - 1)                              # everything before the root
-        visible = [np.concatenate([committed, (st.P - 1) + np.nonzero(st.tree.M[i])[0]]) for i in idx]
+        M = st.tree.M if mask is None else np.asarray(mask)
+        visible = [np.concatenate([committed, (st.P - 1) + np.nonzero(M[i])[0]]) for i in idx]
         for l in range(sh.n_layers):
             x = decoder_layer(x, self.layer_weights(l), n_q_heads=sh.n_q_heads,
                               n_kv_heads=sh.n_kv_heads, d_head=sh.d_head, eps=sh.rms_eps,

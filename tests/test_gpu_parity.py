@@ -539,7 +539,9 @@ def test_verified_decoding_loop(shape, flags, tol):
         first = pair.insert(0, parents, tokens)
         x = emb[tokens]
         y = pair.gpu.stage_forward([0], [first], [len(tokens)], to_dev(x, pair.gpu))
-        pair.ora.stage_forward(0, first, x)
+        ref = pair.ora.stage_forward(0, first, x)
+        assert rel_err(to_np(y), ref) <= TOL[tol], step                       # a 12..24-token context: the mask shows
+        assert rel_err(to_np(y) - x, ref - x) <= 4 * TOL[tol], step            # the layers' own contribution (y is rounded to the storage type)
         pair.verify_head([0], [first], [len(tokens)], y, TOL[tol])
         pair.check_tables(0)
         node = pair.gpu.tree_match([0])[0]
@@ -554,11 +556,12 @@ def test_verified_decoding_loop(shape, flags, tol):
             pair.prune(0, sp.SP_CLEAR, 0)
             k = pair.insert(0, [-1], [want])
             y1 = pair.gpu.stage_forward([0], [k], [1], to_dev(emb[[want]], pair.gpu))
-            pair.ora.stage_forward(0, k, emb[[want]])
+            assert rel_err(to_np(y1), pair.ora.stage_forward(0, k, emb[[want]])) <= TOL[tol], step
             pair.verify_head([0], [k], [1], y1, TOL[tol])
             pair.prune(0, sp.SP_ACCEPT, k)
         assert pair.gpu.tree_read(0)["root_pred"] == pair.ora.req[0].pred[0]
-    say("verified decoding: hits", hits, "misses", misses, "tokens", emitted)
+    say("verified decoding: hits", hits, "misses", misses, "tokens", emitted, "near-ties decided by the GPU:", pair.pred_overrides)
+    assert pair.pred_overrides <= 2
     assert hits >= 3 and misses >= 1
     assert pair.gpu.request_info(0)[0] == 12 + len(emitted)
     pair.close()

@@ -23,7 +23,7 @@ import numpy as np
 __all__ = [
     "ModelShape", "Workload", "CONFIGS", "round_bf16", "to_bf16_bits", "from_bf16_bits",
     "rng", "normal", "layer_weights", "prefix_kv", "tree_uniform_parents",
-    "tree_branching", "tree_chain", "tree_star", "tree_static_levels", "bfs_sorted", "scaled", "hidden_rows",
+    "tree_branching", "tree_deep", "tree_chain", "tree_star", "tree_static_levels", "bfs_sorted", "scaled", "hidden_rows",
     "levels_of", "PruneOp", "StreamStep", "streaming_schedule", "BatchRequest",
     "batch_requests", "batch_schedule",
 ]
@@ -261,6 +261,26 @@ def tree_branching(seed: int, n: int, max_children: int, max_levels: int,
     return parents
 
 
+def tree_deep(seed: int, n: int, max_levels: int, window: int = 6, name: Sequence = ("deep",)) -> List[int]:
+    """A deep, narrow tree: node i's parent is uniform among the `window` nodes before it (the
+    committed tail while i < window), so levels grow with the index and a late node's ancestors are
+    spread over the whole index range; a draw that would create level max_levels is repeated over all
+    earlier nodes."""
+    g = rng(seed, *name)
+    parents: List[int] = []
+    lev: List[int] = []
+    for i in range(n):
+        lo = max(-1, i - window)
+        p = int(g.integers(lo, i))
+        l = 0 if p < 0 else lev[p] + 1
+        while l >= max_levels:
+            p = int(g.integers(-1, i))
+            l = 0 if p < 0 else lev[p] + 1
+        parents.append(p)
+        lev.append(l)
+    return parents
+
+
 def tree_chain(n: int) -> List[int]:
     return [i - 1 for i in range(n)]
 
@@ -358,13 +378,14 @@ class _HostTree:
 
 def streaming_schedule(seed: int, n_steps: int, max_new: int = 8, cap: int = 256,
                        p_accept: float = 0.7, max_levels: int = 0,
-                       name: Sequence = ("stream",)) -> List[StreamStep]:
+                       name: Sequence = ("stream",), initial: Sequence[int] = ()) -> List[StreamStep]:
     """Per step: insert 1..max_new nodes under uniformly random live nodes or the
     committed tail (clamped so the tree never exceeds `cap` live nodes), then
     with probability p_accept accept a random child of the committed tail (the
     root advances, its siblings' subtrees go), else drop a random subtree."""
     g = rng(seed, *name)
     t = _HostTree()
+    t.parents = list(initial)          # the live tree the schedule starts from (empty by default)
     steps: List[StreamStep] = []
     for _ in range(n_steps):
         n_new = int(g.integers(1, max_new + 1))
