@@ -21,7 +21,9 @@
  * table arena and the workspace are passed in as device pointers and must stay
  * valid until sp_stage_destroy().  The library allocates no device memory of
  * its own and creates no streams (the HIP graphs sp_stage_forward may build hold
- * whatever the runtime needs for them).  All device work of a call is enqueued
+ * whatever the runtime needs for them: up to 256 instantiated graphs per stage, one per distinct call
+ * shape, each of 9-10 kernel nodes per layer, i.e. some tens of kilobytes of host and device memory
+ * per graph that the HIP runtime allocates at the capturing call).  All device work of a call is enqueued
  * on the stream passed to it, in call order; calls return without waiting for
  * the GPU unless stated.  Host arrays passed in are read before the call returns.
  * One stream should carry all calls of a stage: the workspace, the page tables
@@ -66,7 +68,7 @@ typedef enum sp_status {
   SP_E_BAD_PARENT = -3,   /* parent not in {-1} U [0, index of the child)             */
   SP_E_BAD_REQ = -4,      /* request id out of range or not initialised               */
   SP_E_BAD_NODE = -5,     /* node index outside the live tree                         */
-  SP_E_ORDER = -6,        /* forward of a node whose parent has not been forwarded    */
+  SP_E_ORDER = -6,        /* forward / accept of a node whose path has not been forwarded */
   SP_E_PENDING = -7,      /* a prune awaits sp_kv_compact (or none does)              */
   SP_E_HIP = -8,          /* a HIP runtime call failed; see sp_last_hip_error()       */
   SP_E_UNSUPPORTED = -9   /* shape or dtype the kernels do not cover                  */
@@ -149,7 +151,9 @@ typedef struct sp_head_weights {
 
 /* ---- set-up ---------------------------------------------------------------- */
 
-/* Buffer sizes a stage of this config needs.  Pure host arithmetic. */
+/* Buffer sizes a stage of this config needs: the device state {E_i, M_i, KV_i} that Algorithm 1
+ * gives every device (hidden rows in flight, tree tables, KV cache) plus the scratch of one
+ * forward call.  Pure host arithmetic. */
 int sp_stage_query_sizes(const sp_config* cfg, sp_sizes* out);
 
 /* Load-time re-layout of one layer's four projection matrices (bf16) into the order the
@@ -169,15 +173,18 @@ int sp_pack_weights(const sp_config* cfg, const sp_layer_weights* in, const sp_l
 int sp_pack_matrix(const void* in /*device*/, void* out /*device, distinct*/, int32_t n_rows, int32_t n_cols,
                    sp_stream stream);
 
-/* Builds a stage.  `layers` is a host array of n_layers entries holding device
+/* Builds a stage: one device of the pipeline with its share of the model's layers and the state
+ * {E_i, M_i, KV_i} of Algorithm 1 ("Input": each device holds hidden states, a copy of the tree mask
+ * and its KV cache; Sec. 3.3.2).  `layers` is a host array of n_layers entries holding device
  * pointers.  Buffers must be at least as large as sp_stage_query_sizes() says and
  * 256-byte aligned.  The tables buffer is initialised on `stream`. */
 int sp_stage_create(const sp_config* cfg, const sp_layer_weights* layers, const sp_buffers* buffers,
                     sp_stream stream, sp_stage** out);
 void sp_stage_destroy(sp_stage* stage);
 
-/* Declares request `req`: it owns slots [slot_base, slot_base+capacity) of every
- * plane, of which the first prefix_len (>= 1: the root) already hold the rotated K
+/* Declares request `req` and its initial device state (Algorithm 1, "Input": KV_i holds the
+ * committed context, M_i is the mask of a tree that holds only the root): it owns slots
+ * [slot_base, slot_base+capacity) of every plane, of which the first prefix_len (>= 1: the root) already hold the rotated K
  * and V of the committed context for every layer.  Its tree becomes empty.  May be
  * called again to reset a request. */
 int sp_request_init(sp_stage* stage, int32_t req, int64_t slot_base, int32_t capacity,
@@ -252,7 +259,9 @@ int sp_stage_forward(sp_stage* stage, int32_t n_req, const int32_t* req_ids /*ho
  * On SP_ACCEPT the prediction stored for `node` becomes the root's (see sp_stage_verify_head).
  * Computes the keep flags from the mask column, their prefix sums, and the compacted
  * tables on the device, and leaves the old->new map there for sp_kv_compact, which
- * must be the next call for this request.  Outputs are computed on the host mirror. */
+ * must be the next call for this request.  Outputs are computed on the host mirror.
+ * SP_ACCEPT needs the whole path root..node to have been forwarded at this stage (its K/V rows
+ * become committed context): SP_E_ORDER otherwise. */
 int sp_tree_prune(sp_stage* stage, int32_t req, int32_t mode, int32_t node,
                   int32_t* n_live_out /*host, nullable*/, int32_t* n_commit_out /*host, nullable*/,
                   sp_stream stream);
@@ -277,7 +286,7 @@ int sp_tree_prune_batch(sp_stage* stage, int32_t n, const int32_t* req_ids, cons
                         int32_t* n_commit_out /*nullable*/, sp_stream stream);
 int sp_kv_compact_batch(sp_stage* stage, int32_t n, const int32_t* req_ids, sp_stream stream);
 
-/* Fixed-width expansion of the tree bottom (Sec. 3.4, "Fixed-width tree"): for each of the
+/* Fixed-width expansion of the tree bottom (Sec. 3.3.3, "Fixed-width tree"): for each of the
  * n_bottom nodes bottom_nodes[] (host; live nodes in ascending order, or the single entry -1
  * for the root of an empty tree) the token source proposes k candidates, cand_tokens /
  * cand_probs (device, [n_bottom][k]; a negative token marks an absent candidate).  A
@@ -292,7 +301,7 @@ int sp_tree_expand(sp_stage* stage, int32_t req, int32_t n_bottom, const int32_t
                    int32_t w, int32_t* out_parents /*device*/, int32_t* out_tokens /*device*/,
                    float* out_probs /*device*/, int32_t* out_count /*device*/, sp_stream stream);
 
-/* ---- verification on the last stage (Algorithm 1, "verify new token"; Sec. 3.3.3) ----- */
+/* ---- verification on the last stage (Algorithm 1, "verify new token"; Sec. 3.4) ----- */
 
 /* Next-token prediction of tree nodes from their outputs of the last decoder layer:
  *   pred = argmax_v ( RMSNorm(x; head->norm, rms_eps) . head->wvocab[v] ),
@@ -343,7 +352,7 @@ int sp_request_set_root_pred(sp_stage* stage, int32_t req, int32_t token, sp_str
 int sp_tree_match(sp_stage* stage, int32_t n, const int32_t* req_ids /*host*/, int32_t* nodes_dev /*device*/,
                   int32_t* nodes_host /*host, nullable*/, sp_stream stream);
 
-/* Lossy verification (Sec. 3.3.3, "Lossless and Lossy Acceleration").  x_root [n][d_model]
+/* Lossy verification (Sec. 3.4, "Lossless and Lossy Acceleration").  x_root [n][d_model]
  * (device, the stage's dtype) holds, for each listed request, the last decoder layer's output of
  * the node that is now the root (the caller keeps that row of sp_stage_forward's x_out from the
  * call that forwarded the node).  The large model's distribution after the root is

@@ -1,6 +1,6 @@
 """Fixed-width layer expansion, CPU oracle (TEST INFRASTRUCTURE, not product).
 
-Sec. 3.4 ("Fixed-width tree") and Sec. 4.3: for each token at the tree bottom the token source
+Sec. 3.3.3 ("Fixed-width tree") and Sec. 4.1: for each token at the tree bottom the token source
 proposes k candidates with their probabilities; a candidate's cumulative probability is its own
 probability times the probabilities, stored in P, of the bottom token and of all its ancestors;
 the w candidates with the highest cumulative probabilities are appended, sorted by the order

@@ -1,4 +1,4 @@
-"""Node-wise computation of one pipeline stage (Sec. 3.3.2, Algorithm 1 lines 1-3).
+"""Node-wise computation of one pipeline stage (Sec. 3.3.2; Algorithm 1, "Node-wise computation").
 
 TEST INFRASTRUCTURE.  `for each layer in device i: E_i <- layer(E_i, M_i, KV_i)`
 with the Llama-family decoder layer the paper builds on (Sec. 2.1, Sec. 4
@@ -244,7 +244,7 @@ class StageOracle:
     def verify_lossy(self, req: int, h_root: np.ndarray, gain: np.ndarray, w_vocab: np.ndarray, mode: str,
                      top_p: float = 1.0):
         """Lossy verification of the root's children from the root's last-layer output h_root [d]
-        (Sec. 3.3.3): mode "relaxed" or "top_p".  Returns (node or -1, top-1 token, logits) and
+        (Sec. 3.4): mode "relaxed" or "top_p".  Returns (node or -1, top-1 token, logits) and
         records the top-1 token as the root's prediction."""
         from .verify import lm_head_logits, greedy_token_fast, relaxed_choice, top_p_choice
         st = self.req[req]

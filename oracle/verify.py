@@ -1,7 +1,7 @@
 """Last-stage verification, CPU oracle (TEST INFRASTRUCTURE, not product).
 
 Sec. 3.3.2, node-wise computation: the last device infers the next token from the output of
-the large model; Algorithm 1, "verify new token tau_hat on device m"; Sec. 3.3.3: validation
+the large model; Algorithm 1, "verify new token tau_hat on device m"; Sec. 3.4: validation
 is against the top-1 prediction of the large model, which keeps decoding lossless.
 
 For a node tau whose hidden state h leaves the last decoder layer, the model's next token is
@@ -15,7 +15,7 @@ torch Linear in float64; argmax ties by hand-made rows; and the lossless propert
 tree-speculative run with distractor tokens and misses emits exactly the token sequence
 of plain one-token-at-a-time greedy decoding.
 
-Lossy verification (Sec. 3.3.3, "Lossless and Lossy Acceleration", options (1) and (2)):
+Lossy verification (Sec. 3.4, "Lossless and Lossy Acceleration", options (1) and (2)):
   relaxed: among the candidate tokens (the root's children) take the one the large model
            gives the highest probability -- every step verifies some child, no stall;
   top-p:   a child is acceptable if its token lies in the large model's top-p set (tokens in

@@ -400,9 +400,9 @@ int sp_request_release(sp_stage* s, int32_t req, sp_stream stream) {
   if (!s) return SP_E_INVALID;
   HostReq* r = get_req(s, req);
   if (!r) return SP_E_BAD_REQ;
-  if (is_paged(s->cfg)) (void)pages_resize(s, req, 0, (hipStream_t)stream);
+  hipError_t e = is_paged(s->cfg) ? pages_resize(s, req, 0, (hipStream_t)stream) : hipSuccess;
   r->active = false; r->pending = false; r->T = 0; r->P = 0;
-  return SP_OK;
+  return e == hipSuccess ? SP_OK : hip_fail(s, e);
 }
 
 int sp_request_pages(const sp_stage* s, int32_t req, int32_t* pages_out, int32_t max_pages, int32_t* n_pages_out) {
@@ -701,6 +701,7 @@ int sp_stage_forward(sp_stage* s, int32_t n_req, const int32_t* req_ids, const i
   bool done = false;
   if (fg) {
     ++fg->seen;
+    const int seen_before = s->prof_seen;
     if (!fg->exec && !fg->failed && fg->seen >= 2) {
       hipGraph_t graph = nullptr;
       if (hipStreamBeginCapture(st, hipStreamCaptureModeThreadLocal) == hipSuccess) {
@@ -723,7 +724,9 @@ int sp_stage_forward(sp_stage* s, int32_t n_req, const int32_t* req_ids, const i
     if (fg->exec) {
       SP_TRY(hipGraphLaunch(fg->exec, st));
       S_last = fg->S_last;
-      s->prof_seen += n_kind;                       // the sampling cadence counts the replayed launches too
+      // the sampling cadence counts the replayed launches too (once: the capturing call has already
+      // counted them while it recorded the launches)
+      s->prof_seen = seen_before + n_kind;
       done = true;
     }
   }
@@ -752,6 +755,9 @@ int sp_tree_prune_batch(sp_stage* s, int32_t n, const int32_t* req_ids, const in
     if (modes[i] != SP_ACCEPT && modes[i] != SP_DROP && modes[i] != SP_CLEAR) return SP_E_INVALID;
     if (r->pending) return SP_E_PENDING;
     if (modes[i] != SP_CLEAR && (nodes[i] < 0 || nodes[i] >= r->T)) return SP_E_BAD_NODE;
+    if (modes[i] == SP_ACCEPT)
+      // the path root..node joins the committed context: its K/V rows must exist at this stage
+      for (int j = nodes[i]; j >= 0; j = r->parent[j]) if (!r->fwd[j]) return SP_E_ORDER;
     for (int j = 0; j < i; ++j) if (modes[j] >= 0 && req_ids[j] == req_ids[i]) return SP_E_INVALID;
     any = true;
   }
@@ -804,13 +810,17 @@ static int compact_batch(sp_stage* s, int32_t n, const int32_t* req_ids, void* r
     hipError_t e = sp_launch_kv_compact(s->d_meta, s->d_tables, b, s->geom, rows, rb, (int)rb, list, (hipStream_t)stream);
     if (e != hipSuccess) return hip_fail(s, e);
   }
+  hipError_t e_pages = hipSuccess;
   for (int i = 0; i < n; ++i) {
     HostReq& r = s->reqs[req_ids[i]];
     r.pending = false;
     // pages past the compacted rows go back to the allocator (work queued later runs after the gather)
-    if (is_paged(s->cfg)) (void)pages_resize(s, req_ids[i], r.P + r.T, (hipStream_t)stream);
+    if (is_paged(s->cfg)) {
+      const hipError_t e = pages_resize(s, req_ids[i], r.P + r.T, (hipStream_t)stream);
+      if (e != hipSuccess && e_pages == hipSuccess) e_pages = e;
+    }
   }
-  return SP_OK;
+  return e_pages == hipSuccess ? SP_OK : hip_fail(s, e_pages);
 }
 
 int sp_kv_compact_batch(sp_stage* s, int32_t n, const int32_t* req_ids, sp_stream stream) {

@@ -179,7 +179,7 @@ __global__ void k_finish(const float* h, const float* part, int S, size_t part_s
     Vec4<T>::st(out + i, *reinterpret_cast<const f32x4_t*>(h + i) + fold4(part + i, S, part_stride));
 }
 
-// Top-1 token of each row (Sec. 3.3.3) from either the per-tile (value, index) pairs the
+// Top-1 token of each row (Sec. 3.4) from either the per-tile (value, index) pairs the
 // output-head kernel left (PAIRS) or plain logits [rows][n_items]; the lowest index among
 // equal maxima.  Also stores it as the node's prediction in the request's tables.
 template <bool PAIRS>

@@ -296,7 +296,7 @@ hipError_t sp_launch_tree_insert(ReqMeta* meta, ReqTables* tables, const InsertA
 }
 // -----------------------------------------------------------------------------
 // Verification of the root's successor (Algorithm 1, "verify new token"; top-1 rule of
-// Sec. 3.3.3): the verified node is the first child of the root whose token is the
+// Sec. 3.4): the verified node is the first child of the root whose token is the
 // model's token after the committed context; -1 if no child carries it (pipeline stall)
 // or the prediction is not known yet.  One workgroup per request, thread t = node t.
 struct MatchBatch {
@@ -342,7 +342,7 @@ hipError_t sp_launch_set_root_pred(ReqMeta* meta, int req, int token, hipStream_
 }
 
 // -----------------------------------------------------------------------------
-// Fixed-width expansion (Sec. 3.4 "Fixed-width tree"): candidate c = (bottom token c / k,
+// Fixed-width expansion (Sec. 3.3.3 "Fixed-width tree"): candidate c = (bottom token c / k,
 // proposal c % k) has cumulative probability P[ancestors, root first] * P[bottom] * p(c),
 // multiplied in that order in float32.  The w largest are kept (an earlier candidate wins a
 // tie) and come out in candidate order, which is parent order (Sec. 3.2 "Layer appending").

@@ -1,4 +1,4 @@
-// Lossy verification at the last stage (Sec. 3.3.3, "Lossless and Lossy Acceleration"):
+// Lossy verification at the last stage (Sec. 3.4, "Lossless and Lossy Acceleration"):
 //   (1) relaxed: of the root's children, the one whose token the large model finds most
 //       probable -- some child is always verified, the pipeline never stalls;
 //   (2) top-p:   children whose token lies in the large model's top-p set (tokens in descending

@@ -341,7 +341,7 @@ def run_verify(args):
     stage.stage_forward([0], [0], [n], x, y)
     t_head = timed(head_only, 30)
     hd_us, cnt = kernel_us(stage, head_only, B.K_VERIFY_HEAD)
-    # fixed-width expansion of a full level: 64 bottom tokens x 16 candidates, width 64 (Sec. 4.3's setting)
+    # fixed-width expansion of a full level: 64 bottom tokens x 16 candidates, width 64 (Sec. 4.1's setting)
     stage.request_init(0, 0, cap, P)
     stage.tree_insert(0, [-1] * 64, list(range(64)), [0.5] * 64)
     ct = torch.randint(0, V, (64, 16), device=DEV, dtype=torch.int32)

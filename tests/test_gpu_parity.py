@@ -242,16 +242,23 @@ def test_forward_graph_of_its_own_matches_eager_calls():
 
 def test_tables_only_random_sequences():
     """Insert / accept / drop sequences up to the 256-node cap: tables bit-exact after every call."""
-    pair = Pair(MINI_F32, 14, {0: 5}, tree_room=4096)
+    pair = Pair(MINI_F32, 14, {0: 5}, tree_room=4096, max_batch_nodes=256)
     g = wl.rng(14, "seq")
     n_live = 0
+
+    def forward_zeros(first, k):
+        # an accept commits the K/V rows of the accepted path, so they must exist: the library refuses
+        # to accept a node that was never forwarded
+        if k:
+            pair.gpu.stage_forward([0], [first], [k], torch.zeros(k, MINI_F32.d_model, device="cuda:0"))
+
     for step in range(60):
         room = 256 - n_live
         k = int(g.integers(0, min(room, 40) + 1))
         parents = [int(g.integers(-1, n_live + i)) for i in range(k)]
         toks = [int(g.integers(0, 1 << 20)) for _ in range(k)]
         prbs = [float(g.random()) for _ in range(k)]
-        pair.insert(0, parents, toks, prbs)
+        forward_zeros(pair.insert(0, parents, toks, prbs), k)
         n_live += k
         pair.check_tables(0)
         if n_live and g.random() < 0.8:
@@ -260,7 +267,7 @@ def test_tables_only_random_sequences():
             pair.prune(0, mode, node)
             n_live = pair.gpu.request_info(0)[1]
     # fill to the cap exactly, then prune at the last node
-    pair.insert(0, [-1] * (256 - n_live))
+    forward_zeros(pair.insert(0, [-1] * (256 - n_live)), 256 - n_live)
     pair.check_tables(0)
     pair.prune(0, sp.SP_DROP, 255)
     pair.prune(0, sp.SP_ACCEPT, 0)
@@ -577,7 +584,7 @@ TOL_LOGIT = {"f32": 1e-5, "bf16": 2e-3}
                                                (MINI_BF16, sp.SP_FLAG_SIMPLE_KERNELS, "bf16", 2113)],
                          ids=["f32_v97", "bf16_v1088", "bf16_packed_v4160", "bf16_simple_v2113"])
 def test_lossy_verification(shape, flags, tol, V):
-    """Relaxed and top-p verification (Sec. 3.3.3) of the roots' children for three requests at once:
+    """Relaxed and top-p verification (Sec. 3.4) of the roots' children for three requests at once:
     vocabularies of one slice, of several slices with a short last one, and of odd size; children with
     duplicate tokens, a token outside the vocabulary, deeper nodes that must not count, a request
     whose root has no child."""
@@ -700,6 +707,7 @@ def test_error_codes():
     assert status(g.stage_forward, [0], [2], [1], x) == -6          # parent 1 not forwarded
     assert status(g.stage_forward, [0], [2], [5], torch.zeros(5, 256, device=g.device)) == -5
     assert status(g.tree_prune, 0, sp.SP_ACCEPT, 3) == -5
+    assert status(g.tree_prune, 0, sp.SP_ACCEPT, 1) == -6           # its K/V rows do not exist yet
     assert status(g.kv_compact, 0) == -7                            # nothing pending
     g.tree_prune(0, sp.SP_DROP, 2)
     assert status(g.tree_insert, 0, [-1]) == -7                     # compaction pending

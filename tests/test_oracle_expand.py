@@ -1,4 +1,4 @@
-"""Pins for oracle/expand.py (fixed-width layer expansion, Sec. 3.4): a hand-worked example,
+"""Pins for oracle/expand.py (fixed-width layer expansion, Sec. 3.3.3): a hand-worked example,
 brute force over all subsets on tiny inputs, and properties of any correct selection."""
 import itertools
 

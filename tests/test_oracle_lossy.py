@@ -1,4 +1,4 @@
-"""Pins for the oracle's lossy verification (Sec. 3.3.3, options (1) relaxed and (2) top-p)
+"""Pins for the oracle's lossy verification (Sec. 3.4, options (1) relaxed and (2) top-p)
 against things other than itself: an exhaustive subset search, Hugging Face's top-p warper,
 and the limits in which both options reduce to rules already pinned elsewhere."""
 import itertools

@@ -3,7 +3,7 @@
 The output head is checked against Hugging Face's LlamaRMSNorm and a torch Linear; the
 greedy token against hand-made rows; the whole verify / accept / miss loop against the
 property that makes the method lossless (Sec. 3.3.2: the selection strictly follows the
-output of the large model; Sec. 3.3.3: top-1 validation): decoding through a speculative
+output of the large model; Sec. 3.4: top-1 validation): decoding through a speculative
 tree full of wrong guesses must emit exactly the tokens of plain one-token-at-a-time greedy
 decoding, which is the T=1 case already pinned against the Hugging Face layer."""
 import numpy as np
