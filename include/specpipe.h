@@ -352,6 +352,20 @@ int sp_request_set_root_pred(sp_stage* stage, int32_t req, int32_t token, sp_str
 int sp_tree_match(sp_stage* stage, int32_t n, const int32_t* req_ids /*host*/, int32_t* nodes_dev /*device*/,
                   int32_t* nodes_host /*host, nullable*/, sp_stream stream);
 
+/* Pruning propagation decided on the device: sp_tree_prune + sp_kv_compact (without hidden rows) for the
+ * listed requests, the verified node of request i read by the prune kernel from nodes_dev[i * stride]
+ * (device; the output of sp_tree_match with stride 1, of sp_stage_verify_lossy with stride 2): a live node is
+ * accepted (SP_ACCEPT), -1 clears the tree (SP_CLEAR: the stall of Algorithm 1, after which the caller
+ * inserts the true token).  Nothing waits for the host between verification and pruning (Sec. 3.4, "Input
+ * more than one tree-level", names GPU-CPU synchronisation as what makes verification of several levels
+ * slow); the call also queues a copy of the nodes to pinned host memory, and the library's host-side view of
+ * these requests (prefix_len, n_live, parents; the pages they hold) catches up at the next call that names
+ * one of them, which waits for that copy if it has not arrived.  The verified nodes must have been forwarded
+ * at this stage (as they have when verification follows their forward).  Not for use under stream capture.
+ * Errors: SP_E_BAD_REQ, SP_E_PENDING, SP_E_INVALID (repeated request, stride not 1 or 2). */
+int sp_tree_prune_verified(sp_stage* stage, int32_t n, const int32_t* req_ids /*host*/,
+                           const int32_t* nodes_dev /*device*/, int32_t stride, sp_stream stream);
+
 /* Lossy verification (Sec. 3.4, "Lossless and Lossy Acceleration").  x_root [n][d_model]
  * (device, the stage's dtype) holds, for each listed request, the last decoder layer's output of
  * the node that is now the root (the caller keeps that row of sp_stage_forward's x_out from the

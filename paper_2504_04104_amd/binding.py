@@ -112,6 +112,7 @@ def load_library(path: Optional[str] = None) -> C.CDLL:
         "sp_stage_forward": [vp, C.c_int32, i32p, i32p, i32p, vp, vp, vp],
         "sp_tree_prune": [vp, C.c_int32, C.c_int32, C.c_int32, i32p, i32p, vp],
         "sp_kv_compact": [vp, C.c_int32, vp, C.c_int32, i32p, i32p, i32p, vp],
+        "sp_tree_prune_verified": [vp, C.c_int32, i32p, vp, C.c_int32, vp],
         "sp_tree_prune_batch": [vp, C.c_int32, i32p, i32p, i32p, i32p, i32p, vp],
         "sp_kv_compact_batch": [vp, C.c_int32, i32p, vp],
         "sp_tree_read": [vp, C.c_int32, C.POINTER(sp_tree_view), vp],
@@ -298,6 +299,13 @@ class Stage:
                                       out.ctypes.data_as(C.POINTER(C.c_int32)), self._stream()), "sp_kv_compact")
         return n_out.value, out[:n_out.value].tolist()
 
+    def tree_prune_verified(self, req_ids: Sequence[int], nodes_dev, stride: int = 1):
+        """Prune + cache compaction by the verified nodes a device tensor holds (int32; the result of
+        tree_match_dev or of verify_lossy's device output)."""
+        ra, rp = _i32(req_ids)
+        _check(self.lib.sp_tree_prune_verified(self.handle, len(ra), rp, nodes_dev.data_ptr(), stride, self._stream()),
+               "sp_tree_prune_verified")
+
     def tree_prune_batch(self, req_ids, modes, nodes):
         ra, rp = _i32(req_ids)
         ma, mp = _i32(modes)
@@ -399,6 +407,26 @@ class Stage:
                "sp_stage_verify_lossy")
         torch.cuda.current_stream(self.device).synchronize()
         return [(int(host[2 * i]), int(host[2 * i + 1])) for i in range(n)]
+
+    def tree_match_dev(self, req_ids: Sequence[int]):
+        """sp_tree_match without the host copy: the device tensor of verified nodes (int32 per request),
+        valid in stream order; nothing waits."""
+        import torch
+        ra, rp = _i32(req_ids)
+        dev = torch.empty(max(len(ra), 1), dtype=torch.int32, device=self.device)
+        _check(self.lib.sp_tree_match(self.handle, len(ra), rp, dev.data_ptr(), None, self._stream()), "sp_tree_match")
+        return dev
+
+    def verify_lossy_dev(self, head: Dict[str, "object"], req_ids: Sequence[int], x_root, mode: int, top_p: float = 1.0):
+        """sp_stage_verify_lossy without the host copy: device tensor [2 * len(req_ids)] of (node, top-1 token)."""
+        import torch
+        ra, rp = _i32(req_ids)
+        n = len(ra)
+        dev = torch.empty(max(2 * n, 2), dtype=torch.int32, device=self.device)
+        h = sp_head_weights(head["norm"].data_ptr(), head["wvocab"].data_ptr(), int(head["wvocab"].shape[0]), 0)
+        _check(self.lib.sp_stage_verify_lossy(self.handle, C.byref(h), n, rp, x_root.data_ptr(), int(mode),
+                                              float(top_p), dev.data_ptr(), None, self._stream()), "sp_stage_verify_lossy")
+        return dev
 
     def tree_match(self, req_ids: Sequence[int]) -> List[int]:
         """Verified root child per request (-1 = miss); waits for the stream."""

@@ -27,6 +27,10 @@ struct HostReq {
   int pend_mode = 0, pend_node = 0;
   short pend_tab_new[SP_T];     // old node -> new index, -1 gone
   std::vector<int> pages;       // paged cache: physical page of every logical page the request holds
+  // A prune decided on the device (sp_tree_prune_verified) whose outcome the mirror has not taken yet:
+  // the verified node arrives in pinned host memory, entry unrec_slot, once the stage's copy event is done.
+  bool unrec = false;
+  int unrec_slot = 0;
 };
 
 inline size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
@@ -143,6 +147,8 @@ struct sp_stage {
   bool use_graphs = true;
   bool fast = false;           // bf16 MFMA kernels in use
   bool packed = false;         // weights are in MFMA fragment order
+  int* pin_nodes = nullptr;    // pinned host copy of the device-side verification results (sp_tree_prune_verified)
+  hipEvent_t rec_ev = nullptr; // done when that copy has arrived
   int n_cu = 256;              // compute units of the device
   int device = 0;              // the device that was current at sp_stage_create
   int last_hip = 0;
@@ -198,8 +204,11 @@ hipError_t pages_resize(sp_stage* s, int req, int slots, hipStream_t st) {
 }
 inline int pages_for(const sp_stage* s, int slots) { return (slots + s->cfg.page_slots - 1) / s->cfg.page_slots; }
 
+void reconcile(sp_stage* s, int req);
+
 HostReq* get_req(sp_stage* s, int req) {
   if (!s || req < 0 || req >= (int)s->reqs.size() || !s->reqs[req].active) return nullptr;
+  if (s->reqs[req].unrec) reconcile(s, req);
   return &s->reqs[req];
 }
 
@@ -231,6 +240,22 @@ void mirror_prune(HostReq& r, int mode, int node, int* n_tab, int* n_commit) {
   r.P += commit;
   *n_tab = k;
   *n_commit = commit;
+}
+
+// The mirror catches up with a prune that was decided on the device: waits for the copy of the verified
+// node (queued right behind the kernel that produced it, so it has normally arrived long before any
+// host code asks), then replays the prune on the parent list and returns the freed pages.
+void reconcile(sp_stage* s, int req) {
+  HostReq& r = s->reqs[req];
+  if (!r.unrec) return;
+  r.unrec = false;
+  if (hipEventSynchronize(s->rec_ev) != hipSuccess) return;
+  const int node = s->pin_nodes[r.unrec_slot];
+  const int mode = (node >= 0 && node < r.T) ? SP_ACCEPT : SP_CLEAR;
+  int live = 0, commit = 0;
+  mirror_prune(r, mode, node, &live, &commit);
+  r.pending = false;                               // the compaction was queued together with the prune
+  if (is_paged(s->cfg)) (void)pages_resize(s, req, r.P + r.T, nullptr);
 }
 
 }  // namespace
@@ -344,6 +369,8 @@ void sp_stage_destroy(sp_stage* stage) {
   if (!stage) return;
   for (hipEvent_t ev : stage->prof_ev) (void)hipEventDestroy(ev);
   for (auto& g : stage->graphs) if (g.exec) (void)hipGraphExecDestroy(g.exec);
+  if (stage->rec_ev) (void)hipEventDestroy(stage->rec_ev);
+  if (stage->pin_nodes) (void)hipHostFree(stage->pin_nodes);
   delete stage;
 }
 
@@ -374,6 +401,8 @@ int sp_request_init(sp_stage* s, int32_t req, int64_t slot_base, int32_t capacit
   if (!s) return SP_E_INVALID;
   if (req < 0 || req >= (int)s->reqs.size()) return SP_E_BAD_REQ;
   if (slot_base < 0 || capacity < 1 || prefix_len < 1) return SP_E_INVALID;
+  // a reset does not care how a device-side prune of the old tree came out (its pages all go back below)
+  s->reqs[req].unrec = false;
   HostReq& r = s->reqs[req];
   const bool paged = is_paged(s->cfg);
   if (paged) {
@@ -393,6 +422,7 @@ int sp_request_init(sp_stage* s, int32_t req, int64_t slot_base, int32_t capacit
       return hip_fail(s, e);
   }
   r.active = true; r.base = slot_base; r.cap = capacity; r.P = prefix_len; r.T = 0; r.pending = false;
+  r.unrec = false;
   return SP_OK;
 }
 
@@ -407,6 +437,7 @@ int sp_request_release(sp_stage* s, int32_t req, sp_stream stream) {
 
 int sp_request_pages(const sp_stage* s, int32_t req, int32_t* pages_out, int32_t max_pages, int32_t* n_pages_out) {
   if (!s || req < 0 || req >= (int)s->reqs.size() || !s->reqs[req].active) return s ? SP_E_BAD_REQ : SP_E_INVALID;
+  if (s->reqs[req].unrec) reconcile(const_cast<sp_stage*>(s), req);
   if (!is_paged(s->cfg)) return SP_E_UNSUPPORTED;
   const HostReq& r = s->reqs[req];
   if (n_pages_out) *n_pages_out = (int32_t)r.pages.size();
@@ -417,11 +448,17 @@ int sp_request_pages(const sp_stage* s, int32_t req, int32_t* pages_out, int32_t
   return SP_OK;
 }
 
-int sp_stage_free_pages(const sp_stage* s) { return s ? (int)s->free_pages.size() : SP_E_INVALID; }
+int sp_stage_free_pages(const sp_stage* s) {
+  if (!s) return SP_E_INVALID;
+  for (size_t r = 0; r < s->reqs.size(); ++r)
+    if (s->reqs[r].active && s->reqs[r].unrec) reconcile(const_cast<sp_stage*>(s), (int)r);
+  return (int)s->free_pages.size();
+}
 
 int sp_request_info(const sp_stage* s, int32_t req, int32_t* prefix_len, int32_t* n_live, int32_t* n_forwarded) {
   if (!s) return SP_E_INVALID;
   if (req < 0 || req >= (int)s->reqs.size() || !s->reqs[req].active) return SP_E_BAD_REQ;
+  if (s->reqs[req].unrec) reconcile(const_cast<sp_stage*>(s), req);
   const HostReq& r = s->reqs[req];
   if (prefix_len) *prefix_len = r.P;
   if (n_live) *n_live = r.T;
@@ -762,7 +799,7 @@ int sp_tree_prune_batch(sp_stage* s, int32_t n, const int32_t* req_ids, const in
     any = true;
   }
   if (any) {
-    hipError_t e = sp_launch_tree_prune(s->d_meta, s->d_tables, b, (hipStream_t)stream);
+    hipError_t e = sp_launch_tree_prune(s->d_meta, s->d_tables, b, nullptr, 0, (hipStream_t)stream);
     if (e != hipSuccess) return hip_fail(s, e);
   }
   for (int i = 0; i < n; ++i) {
@@ -787,6 +824,48 @@ int sp_tree_prune(sp_stage* s, int32_t req, int32_t mode, int32_t node, int32_t*
   if (!s) return SP_E_INVALID;
   ProfScope scope(s, SP_K_TREE_PRUNE, (hipStream_t)stream);
   return sp_tree_prune_batch(s, 1, &req, &mode, &node, n_live_out, n_commit_out, stream);
+}
+
+int sp_tree_prune_verified(sp_stage* s, int32_t n, const int32_t* req_ids, const int32_t* nodes_dev, int32_t stride,
+                           sp_stream stream) {
+  if (!s || !req_ids || !nodes_dev) return SP_E_INVALID;
+  if (n < 0 || n > SP_MAX_BATCH_REQ) return SP_E_CAPACITY;
+  if (stride < 1 || stride > 2) return SP_E_INVALID;
+  PruneBatch b;
+  b.n = n;
+  for (int i = 0; i < n; ++i) {
+    HostReq* r = get_req(s, req_ids[i]);                  // (takes in any earlier device-side prune of the request)
+    if (!r) return SP_E_BAD_REQ;
+    if (r->pending) return SP_E_PENDING;
+    for (int j = 0; j < i; ++j) if (req_ids[j] == req_ids[i]) return SP_E_INVALID;
+    b.req[i] = req_ids[i]; b.mode[i] = SP_ACCEPT; b.node[i] = 0;
+  }
+  if (n == 0) return SP_OK;
+  // one batch of results is in flight at a time: the pinned buffer is free once every request of the
+  // previous batch has been taken in
+  for (size_t q = 0; q < s->reqs.size(); ++q) if (s->reqs[q].active && s->reqs[q].unrec) reconcile(s, (int)q);
+  hipError_t e;
+  if (!s->pin_nodes) {
+    if ((e = hipHostMalloc((void**)&s->pin_nodes, sizeof(int) * 2 * SP_MAX_BATCH_REQ, hipHostMallocDefault)) != hipSuccess)
+      return hip_fail(s, e);
+    if ((e = hipEventCreateWithFlags(&s->rec_ev, hipEventDisableTiming)) != hipSuccess) return hip_fail(s, e);
+  }
+  hipStream_t st = (hipStream_t)stream;
+  { ProfScope scope(s, SP_K_TREE_PRUNE, st);
+    if ((e = sp_launch_tree_prune(s->d_meta, s->d_tables, b, nodes_dev, stride, st)) != hipSuccess) return hip_fail(s, e); }
+  { ProfScope scope(s, SP_K_KV_COMPACT, st);
+    const size_t rb = (size_t)s->cfg.d_model * elt_bytes(s->cfg.dtype);
+    if ((e = sp_launch_kv_compact(s->d_meta, s->d_tables, b, s->geom, nullptr, rb, (int)rb, nullptr, st)) != hipSuccess)
+      return hip_fail(s, e); }
+  if ((e = hipMemcpyAsync(s->pin_nodes, nodes_dev, sizeof(int) * (size_t)n * stride, hipMemcpyDeviceToHost, st)) != hipSuccess ||
+      (e = hipEventRecord(s->rec_ev, st)) != hipSuccess)
+    return hip_fail(s, e);
+  for (int i = 0; i < n; ++i) {
+    HostReq& r = s->reqs[req_ids[i]];
+    r.unrec = true;
+    r.unrec_slot = i * stride;
+  }
+  return SP_OK;
 }
 
 // rows / list (nullable, one request only): hidden rows compacted by the same launch as the cache

@@ -30,7 +30,10 @@ hipError_t sp_launch_request_init(ReqMeta* meta, ReqTables* tables, int req, lon
                                   hipStream_t st);
 // first_slot: cache slot of the first new node (host mirror: base + prefix_len + n_live)
 hipError_t sp_launch_tree_insert(ReqMeta* meta, ReqTables* tables, const InsertArgs& a, KvGeom g, hipStream_t st);
-hipError_t sp_launch_tree_prune(ReqMeta* meta, ReqTables* tables, const PruneBatch& b, hipStream_t st);
+// dev_nodes (nullable, device): item i accepts node dev_nodes[i * dev_stride] if it is a live node and clears
+// the tree otherwise; the modes and nodes of `b` are then ignored (entries with mode < 0 are still skipped)
+hipError_t sp_launch_tree_prune(ReqMeta* meta, ReqTables* tables, const PruneBatch& b, const int* dev_nodes,
+                                int dev_stride, hipStream_t st);
 hipError_t sp_launch_pages_set(int* page_table, int pt_stride, int req, int first, int n, const int* pages /*host*/,
                                hipStream_t st);
 // out[i] (device) = verified root child of request reqs[i], or -1

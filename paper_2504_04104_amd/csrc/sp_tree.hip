@@ -96,15 +96,23 @@ __global__ void __launch_bounds__(SP_T) k_tree_insert(ReqMeta* meta, ReqTables* 
 
 // Prune flags from the mask column, wave-level prefix sums (ballot + popcount,
 // wave64), compacted tables written in place, and the old->new map for the cache.
-__global__ void __launch_bounds__(SP_T) k_tree_prune(ReqMeta* meta, ReqTables* tables, PruneBatch b) {
+// dev_nodes (nullable): the verified node of every item, left on the device by the match or the lossy
+// verification kernel: node >= 0 is accepted, anything else clears the tree (a stall).
+__global__ void __launch_bounds__(SP_T) k_tree_prune(ReqMeta* meta, ReqTables* tables, PruneBatch b,
+                                                      const int* dev_nodes, int dev_stride) {
   const int item = blockIdx.x;
-  const int mode = b.mode[item];
+  int mode = b.mode[item];
   if (mode < 0) return;
   const int req = b.req[item];
-  const int r = mode == 2 ? 0 : b.node[item];        // mode 2 (clear) names no node
   ReqTables& t = tables[req];
   const int T = meta[req].T;
   const int P = meta[req].P;
+  int node = b.node[item];
+  if (dev_nodes != nullptr) {
+    node = dev_nodes[(size_t)item * dev_stride];
+    mode = (node >= 0 && node < T) ? 0 : 2;
+  }
+  const int r = mode == 2 ? 0 : node;                // mode 2 (clear) names no node
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
 
   __shared__ unsigned long long s_tab[SP_W], s_kv[SP_W], s_path[SP_W];
@@ -463,8 +471,9 @@ hipError_t sp_launch_pages_set(int* page_table, int pt_stride, int req, int firs
   return hipSuccess;
 }
 
-hipError_t sp_launch_tree_prune(ReqMeta* meta, ReqTables* tables, const PruneBatch& b, hipStream_t st) {
-  hipLaunchKernelGGL(k_tree_prune, dim3(b.n), dim3(SP_T), 0, st, meta, tables, b);
+hipError_t sp_launch_tree_prune(ReqMeta* meta, ReqTables* tables, const PruneBatch& b, const int* dev_nodes,
+                                int dev_stride, hipStream_t st) {
+  hipLaunchKernelGGL(k_tree_prune, dim3(b.n), dim3(SP_T), 0, st, meta, tables, b, dev_nodes, dev_stride);
   return hipGetLastError();
 }
 static RowsJob rows_job(void* rows, size_t row_stride_bytes, int row_bytes) {

@@ -336,6 +336,15 @@ def run_verify(args):
         stage.tree_prune(0, sp.SP_ACCEPT, node)
         stage.kv_compact(0, y, rn)
     t = timed(step, 20)
+
+    def step_device_handover():
+        stage.request_init(0, 0, cap, P)
+        stage.set_root_pred(0, tokens[roots[0]])
+        stage.tree_insert(0, par, tokens)
+        stage.stage_forward([0], [0], [n], x, y)
+        stage.verify_head(head, [0], [0], [n], y)
+        stage.tree_prune_verified([0], stage.tree_match_dev([0]))     # prune + compaction read the node on the device
+    t_dev = timed(step_device_handover, 20)
     stage.request_init(0, 0, cap, P)
     stage.tree_insert(0, par, tokens)
     stage.stage_forward([0], [0], [n], x, y)
@@ -356,6 +365,7 @@ def run_verify(args):
     hbytes = V * sh.d_model * 2
     res = {"run": "verify", "workload": "last stage of the 8B shape: 4 layers + output head, vocab 128256, 64 nodes",
            "ms_per_step": round(t * 1e3, 3), "tree_tokens_per_s": round(n / t, 1),
+           "ms_per_step_device_handover": round(t_dev * 1e3, 3),
            "expand_call_us_with_host_copy": round(t_expand * 1e6, 1),
            "lossy_relaxed_call_us_with_host_wait": round(t_relaxed * 1e6, 1),
            "lossy_top_p_call_us_with_host_wait": round(t_top_p * 1e6, 1),

@@ -352,5 +352,27 @@ class Pair:
             return got, ref
         return None
 
+    def prune_verified(self, reqs: Sequence[int], nodes_dev: torch.Tensor, want_nodes: Sequence[int], stride: int = 1):
+        """sp_tree_prune_verified (prune + compaction decided on the device from nodes_dev) against the
+        oracle's accept / clear of want_nodes: same checks as prune(), the cache compared bit for bit."""
+        before = {}
+        for r in reqs:
+            st = self.ora.req[r]
+            before[r] = (st.P, self.tree_region(r, st.P, st.tree.n - 1), self.rows(r, 0, st.P))
+        self.gpu.tree_prune_verified(reqs, nodes_dev, stride)
+        for r, node in zip(reqs, want_nodes):
+            st = self.ora.req[r]
+            pr = self.ora.accept(r, node) if node >= 0 else self.ora.clear(r)
+            P_old, reg, ctx = before[r]
+            keep = pr.kv_keep[1:]
+            sel = torch.from_numpy(np.nonzero(keep)[0]).to(reg.device)
+            after = self.tree_region(r, P_old, int(keep.sum()))
+            assert torch.equal(after.view(torch.uint8), reg.index_select(3, sel).contiguous().view(torch.uint8))
+            assert torch.equal(self.rows(r, 0, P_old).contiguous().view(torch.uint8), ctx.contiguous().view(torch.uint8))
+            self.check_tables(r)                         # also the host mirror: prefix_len and n_live
+            if self.page_slots:
+                live_slots = st.P + st.tree.n - 1
+                assert len(self.gpu.request_pages(r)) == -(-live_slots // self.page_slots)
+
     def close(self):
         self.gpu.close()

@@ -511,15 +511,19 @@ def test_verify_head_many_rows_and_order_error():
     pair.close()
 
 
+@pytest.mark.parametrize("handover", ["host", "device"])
 @pytest.mark.parametrize("shape,flags,tol", [(MINI_F32, 0, "f32"), (MINI_BF16, sp.SP_FLAG_PACKED_WEIGHTS, "bf16")],
                          ids=["f32", "bf16_packed"])
-def test_verified_decoding_loop(shape, flags, tol):
+def test_verified_decoding_loop(shape, flags, tol, handover):
     """Insert a level, forward, predict, match the root's successor, accept or stall -- the loop of
     Algorithm 1 with the stage as the whole model -- on the GPU and on the oracle side by side.  The
     guesses hold the right token about two times in three, so hits, misses (SP_CLEAR + the true token
-    as a level of its own) and the hand-over of the accepted node's prediction to the root all occur."""
+    as a level of its own) and the hand-over of the accepted node's prediction to the root all occur.
+    handover "device": the verified node never visits the host before the prune: sp_tree_prune_verified reads
+    it from the match kernel's output (accept, or clear on a miss) and compacts the cache in the same call;
+    the host's view of the request catches up afterwards."""
     V = 128
-    pair = Pair(shape, 24, {0: 12}, tree_room=300, vocab=V)
+    pair = Pair(shape, 24, {0: 12}, tree_room=300, vocab=V, page_slots=32 if handover == "device" and tol == "bf16" else 0)
     emb = wl.embedding_table(shape, 24, V)
     rs = np.random.RandomState(24)
     pair.gpu.set_root_pred(0, 17)
@@ -551,16 +555,24 @@ def test_verified_decoding_loop(shape, flags, tol):
         assert rel_err(to_np(y) - x, ref - x) <= 4 * TOL[tol], step            # the layers' own contribution (y is rounded to the storage type)
         pair.verify_head([0], [first], [len(tokens)], y, TOL[tol])
         pair.check_tables(0)
-        node = pair.gpu.tree_match([0])[0]
-        assert node == pair.ora.match(0)
         want = int(pair.ora.req[0].pred[0])
         emitted.append(want)
+        if handover == "device":
+            node = pair.ora.match(0)
+            nodes_dev = pair.gpu.tree_match_dev([0])
+            pair.prune_verified([0], nodes_dev, [node])              # no host read between match and prune
+            assert int(nodes_dev[0]) == node
+        else:
+            node = pair.gpu.tree_match([0])[0]
+            assert node == pair.ora.match(0)
+            if node >= 0:
+                pair.prune(0, sp.SP_ACCEPT, node)
+            else:
+                pair.prune(0, sp.SP_CLEAR, 0)
         if node >= 0:
             hits += 1
-            pair.prune(0, sp.SP_ACCEPT, node)
         else:
             misses += 1
-            pair.prune(0, sp.SP_CLEAR, 0)
             k = pair.insert(0, [-1], [want])
             y1 = pair.gpu.stage_forward([0], [k], [1], to_dev(emb[[want]], pair.gpu))
             assert rel_err(to_np(y1), pair.ora.stage_forward(0, k, emb[[want]])) <= TOL[tol], step
@@ -625,6 +637,14 @@ def test_lossy_verification(shape, flags, tol, V):
     # a single request out of the three, in another order of arguments
     one, _ = pair.verify_lossy([1], x_root[1:2].contiguous(), "top_p", 0.93, TOL_LOGIT[tol])
     assert one[0] == results[("top_p", 0.93)][1]
+    # device-side hand-over: the (node, top-1) pairs stay on the device and the prune reads them with stride 2;
+    # request 1 accepts its relaxed choice, request 2 (no children) clears an empty tree
+    n1 = pair.gpu.request_info(1)[1]
+    pair.forward([1], [0], [n1], wl.hidden_rows(shape, 31, ("fw1",), n1))          # the accepted path's K/V rows exist
+    res_dev = pair.gpu.verify_lossy_dev(pair.head, [1, 2], x_root[1:3].contiguous(), sp.SP_VERIFY_RELAXED, 1.0)
+    want1 = results[("relaxed", 1.0)][1][0]
+    pair.prune_verified([1, 2], res_dev, [want1, -1], stride=2)
+    assert res_dev.tolist() == [want1, int(order[1, 0]), -1, int(order[2, 0])]
     with pytest.raises(sp.SpError):
         pair.gpu.verify_lossy(pair.head, [0], x_root[:1].contiguous(), sp.SP_VERIFY_TOP_P, 0.0)
     with pytest.raises(sp.SpError):
