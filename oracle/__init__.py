@@ -17,18 +17,20 @@ decoder layer run sequentially along every root-to-leaf path, torch SDPA with
 an explicit mask, RoPE's relative-position identity, the closed forms of
 the paper's memory table, and for verification Hugging Face's RMSNorm + a
 torch Linear and the lossless property (tree-speculative decoding emits the
-sequence of plain greedy decoding).  No function here is "parity unpinned".
+sequence of plain greedy decoding); for stochastic verification Hugging Face's temperature /
+top-k / top-p warpers, the measure of the uniform numbers that draw each candidate, and the limits
+that reduce the draw to the arg-max.  No function here is "parity unpinned".
 """
 from .tree import SpecTree
 from .stage import (StageOracle, RequestState, rmsnorm, rope_rotate, silu, tree_attention,
                     decoder_layer)
 from .prune import (accept_masks, drop_masks, compact_rows, PruneResult)
 from .verify import (lm_head_logits, greedy_token, greedy_token_fast, match_root_child, softmax_probs, top_p_set,
-                     relaxed_choice, top_p_choice)
+                     relaxed_choice, top_p_choice, sampling_candidates, sample_token)
 
 __all__ = [
     "SpecTree", "StageOracle", "RequestState", "rmsnorm", "rope_rotate", "silu",
     "tree_attention", "decoder_layer", "accept_masks", "drop_masks", "compact_rows",
     "PruneResult", "lm_head_logits", "greedy_token", "greedy_token_fast", "match_root_child",
-    "softmax_probs", "top_p_set", "relaxed_choice", "top_p_choice",
+    "softmax_probs", "top_p_set", "relaxed_choice", "top_p_choice", "sampling_candidates", "sample_token",
 ]

@@ -120,3 +120,46 @@ def top_p_choice(logits: np.ndarray, parent: Sequence[int], token: Sequence[int]
         if best == -1 or q > best_q:
             best, best_q = k, q
     return best
+
+
+# ----------------------------------------------------------------------------
+# Stochastic decoding at the verifier (Sec. 4.3, "Stochastic Decoding")
+# ----------------------------------------------------------------------------
+# The large model's next token is drawn instead of taken as the arg-max: temperature T, and
+# candidates are collected in descending probability until their probabilities sum to top_p or
+# top_k of them have been taken, whichever comes first (the paper's setting: T = 0.6, 0.9, 80).
+# The drawn token then plays the part of the top-1 token: the step verifies the root child that
+# carries it, or stalls.  Readings where the paper is silent: probabilities are those of
+# softmax(logits / T) over the whole vocabulary (the running sum is measured against the full
+# distribution, not against the top_k tokens' share of it); equal probabilities are ordered by
+# ascending token id; the draw is the inverse CDF of the candidates' renormalised probabilities
+# at a uniform number u in [0, 1) that the caller supplies: candidate j is drawn iff
+# C_(j-1) <= u * C_m < C_j, C the running sums in candidate order and C_m their total.
+# Pins (tests/test_oracle_sampling.py): Hugging Face's temperature / top-k / top-p warpers for the
+# candidate set in the cases where the two cuts do not interact; the measure of u that draws each
+# candidate equals its renormalised probability; T -> 0, top_k = 1 and top_p -> 0 all reduce to
+# the arg-max; the candidates are a prefix of the descending order, by exhaustive check.
+def sampling_candidates(logits: np.ndarray, temperature: float, top_p: float, top_k: int):
+    """(tokens, probabilities under softmax(logits / T), most probable first) the stochastic decoder may emit."""
+    z = np.asarray(logits, F64) / F64(temperature)
+    probs = softmax_probs(z)
+    order = sorted(range(len(probs)), key=lambda v: (-probs[v], v))
+    toks, ps, run = [], [], 0.0
+    for v in order:
+        toks.append(v)
+        ps.append(probs[v])
+        run += probs[v]
+        if run >= top_p or len(toks) >= top_k:
+            break
+    return toks, np.asarray(ps, F64)
+
+
+def sample_token(logits: np.ndarray, temperature: float, top_p: float, top_k: int, u: float) -> int:
+    """The token drawn at uniform number u in [0, 1)."""
+    toks, ps = sampling_candidates(logits, temperature, top_p, top_k)
+    run = np.cumsum(ps)
+    x = F64(u) * run[-1]
+    for j, t in enumerate(toks):
+        if x < run[j]:
+            return int(t)
+    return int(toks[-1])          # u * total rounded up to the total itself
