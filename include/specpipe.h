@@ -389,6 +389,25 @@ int sp_stage_verify_lossy(sp_stage* stage, const sp_head_weights* head, int32_t 
                           const void* x_root /*device*/, int32_t mode, float top_p, int32_t* result_dev /*device*/,
                           int32_t* result_host /*host, nullable*/, sp_stream stream);
 
+/* Stochastic verification (Sec. 4.3, "Stochastic Decoding": temperature 0.6, candidates collected until
+ * their probabilities reach 0.9 or 80 have been taken).  x_root as for sp_stage_verify_lossy.  The token
+ * after the root of req_ids[i] is drawn from softmax(RMSNorm(x_root[i]) W_vocab^T / temperature): candidates
+ * in descending probability (equal ones by ascending id) up to and including the one at which the running
+ * sum reaches top_p, at most top_k (<= SP_MAX_SAMPLE_TOP_K) of them; with C_j the running sums over the
+ * m candidates, candidate j is drawn iff C_(j-1) <= u[i] * C_m < C_j, u[i] in [0, 1) supplied by the caller
+ * (host array: the library draws no random numbers).  The drawn token takes the place of the top-1 token:
+ * result_dev[2i] = the first child of the root that carries it, -1 if none does (a stall, continue as in the
+ * lossless flow), result_dev[2i+1] = the token, which is also stored as the root's prediction.
+ * Probabilities and running sums are float32; a draw within rounding of a boundary may fall on either side.
+ * Errors: SP_E_INVALID (temperature <= 0, top_p outside (0, 1], top_k outside [1, SP_MAX_SAMPLE_TOP_K], u
+ * outside [0, 1), repeated request), SP_E_BAD_REQ, SP_E_PENDING, SP_E_CAPACITY (n rows of logits exceed the
+ * workspace). */
+#define SP_MAX_SAMPLE_TOP_K 128
+int sp_stage_verify_sample(sp_stage* stage, const sp_head_weights* head, int32_t n, const int32_t* req_ids /*host*/,
+                           const void* x_root /*device*/, float temperature, float top_p, int32_t top_k,
+                           const float* u /*host, n*/, int32_t* result_dev /*device, 2n*/,
+                           int32_t* result_host /*host, nullable*/, sp_stream stream);
+
 /* ---- inspection ------------------------------------------------------------- */
 
 /* Copies a request's device tables to the host.  Waits for `stream`. */

@@ -101,6 +101,8 @@ def load_library(path: Optional[str] = None) -> C.CDLL:
         "sp_stage_verify_head_noalloc": [vp, C.POINTER(sp_head_weights), C.c_int32, i32p, i32p, i32p, vp, vp, vp, vp],
         "sp_stage_verify_lossy": [vp, C.POINTER(sp_head_weights), C.c_int32, i32p, vp, C.c_int32, C.c_float, vp,
                                   i32p, vp],
+        "sp_stage_verify_sample": [vp, C.POINTER(sp_head_weights), C.c_int32, i32p, vp, C.c_float, C.c_float, C.c_int32,
+                                   f32p, vp, i32p, vp],
         "sp_request_set_root_pred": [vp, C.c_int32, C.c_int32, vp],
         "sp_tree_match": [vp, C.c_int32, i32p, vp, i32p, vp],
         "sp_tree_expand": [vp, C.c_int32, C.c_int32, i32p, C.c_int32, vp, vp, C.c_int32, vp, vp, vp, vp, vp],
@@ -405,6 +407,23 @@ class Stage:
                                               float(top_p), dev.data_ptr(),
                                               C.cast(host.data_ptr(), C.POINTER(C.c_int32)), self._stream()),
                "sp_stage_verify_lossy")
+        torch.cuda.current_stream(self.device).synchronize()
+        return [(int(host[2 * i]), int(host[2 * i + 1])) for i in range(n)]
+
+    def verify_sample(self, head: Dict[str, "object"], req_ids: Sequence[int], x_root, temperature: float, top_p: float,
+                      top_k: int, u: Sequence[float]) -> List[tuple]:
+        """sp_stage_verify_sample: [(verified node or -1, drawn token)] per request; waits for the stream."""
+        import torch
+        ra, rp = _i32(req_ids)
+        n = len(ra)
+        ua = np.ascontiguousarray(np.asarray(u, dtype=np.float32))
+        dev = torch.empty(max(2 * n, 2), dtype=torch.int32, device=self.device)
+        host = torch.empty(max(2 * n, 2), dtype=torch.int32, pin_memory=True)
+        h = sp_head_weights(head["norm"].data_ptr(), head["wvocab"].data_ptr(), int(head["wvocab"].shape[0]), 0)
+        _check(self.lib.sp_stage_verify_sample(self.handle, C.byref(h), n, rp, x_root.data_ptr(), float(temperature),
+                                               float(top_p), int(top_k), ua.ctypes.data_as(C.POINTER(C.c_float)),
+                                               dev.data_ptr(), C.cast(host.data_ptr(), C.POINTER(C.c_int32)),
+                                               self._stream()), "sp_stage_verify_sample")
         torch.cuda.current_stream(self.device).synchronize()
         return [(int(host[2 * i]), int(host[2 * i + 1])) for i in range(n)]
 

@@ -14,6 +14,7 @@
 static_assert(SP_T == SP_MAX_TREE_NODES, "tree capacity");
 static_assert(SP_W == SP_ANC_WORDS, "mask words");
 static_assert(SP_BATCH == SP_MAX_BATCH_REQ, "batch capacity");
+static_assert(SP_SAMPLE_MAX_K == SP_MAX_SAMPLE_TOP_K, "candidates of a stochastic verification");
 
 namespace {
 
@@ -1111,6 +1112,47 @@ int sp_stage_verify_lossy(sp_stage* s, const sp_head_weights* head, int32_t n, c
   if (e == hipSuccess)
     e = sp_launch_verify_lossy(s->d_meta, s->d_tables, w.part, n, req_ids, V, mode, top_p, w.part + logit_floats,
                                result_dev, st);
+  if (e == hipSuccess && result_host)
+    e = hipMemcpyAsync(result_host, result_dev, sizeof(int32_t) * 2 * n, hipMemcpyDeviceToHost, st);
+  return e == hipSuccess ? SP_OK : hip_fail(s, e);
+}
+
+int sp_stage_verify_sample(sp_stage* s, const sp_head_weights* head, int32_t n, const int32_t* req_ids,
+                           const void* x_root, float temperature, float top_p, int32_t top_k, const float* u,
+                           int32_t* result_dev, int32_t* result_host, sp_stream stream) {
+  if (!s || !head || !req_ids || !result_dev || !u) return SP_E_INVALID;
+  if (!head->norm || !head->wvocab || head->vocab < 1) return SP_E_INVALID;
+  if (!(temperature > 0.f) || !(top_p > 0.f && top_p <= 1.f)) return SP_E_INVALID;      // also rejects NaN
+  if (top_k < 1 || top_k > SP_MAX_SAMPLE_TOP_K) return SP_E_INVALID;
+  const sp_config& c = s->cfg;
+  if (n < 0 || n > SP_MAX_BATCH_REQ || n > c.max_batch_nodes) return SP_E_CAPACITY;
+  for (int i = 0; i < n; ++i) {
+    HostReq* r = get_req(s, req_ids[i]);
+    if (!r) return SP_E_BAD_REQ;
+    if (r->pending) return SP_E_PENDING;
+    if (!(u[i] >= 0.f && u[i] < 1.f)) return SP_E_INVALID;
+    for (int j = 0; j < i; ++j) if (req_ids[j] == req_ids[i]) return SP_E_INVALID;
+  }
+  if (n == 0) return SP_OK;
+  if (!x_root) return SP_E_INVALID;
+  const int d = c.d_model, V = head->vocab;
+  if (V >= (1 << 16) * 1024) return SP_E_UNSUPPORTED;                  // the gather counts 16 bits per thread
+  Workspace& w = s->ws;
+  const size_t logit_floats = (size_t)n * V;
+  if (logit_floats > w.part_floats) return SP_E_CAPACITY;
+  hipStream_t st = (hipStream_t)stream;
+  hipError_t e = sp_launch_row_norm(c.dtype, x_root, head->norm, w.xn, n, d, c.rms_eps, st);
+  if (e != hipSuccess) return hip_fail(s, e);
+  ProfScope p(s, SP_K_VERIFY_HEAD, st);
+  if (s->fast && V % 64 == 0 && d % 128 == 0) {
+    int S = 1;
+    e = sp_launch_gemm_bf16((const bf16_t*)w.xn, (const bf16_t*)head->wvocab, s->packed, w.part, n, V, d, 1,
+                            logit_floats, &S, st);
+  } else {
+    e = sp_launch_gemm_simple(c.dtype, w.xn, head->wvocab, w.part, n, V, d, st);
+  }
+  if (e == hipSuccess)
+    e = sp_launch_verify_sample(s->d_meta, s->d_tables, w.part, n, req_ids, V, temperature, top_p, top_k, u, result_dev, st);
   if (e == hipSuccess && result_host)
     e = hipMemcpyAsync(result_host, result_dev, sizeof(int32_t) * 2 * n, hipMemcpyDeviceToHost, st);
   return e == hipSuccess ? SP_OK : hip_fail(s, e);

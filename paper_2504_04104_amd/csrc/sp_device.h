@@ -88,6 +88,7 @@ struct PruneBatch {
   int node[SP_BATCH];
 };
 
+#define SP_SAMPLE_MAX_K 128  // most candidates of a stochastic verification (== SP_MAX_SAMPLE_TOP_K)
 #define SP_EXPAND_MAX 4096   // candidates of one fixed-width expansion (bottom tokens x k)
 
 struct ExpandArgs {      // by value

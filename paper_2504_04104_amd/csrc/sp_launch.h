@@ -53,6 +53,10 @@ size_t sp_lossy_scratch_floats(int n, int V);
 // mode 1 relaxed, 2 top-p; logits [n][V]; out[2i] = verified node of reqs[i] or -1, out[2i+1] = top-1 token
 hipError_t sp_launch_verify_lossy(ReqMeta* meta, const ReqTables* tables, const float* logits, int n, const int* reqs,
                                   int V, int mode, float top_p, float* scratch, int* out, hipStream_t st);
+// stochastic verification: out[2i] = verified node of reqs[i] or -1, out[2i+1] = the token drawn at u[i]
+hipError_t sp_launch_verify_sample(ReqMeta* meta, const ReqTables* tables, const float* logits, int n, const int* reqs,
+                                   int V, float temperature, float top_p, int top_k, const float* u /*host*/, int* out,
+                                   hipStream_t st);
 hipError_t sp_launch_kv_compact(const ReqMeta* meta, const ReqTables* tables, const PruneBatch& b, KvGeom g,
                                 void* rows /*nullable: hidden rows of the one request, same launch*/,
                                 size_t row_stride_bytes, int row_bytes, const RowList* l, hipStream_t st);

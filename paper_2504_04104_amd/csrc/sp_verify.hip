@@ -247,6 +247,181 @@ __global__ void __launch_bounds__(256) k_lossy_decide(ReqMeta* meta, const ReqTa
   }
 }
 
+// ---------------------------------------------------------------------------------------------
+// Stochastic verification (Sec. 4.3, "Stochastic Decoding"): the token after the root is drawn from
+// the large model's distribution at temperature T, among the candidates collected in descending
+// probability until their probabilities sum to top_p or top_k of them have been taken (equal
+// probabilities by ascending token id); the draw is the inverse CDF of the candidates' renormalised
+// probabilities at a uniform number the caller supplies.  The drawn token takes the place of the
+// top-1 token: it becomes the root's prediction, and the verified node is the first root child that
+// carries it (-1: a stall).
+// One workgroup of 1024 threads per request: row maximum, normaliser over the whole vocabulary, the
+// top_k-th largest logit by a radix select over the order-preserving bit pattern (four passes of 8
+// bits, one histogram per wave), an index-ordered gather of the logits above it and of the first
+// ones equal to it, a sort by counting, and the running sums by one thread.
+struct SampleBatch {
+  int n, V, top_k;
+  float inv_T, top_p;
+  int req[SP_BATCH];
+  float u[SP_BATCH];
+};
+
+__device__ __forceinline__ uint32_t order_key(float f) {           // ascending like the floats themselves
+  const uint32_t b = __float_as_uint(f);
+  return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
+}
+__device__ __forceinline__ float key_value(uint32_t k) {
+  return __uint_as_float((k & 0x80000000u) ? (k & 0x7fffffffu) : ~k);
+}
+
+__global__ void __launch_bounds__(1024) k_sample_decide(ReqMeta* meta, const ReqTables* tables,
+                                                         const float* __restrict__ logits, SampleBatch b, int* out) {
+  __shared__ float s_f[16];
+  __shared__ unsigned s_hist[16][256];
+  __shared__ unsigned s_scan[16];
+  __shared__ unsigned s_pick[2];                  // digit chosen by a pass, and how many of the top_k are still to find below it
+  __shared__ uint32_t s_key[SP_SAMPLE_MAX_K], s_skey[SP_SAMPLE_MAX_K];
+  __shared__ int s_idx[SP_SAMPLE_MAX_K], s_sidx[SP_SAMPLE_MAX_K];
+  __shared__ int s_tok, s_best;
+  const int item = blockIdx.x, req = b.req[item];
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const float* L = logits + (size_t)item * b.V;
+  const int V = b.V, K = min(b.top_k, V);
+
+  // row maximum
+  float mx = -INFINITY;
+  for (int i = tid; i < V; i += 1024) mx = fmaxf(mx, L[i]);
+  mx = wave_max(mx);
+  if (lane == 0) s_f[wave] = mx;
+  __syncthreads();
+  mx = s_f[0];
+#pragma unroll
+  for (int w = 1; w < 16; ++w) mx = fmaxf(mx, s_f[w]);
+  __syncthreads();
+  // normaliser of softmax(l / T) over the whole vocabulary, added in a fixed order
+  float z = 0.f;
+  for (int i = tid; i < V; i += 1024) z += expf((L[i] - mx) * b.inv_T);
+  z = wave_sum(z);
+  if (lane == 0) s_f[wave] = z;
+  __syncthreads();
+  float Z = 0.f;
+#pragma unroll
+  for (int w = 0; w < 16; ++w) Z += s_f[w];
+
+  // the K-th largest key: fix its bytes from the top, counting the keys that share the bytes fixed so far
+  uint32_t prefix = 0u, mask = 0u;
+  unsigned need = (unsigned)K;
+  for (int shift = 24; shift >= 0; shift -= 8) {
+    for (int i = tid; i < 16 * 256; i += 1024) (&s_hist[0][0])[i] = 0u;
+    __syncthreads();
+    for (int i = tid; i < V; i += 1024) {
+      const uint32_t k = order_key(L[i]);
+      if ((k & mask) == prefix) atomicAdd(&s_hist[wave][(k >> shift) & 255u], 1u);
+    }
+    __syncthreads();
+    if (tid < 256) {
+      unsigned c = 0u;
+#pragma unroll
+      for (int w = 0; w < 16; ++w) c += s_hist[w][tid];
+      s_hist[0][tid] = c;
+    }
+    __syncthreads();
+    if (tid == 0) {
+      unsigned above = 0u;
+      int bin = 255;
+      for (; bin > 0; --bin) {
+        if (above + s_hist[0][bin] >= need) break;
+        above += s_hist[0][bin];
+      }
+      s_pick[0] = (unsigned)bin;
+      s_pick[1] = need - above;
+    }
+    __syncthreads();
+    prefix |= s_pick[0] << shift;
+    mask |= 255u << shift;
+    need = s_pick[1];
+    __syncthreads();
+  }
+  const uint32_t kth = prefix;                    // `need` of the keys equal to it belong to the top K: those with the lowest index
+  const int n_gt = K - (int)need;
+
+  // gather in index order: thread t owns the indices [t * chunk, (t + 1) * chunk)
+  const int chunk = (V + 1023) / 1024;
+  const int i0 = min(tid * chunk, V), i1 = min(i0 + chunk, V);
+  unsigned c_gt = 0u, c_eq = 0u;
+  for (int i = i0; i < i1; ++i) {
+    const uint32_t k = order_key(L[i]);
+    c_gt += k > kth;
+    c_eq += k == kth;
+  }
+  // exclusive prefix sums over the threads (both counts in one word: a chunk holds fewer than 65536 indices)
+  unsigned mine = (c_gt << 16) | c_eq, incl = mine;
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    const unsigned v = __shfl_up(incl, o, 64);
+    if (lane >= o) incl += v;
+  }
+  if (lane == 63) s_scan[wave] = incl;
+  __syncthreads();
+  unsigned base = 0u;
+  for (int w = 0; w < wave; ++w) base += s_scan[w];
+  const unsigned excl = base + incl - mine;
+  int p_gt = (int)(excl >> 16), p_eq = (int)(excl & 0xffffu);
+  for (int i = i0; i < i1; ++i) {
+    const uint32_t k = order_key(L[i]);
+    if (k > kth) { s_key[p_gt] = k; s_idx[p_gt] = i; ++p_gt; }
+    else if (k == kth) { if (p_eq < (int)need) { s_key[n_gt + p_eq] = k; s_idx[n_gt + p_eq] = i; } ++p_eq; }
+  }
+  __syncthreads();
+  // descending probability, equal ones by ascending token id: a candidate's place is the number that beat it
+  if (tid < K) {
+    const uint32_t k = s_key[tid];
+    const int ix = s_idx[tid];
+    int rank = 0;
+    for (int j = 0; j < K; ++j) rank += (s_key[j] > k) || (s_key[j] == k && s_idx[j] < ix);
+    s_skey[rank] = k;
+    s_sidx[rank] = ix;
+  }
+  if (tid == 0) s_best = 0x7fffffff;
+  __syncthreads();
+  if (tid == 0) {
+    // running sums until top_p is reached (or the K candidates are used up); then the inverse CDF at u
+    float run = 0.f;
+    int m = 0;
+    float* cum = reinterpret_cast<float*>(&s_hist[1][0]);         // K floats, free by now
+    for (; m < K;) {
+      run += expf((key_value(s_skey[m]) - mx) * b.inv_T) / Z;
+      cum[m] = run;
+      ++m;
+      if (run >= b.top_p) break;
+    }
+    const float x = b.u[item] * run;
+    int j = 0;
+    while (j + 1 < m && !(x < cum[j])) ++j;
+    s_tok = s_sidx[j];
+  }
+  __syncthreads();
+  const int tok = s_tok;
+  const ReqTables& t = tables[req];
+  if (tid < meta[req].T && t.parent[tid] == -1 && t.token[tid] == tok) atomicMin(&s_best, tid);
+  __syncthreads();
+  if (tid == 0) {
+    out[2 * item] = s_best == 0x7fffffff ? -1 : s_best;
+    out[2 * item + 1] = tok;
+    meta[req].root_pred = tok;
+  }
+}
+
+hipError_t sp_launch_verify_sample(ReqMeta* meta, const ReqTables* tables, const float* logits, int n, const int* reqs,
+                                   int V, float temperature, float top_p, int top_k, const float* u, int* out,
+                                   hipStream_t st) {
+  SampleBatch b;
+  b.n = n; b.V = V; b.top_k = top_k; b.inv_T = 1.f / temperature; b.top_p = top_p;
+  for (int i = 0; i < n; ++i) { b.req[i] = reqs[i]; b.u[i] = u[i]; }
+  hipLaunchKernelGGL(k_sample_decide, dim3(n), dim3(1024), 0, st, meta, tables, logits, b, out);
+  return hipGetLastError();
+}
+
 hipError_t sp_launch_row_norm(int dtype, const void* x, const void* gain, void* xn, int M, int d, float eps,
                               hipStream_t st) {
   if (dtype == 0)

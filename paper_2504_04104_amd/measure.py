@@ -7,6 +7,7 @@
     python -m paper_2504_04104_amd.measure --run c5           # 32 requests, ragged batch
     python -m paper_2504_04104_amd.measure --run compact      # batched prune + KV compaction, scaled
     python -m paper_2504_04104_amd.measure --run verify       # last stage: output head (vocab 128256) + match
+    python -m paper_2504_04104_amd.measure --run wide         # many-row projections at 512 / 574 / 1024 rows
 
 Each run prints one JSON line.  These runs only time the HIP path (parity is the tests' job), so
 weights are drawn on the GPU (seeded N(0, 0.02)) instead of through the host generators; trees,
@@ -302,6 +303,46 @@ def run_compact(args):
     stage.close()
 
 
+def run_wide(args):
+    """The many-row projection kernels on the 8B-shaped layer: forward calls of 512, 574 (the ragged cold
+    batch of config 5) and 1024 rows spread over requests with short contexts, each projection kind
+    bracketed by HIP events.  One layer; FLOP/s per projection against the dense bf16 matrix-core peak."""
+    w = wl.CONFIGS["C5"]
+    sh = wl.scaled(w.shape, n_layers=1)
+    layers = gpu_layers(sh, w.seed)
+    out = {}
+    for M in (512, 574, 1024):
+        if M == 574:
+            sizes = [len(r.parents) for r in wl.batch_requests(w.seed)]
+        else:
+            sizes = [256] * (M // 256)
+        assert sum(sizes) == M
+        R, P, cap = len(sizes), 64, 64 + 256 + 8
+        stage = sp.Stage(sh, layers, kv_slots=R * cap, max_requests=R, max_batch_nodes=M, flags=sp.SP_FLAG_PACKED_WEIGHTS)
+        fill_kv(stage, w.seed)
+        x = torch.randn(M, sh.d_model, device=DEV).to(torch.bfloat16)
+        y = torch.empty_like(x)
+        ids = list(range(R))
+        pars = [wl.tree_uniform_parents(w.seed, n, 12, name=("wide", r)) for r, n in enumerate(sizes)]
+
+        def step():
+            for r in ids:
+                stage.request_init(r, r * cap, cap, P)
+            stage.tree_insert_batch(ids, pars)
+            stage.stage_forward(ids, [0] * R, sizes, x, y)
+        step()
+        row = {}
+        for kind, name, N, K in ((B.K_GEMM_QKV, "qkv", sh.d_q + 2 * sh.d_kv, sh.d_model), (B.K_GEMM_O, "o", sh.d_model, sh.d_q),
+                                 (B.K_GEMM_GATEUP, "gateup", 2 * sh.d_ff, sh.d_model), (B.K_GEMM_DOWN, "down", sh.d_model, sh.d_ff)):
+            us, cnt = kernel_us(stage, step, kind)
+            us /= cnt
+            row[name] = {"us": round(us, 1), "TFLOPs": round(2.0 * M * N * K / us / 1e6, 1),
+                         "mfma_frac": round(2.0 * M * N * K / us / 1e6 / MFMA_PEAK, 4)}
+        out[M] = row
+        stage.close()
+    print(json.dumps({"run": "wide", "workload": "8B-shaped layer, many-row projections (k_gemm_wide)", "by_rows": out}))
+
+
 def run_verify(args):
     """Last-stage step on the 8B-shaped stage: forward of 64 nodes, output head over a vocabulary of
     128256 with the top-1 token per node, match of the root's successor, accept, compaction."""
@@ -362,6 +403,7 @@ def run_verify(args):
     xr = y[:1].contiguous()
     t_relaxed = timed(lambda: stage.verify_lossy(head, [0], xr, sp.SP_VERIFY_RELAXED, 1.0), 30)
     t_top_p = timed(lambda: stage.verify_lossy(head, [0], xr, sp.SP_VERIFY_TOP_P, 0.9), 30)
+    t_sample = timed(lambda: stage.verify_sample(head, [0], xr, 0.6, 0.9, 80, [0.37]), 30)
     hbytes = V * sh.d_model * 2
     res = {"run": "verify", "workload": "last stage of the 8B shape: 4 layers + output head, vocab 128256, 64 nodes",
            "ms_per_step": round(t * 1e3, 3), "tree_tokens_per_s": round(n / t, 1),
@@ -369,6 +411,7 @@ def run_verify(args):
            "expand_call_us_with_host_copy": round(t_expand * 1e6, 1),
            "lossy_relaxed_call_us_with_host_wait": round(t_relaxed * 1e6, 1),
            "lossy_top_p_call_us_with_host_wait": round(t_top_p * 1e6, 1),
+           "stochastic_T0.6_p0.9_k80_call_us_with_host_wait": round(t_sample * 1e6, 1),
            "head_call_us": round(t_head * 1e6, 1), "head_kernels_us": round(hd_us / cnt, 1),
            "head_weights_MB": round(hbytes / 1e6, 1),
            "head_GBps": round(hbytes / (hd_us / cnt * 1e-6) / 1e9, 1),
@@ -380,12 +423,12 @@ def run_verify(args):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--page-slots", type=int, default=0, help="c5: keep the cache in pages of this many slots")
-    ap.add_argument("--run", required=True, choices=["sweep", "c3", "c4", "c5", "compact", "verify"])
+    ap.add_argument("--run", required=True, choices=["sweep", "c3", "c4", "c5", "compact", "verify", "wide"])
     ap.add_argument("--steps", type=int, default=0)
     args = ap.parse_args()
     # a stream of our own: the forward call replays HIP graphs of its launches only on a stream that can be captured
     torch.cuda.set_stream(torch.cuda.Stream(device=DEV))
-    {"sweep": run_sweep, "c3": run_c3, "c4": run_c4, "c5": run_c5, "compact": run_compact, "verify": run_verify}[args.run](args)
+    {"sweep": run_sweep, "c3": run_c3, "c4": run_c4, "c5": run_c5, "compact": run_compact, "verify": run_verify, "wide": run_wide}[args.run](args)
 
 
 if __name__ == "__main__":

@@ -664,6 +664,88 @@ def test_lossy_verification(shape, flags, tol, V):
     pair.close()
 
 
+@pytest.mark.parametrize("shape,flags,tol,V", [(MINI_F32, 0, "f32", 97), (MINI_F32, 0, "f32", 5003),
+                                               (MINI_BF16, sp.SP_FLAG_PACKED_WEIGHTS, "bf16", 4160)],
+                         ids=["f32_v97", "f32_v5003", "bf16_packed_v4160"])
+def test_stochastic_verification(shape, flags, tol, V):
+    """Stochastic decoding at the verifier (Sec. 4.3): the token after the root is drawn at temperature T among
+    the candidates collected until their probabilities reach top_p or top_k have been taken; the uniform
+    numbers are inputs.  The GPU forms probabilities in float32 from its own logits, the oracle in float64,
+    so a draw is compared exactly unless the uniform number lies within a margin of an interval boundary
+    (or the cut itself is within the margin of top_p), where the neighbouring outcome is accepted too."""
+    from oracle.verify import lm_head_logits, sampling_candidates, sample_token, match_root_child
+    pair = Pair(shape, 35, {0: 20, 1: 33, 2: 9}, vocab=V, head_gain=8.0)
+    rs = np.random.RandomState(35)
+    x_np = wl.hidden_rows(shape, 35, ("root",), 3)
+    x_root = to_dev(x_np, pair.gpu)
+    logits = lm_head_logits(x_np.astype(np.float64), pair.head_np["norm"], pair.head_np["wvocab"], shape.rms_eps)
+    order = np.argsort(-logits, axis=1, kind="stable")
+    # root children: the most likely tokens (one twice), a token outside the vocabulary; deeper nodes must not count
+    for r, n_root in ((0, 6), (1, 9)):
+        toks = [int(t) for t in order[r, :n_root - 2]] + [int(order[r, 1]), V + 3]
+        rs.shuffle(toks)
+        pair.insert(r, [-1] * n_root + [0, 1], toks + [int(order[r, 0])] * 2)
+    eps_logit = TOL_LOGIT[tol] * float(np.max(np.abs(logits)))
+    n_checked = n_marginal = 0
+    for T, p, k in ((0.6, 0.9, 80), (1.0, 0.5, 8), (0.3, 0.99, 128), (1.5, 1.0, 5), (0.6, 0.9, 1)):
+        slack = 6.0 * eps_logit / T + 2e-6
+        cands = [sampling_candidates(logits[r], T, p, k) for r in range(3)]
+        us = []
+        # centres of the three widest intervals, then uniform numbers anywhere
+        for which in range(3):
+            row = []
+            for r in range(3):
+                toks, ps = cands[r]
+                c = np.concatenate(([0.0], np.cumsum(ps))) / ps.sum()
+                j = int(np.argsort(-ps, kind="stable")[min(which, len(ps) - 1)])
+                row.append(0.5 * (c[j] + c[j + 1]))
+            us.append(row)
+        us += [[float(v) for v in rs.uniform(0.0, 1.0, 3)] for _ in range(12)] + [[0.0, 0.0, 0.0]]
+        for u in us:
+            u32 = [float(np.float32(min(v, 0.9999999))) for v in u]
+            got = pair.gpu.verify_sample(pair.head, [0, 1, 2], x_root, T, p, k, u32)
+            for r in range(3):
+                node, tok = got[r]
+                toks, ps = cands[r]
+                want = sample_token(logits[r], T, p, k, u32[r])
+                # outcomes the margin allows: cut one candidate earlier / later where the running sum is within
+                # the margin of top_p, boundaries moved by the margin
+                allowed = set()
+                full_t, full_p = sampling_candidates(logits[r], T, 1.0 + 1e-9, min(k, len(toks) + 1))
+                run = np.cumsum(full_p)
+                for m in range(max(1, len(toks) - 1), min(len(full_t), len(toks) + 1) + 1):
+                    cut_ok = (m == len(toks)) or (m < len(toks) and run[m - 1] >= p - slack) or \
+                             (m > len(toks) and run[len(toks) - 1] < p + slack and m <= k)
+                    if not cut_ok:
+                        continue
+                    c = np.concatenate(([0.0], run[:m])) / run[m - 1]
+                    for j in range(m):
+                        if c[j] - slack <= u32[r] < c[j + 1] + slack:
+                            allowed.add(int(full_t[j]))
+                assert tok in allowed, (T, p, k, r, u32[r], tok, want, sorted(allowed))
+                n_checked += 1
+                n_marginal += len(allowed) > 1
+                if len(allowed) == 1:
+                    assert tok == want
+                par, _, tk, _, _ = pair.ora.req[r].tree.view()
+                assert node == match_root_child(par, tk, tok), (r, node, tok)
+                assert pair.gpu.tree_read(r)["root_pred"] == tok
+                pair.ora.set_root_pred(r, tok)
+    say("stochastic verification:", n_checked, "draws,", n_marginal, "inside a margin")
+    # float32 logits: the selection, the order, the running sums and the draw are compared exactly (a handful of
+    # uniform numbers may sit on a boundary); bf16 logits move every probability by several per cent at these
+    # temperatures, so there the margin rule above is the whole check
+    if tol == "f32":
+        assert n_marginal <= n_checked // 20
+    for bad in (dict(temperature=0.0), dict(top_p=0.0), dict(top_k=0), dict(top_k=129), dict(u=[1.0])):
+        kw = dict(temperature=0.6, top_p=0.9, top_k=80, u=[0.5])
+        kw.update(bad)
+        with pytest.raises(sp.SpError) as ei:
+            pair.gpu.verify_sample(pair.head, [0], x_root[:1].contiguous(), kw["temperature"], kw["top_p"], kw["top_k"], kw["u"])
+        assert ei.value.status == -1
+    pair.close()
+
+
 # ---------------------------------------------------------------------------------------
 # fixed-width expansion
 def test_fixed_width_expansion_matches_oracle():
