@@ -40,13 +40,17 @@
 // ARGMAX (output head of the last stage, Algorithm 1 "verify new token"): instead of the
 // products, a workgroup leaves per row the largest of its 16*NCG columns and that column's
 // index (the lowest one among equal maxima) as a (float, int) pair at out[(m * tiles + tile) * 2].
-template <int MT, int NCG, bool GATEUP, int KC, int PF, bool PACKED, bool ARGMAX = false>
+// TWO (plain products only): a wave holds two strips of 16 weight rows, 64 rows apart, so that a workgroup
+// covers 32*NCG columns: with 128 activation rows the staged panel would otherwise be twice the size of the
+// weights it meets, and the reads of the panel out of L2, not HBM, would set the pace.
+template <int MT, int NCG, bool GATEUP, int KC, int PF, bool PACKED, bool ARGMAX = false, bool TWO = false>
 __global__ void __launch_bounds__(256)
 k_gemm_bf16(const bf16_t* __restrict__ X, const bf16_t* __restrict__ W, float* __restrict__ out,
             bf16_t* __restrict__ act, int M, int N, int K, int chunks_total, int S) {
+  static_assert(!(TWO && (GATEUP || ARGMAX)), "two strips per wave: plain products only");
   constexpr int NKH = 4 / NCG;            // waves sharing a column group split each chunk's k-steps
   constexpr int KSTEPS = (KC / 32) / NKH;
-  constexpr int NW = GATEUP ? 2 : 1;
+  constexpr int NW = (GATEUP || TWO) ? 2 : 1;
   constexpr int ROWS = MT * 16;
   constexpr int XS = KC * 2 + 16;         // LDS row stride in bytes (conflict-free 16-byte reads)
   constexpr int UPR = KC / 8;             // 16-byte units per X row chunk
@@ -58,15 +62,16 @@ k_gemm_bf16(const bf16_t* __restrict__ X, const bf16_t* __restrict__ W, float* _
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int cg = wave % NCG, kh = wave / NCG;
   const int r = lane & 15, kg = lane >> 4;
-  const int n0 = blockIdx.x * (16 * NCG) + cg * 16;
+  const int n0 = blockIdx.x * (16 * NCG * (TWO ? 2 : 1)) + cg * 16;
+  const int pair_off = TWO ? 16 * NCG : N;   // rows between a wave's two strips (gate/up: the up rows follow the N gate rows)
   const int m_base = blockIdx.z * ROWS;
   const int c_begin = (int)(((long long)blockIdx.y * chunks_total) / S);
   const int c_end = (int)(((long long)(blockIdx.y + 1) * chunks_total) / S);
 
   const bf16_t* w0 = PACKED ? W + ((size_t)(n0 / 16) * (K / 32) + kh * KSTEPS) * 512 + lane * 8
                             : W + (size_t)(n0 + r) * K + kg * 8 + kh * (KSTEPS * 32);
-  const bf16_t* w1 = PACKED ? W + ((size_t)((N + n0) / 16) * (K / 32) + kh * KSTEPS) * 512 + lane * 8
-                            : W + (size_t)(N + n0 + r) * K + kg * 8 + kh * (KSTEPS * 32);   // up rows (GATEUP)
+  const bf16_t* w1 = PACKED ? W + ((size_t)((pair_off + n0) / 16) * (K / 32) + kh * KSTEPS) * 512 + lane * 8
+                            : W + (size_t)(pair_off + n0 + r) * K + kg * 8 + kh * (KSTEPS * 32);   // second strip
 #define SP_WOFF(C, s) (PACKED ? ((size_t)(C) * (KC / 32) + (s)) * 512 : (size_t)(C)*KC + (s) * 32)
   const int xu = tid % UPR, xr = tid / UPR;
   // rows past M are read from the last valid row and multiply into output rows that are never stored
@@ -91,7 +96,7 @@ k_gemm_bf16(const bf16_t* __restrict__ X, const bf16_t* __restrict__ W, float* _
 #define SP_LOAD_W(B, C)                                                                                 \
   _Pragma("unroll") for (int s = 0; s < KSTEPS; ++s) {                                                  \
     wb[B][0][s] = *reinterpret_cast<const u32x4_t*>(w0 + SP_WOFF(C, s));                                \
-    if (GATEUP) wb[B][NW - 1][s] = *reinterpret_cast<const u32x4_t*>(w1 + SP_WOFF(C, s));               \
+    if (NW == 2) wb[B][NW - 1][s] = *reinterpret_cast<const u32x4_t*>(w1 + SP_WOFF(C, s));              \
   }
   // One chunk C out of weight buffer B.  The activation panel of chunk C+1 was loaded to
   // registers one chunk earlier and goes to the other LDS buffer first; then the loads of
@@ -204,7 +209,9 @@ k_gemm_bf16(const bf16_t* __restrict__ X, const bf16_t* __restrict__ W, float* _
       pk.y = pack_bf16x2(o[2], o[3]);
       *reinterpret_cast<uint2*>(act + (size_t)m * N + ncol) = pk;
     } else {
-      *reinterpret_cast<f32x4_t*>(out + ((size_t)blockIdx.y * M + m) * N + ncol) = acc[0][mt];
+      float* o = out + ((size_t)blockIdx.y * M + m) * N + ncol;
+      *reinterpret_cast<f32x4_t*>(o) = acc[0][mt];
+      if (TWO) *reinterpret_cast<f32x4_t*>(o + pair_off) = acc[NW - 1][mt];
     }
   }
 }
@@ -212,22 +219,39 @@ k_gemm_bf16(const bf16_t* __restrict__ X, const bf16_t* __restrict__ W, float* _
 // ---- launchers -------------------------------------------------------------------
 // Up to 64 rows run as one block of MT = ceil(M/16) tiles; more rows run in blocks of 128 (MT = 8,
 // always with the 128-wide chunk so that the two LDS panels fit), each block streaming the weights once.
+// More than 64 rows (MT = 8): workgroups of twice the columns -- two strips per wave for the plain products,
+// four column groups instead of two for gate/up -- so that panel and weights stay one to one.
 template <int NCG, bool GATEUP, int KCV, bool PACKED, bool ARGMAX = false>
 static hipError_t launch_mt(int MT, dim3 grid, hipStream_t st, const bf16_t* X, const bf16_t* W, float* out,
-                            bf16_t* act, int M, int N, int K, int S) {
+                            bf16_t* act, int M, int N, int K, int S, bool two = false) {
 #define SP_GO(MTV, KCX)                                                                                        \
   hipLaunchKernelGGL((k_gemm_bf16<MTV, NCG, GATEUP, KCX, SP_GEMM_PF, PACKED, ARGMAX>), grid, dim3(256), 0, st, X, \
                      W, out, act, M, N, K, K / KCX, S)
+  if (!ARGMAX && MT == 4 && GATEUP && NCG == 4) {      // the 64 + 64 column gate/up workgroup at 49-64 rows
+    hipLaunchKernelGGL((k_gemm_bf16<4, 4, true, 128, SP_GEMM_PF, PACKED, false>), grid, dim3(256), 0, st, X, W, out, act, M, N, K, K / 128, S);
+    return hipGetLastError();
+  }
   switch (MT) {
     case 1: SP_GO(1, KCV); break;
     case 2: SP_GO(2, KCV); break;
     case 3: SP_GO(3, KCV); break;
     case 4: SP_GO(4, KCV); break;
-    default: SP_GO(8, 128); break;
+    default:
+      if (ARGMAX) SP_GO(8, 128);
+      else if (GATEUP && NCG == 4)
+        hipLaunchKernelGGL((k_gemm_bf16<8, 4, true, 128, SP_GEMM_PF, PACKED, false>), grid, dim3(256), 0, st, X, W, out, act,
+                           M, N, K, K / 128, S);
+      else if (GATEUP || !two) SP_GO(8, 128);
+      else
+        hipLaunchKernelGGL((k_gemm_bf16<8, 4, false, 128, SP_GEMM_PF, PACKED, false, true>), grid, dim3(256), 0, st, X, W,
+                           out, act, M, N, K, K / 128, S);
+      break;
   }
 #undef SP_GO
   return hipGetLastError();
 }
+// columns one workgroup covers
+static inline int tile_cols(int MT, bool gateup) { return 16 * (gateup ? SP_GEMM_NCG_GATEUP : SP_GEMM_NCG_PLAIN); }
 
 static inline void row_blocks(int M, int* MT, int* mblocks) {
   if (M <= 64) { *MT = (M + 15) / 16; *mblocks = 1; }
@@ -236,10 +260,16 @@ static inline void row_blocks(int M, int* MT, int* mblocks) {
 
 hipError_t sp_launch_gemm_bf16(const bf16_t* X, const bf16_t* W, bool packed, float* out, int M, int N, int K,
                                int max_split, size_t part_capacity_floats, int* S_out, hipStream_t st) {
-  constexpr int TILE = 16 * SP_GEMM_NCG_PLAIN;
-  if (M < 1 || N % TILE || K % SP_GEMM_KC_PLAIN || K % 128) return hipErrorInvalidValue;
   int MT, mblocks;
   row_blocks(M, &MT, &mblocks);
+  // 128-row blocks: two strips per wave (128 columns per workgroup) halve the panel traffic out of L2 (the
+  // 128 x K panel is read once per column tile: N/128 instead of N/64 times) but double the split count that
+  // fills the chip, i.e. the partial sums that go to memory and back.  The panel saving is N/128 * M*K*2 bytes
+  // of L2 reads, the price 65536/N * M*N*4 bytes of memory traffic: worth it for the large matrices (70B
+  // shape: 5.38 -> 4.78 ms per 128-node step), not for the 8B shape (65-128 rows: +3 to +6 %).
+  const bool two = MT == 8 && N % 128 == 0 && (double)N * (double)K >= 64.0 * 1048576.0;
+  const int TILE = two ? 128 : 16 * SP_GEMM_NCG_PLAIN;
+  if (M < 1 || N % TILE || K % SP_GEMM_KC_PLAIN || K % 128) return hipErrorInvalidValue;
   const int chunks = K / (MT == 8 ? 128 : SP_GEMM_KC_PLAIN);
   const int tiles = N / TILE;
   // Enough workgroups to keep every CU streaming, within the partial-sum buffer.
@@ -257,16 +287,25 @@ hipError_t sp_launch_gemm_bf16(const bf16_t* X, const bf16_t* W, bool packed, fl
   if ((size_t)S * M * N > part_capacity_floats) return hipErrorInvalidValue;
   *S_out = S;
   const dim3 grid(tiles, S, mblocks);
-  if (packed) return launch_mt<SP_GEMM_NCG_PLAIN, false, SP_GEMM_KC_PLAIN, true>(MT, grid, st, X, W, out, nullptr, M, N, K, S);
-  return launch_mt<SP_GEMM_NCG_PLAIN, false, SP_GEMM_KC_PLAIN, false>(MT, grid, st, X, W, out, nullptr, M, N, K, S);
+  if (packed) return launch_mt<SP_GEMM_NCG_PLAIN, false, SP_GEMM_KC_PLAIN, true>(MT, grid, st, X, W, out, nullptr, M, N, K, S, two);
+  return launch_mt<SP_GEMM_NCG_PLAIN, false, SP_GEMM_KC_PLAIN, false>(MT, grid, st, X, W, out, nullptr, M, N, K, S, two);
 }
 
 hipError_t sp_launch_gemm_gateup_bf16(const bf16_t* X, const bf16_t* W, bool packed, bf16_t* act, int M, int F,
                                       int K, hipStream_t st) {
-  constexpr int TILE = 16 * SP_GEMM_NCG_GATEUP;
-  if (M < 1 || F % TILE || K % SP_GEMM_KC_GATEUP || K % 128) return hipErrorInvalidValue;
   int MT, mblocks;
   row_blocks(M, &MT, &mblocks);
+  if (M < 1 || F % 64 || K % SP_GEMM_KC_GATEUP || K % 128) return hipErrorInvalidValue;
+  // From 49 rows on: 64 gate + 64 up columns per workgroup (four column groups, 128-k chunks) where that
+  // still gives every CU a workgroup, so that the staged panel is at most as large as the weights it meets
+  // (70B shape: gate/up 193.6 -> 179.3 us at 64 rows, 252 -> 212 us at 128 rows); else 32 + 32 columns.  With
+  // d_ff = 14336 the wider workgroups number 224 and run level with the 448 narrow ones (53.2 against 53.9 us).
+  if ((MT == 8 || MT == 4) && F / 64 * mblocks >= 256) {
+    const dim3 grid(F / 64, 1, mblocks);
+    if (packed) return launch_mt<4, true, SP_GEMM_KC_GATEUP, true>(MT, grid, st, X, W, nullptr, act, M, F, K, 1);
+    return launch_mt<4, true, SP_GEMM_KC_GATEUP, false>(MT, grid, st, X, W, nullptr, act, M, F, K, 1);
+  }
+  const int TILE = tile_cols(MT, true);
   const dim3 grid(F / TILE, 1, mblocks);
   if (packed) return launch_mt<SP_GEMM_NCG_GATEUP, true, SP_GEMM_KC_GATEUP, true>(MT, grid, st, X, W, nullptr, act, M, F, K, 1);
   return launch_mt<SP_GEMM_NCG_GATEUP, true, SP_GEMM_KC_GATEUP, false>(MT, grid, st, X, W, nullptr, act, M, F, K, 1);
