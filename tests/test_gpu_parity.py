@@ -845,17 +845,18 @@ def test_c2_full_size_in_bench_configuration():
     pair.close()
 
 
-@pytest.mark.parametrize("n_nodes", [128, 60])
-def test_c3_dimensions_one_layer(n_nodes):
+@pytest.mark.parametrize("n_nodes,flags", [(128, sp.SP_FLAG_PACKED_WEIGHTS), (60, 0), (100, 0)],
+                         ids=["128_packed", "60_rowmajor", "100_rowmajor"])
+def test_c3_dimensions_one_layer(n_nodes, flags):
     """One layer at the 70B shape (d=8192, 64/8 heads, FFN 28672) with config 3's 128-node tree and
     prefix 4096: a 128-row block per projection (two strips of 16 weight rows per wave, 64 + 64 gate/up
     columns per workgroup), 8 query heads per KV head; and with 60 nodes, where the gate/up projection
-    takes the same wide workgroups with four row tiles, the last one ragged.  (All ten layers: the
-    full-depth test.)"""
+    takes the same wide workgroups with four row tiles, the last one ragged; both weight layouts.
+    (All ten layers: the full-depth test.)"""
     w = wl.CONFIGS["C3"]
     shape = wl.scaled(w.shape, n_layers=1)
     say("C3 dims, 1 layer,", n_nodes, "nodes")
-    pair = Pair(shape, w.seed, {0: w.prefix_len}, max_batch_nodes=128, flags=sp.SP_FLAG_PACKED_WEIGHTS)
+    pair = Pair(shape, w.seed, {0: w.prefix_len}, max_batch_nodes=128, flags=flags)
     par = wl.tree_branching(w.seed, n_nodes, w.max_children, w.max_levels)
     x = wl.hidden_rows(shape, w.seed, ("x",), n_nodes)
     pair.insert(0, par)
