@@ -274,123 +274,231 @@ __device__ __forceinline__ float key_value(uint32_t k) {
   return __uint_as_float((k & 0x80000000u) ? (k & 0x7fffffffu) : ~k);
 }
 
+// Eight loads of W floats per thread, all issued before the first use: one workgroup reads the whole row, so
+// with a load per iteration a pass would be a chain of V / 1024 memory latencies.  W = 4 needs V % 4 == 0
+// (then an index below V is followed by three more).  Index of element (u, c): base + (u * 1024 + tid) * W + c.
+template <int W>
+__device__ __forceinline__ void sample_load(const float* __restrict__ L, int V, int base, int tid, float (&v)[8][W]) {
+#pragma unroll
+  for (int u = 0; u < 8; ++u) {
+    const int i = base + (u * 1024 + tid) * W;
+    if constexpr (W == 4) {
+      const float4 t = i < V ? *reinterpret_cast<const float4*>(L + i) : make_float4(0.f, 0.f, 0.f, 0.f);
+      v[u][0] = t.x; v[u][1] = t.y; v[u][2] = t.z; v[u][3] = t.w;
+    } else {
+      v[u][0] = i < V ? L[i] : 0.f;
+    }
+  }
+}
+
+#define SP_SAMPLE_CAND 2048   // candidates the short path can hold
+
+// One workgroup per request.  The K = top_k largest logits are found without ordering the row: every thread
+// keeps the maximum of the elements it reads, a wave takes the ceil(K / 16) largest of its 64 thread maxima,
+// and the smallest of those 16 * ceil(K / 16) >= K distinct elements is a lower bound t0 of the K-th largest
+// logit.  A second pass collects the elements >= t0 (a few hundred on a spread-out row) and their places follow
+// from counting.  Rows that defeat the bound (long runs of equal logits, vocabularies under a few thousand)
+// take a radix selection over the whole row instead.
+template <int W>
 __global__ void __launch_bounds__(1024) k_sample_decide(ReqMeta* meta, const ReqTables* tables,
                                                          const float* __restrict__ logits, SampleBatch b, int* out) {
-  __shared__ float s_f[16];
+  __shared__ float s_f[16], s_g[16];
   __shared__ unsigned s_hist[16][256];
   __shared__ unsigned s_scan[16];
   __shared__ unsigned s_pick[2];                  // digit chosen by a pass, and how many of the top_k are still to find below it
   __shared__ uint32_t s_key[SP_SAMPLE_MAX_K], s_skey[SP_SAMPLE_MAX_K];
   __shared__ int s_idx[SP_SAMPLE_MAX_K], s_sidx[SP_SAMPLE_MAX_K];
+  __shared__ uint32_t s_ckey[SP_SAMPLE_CAND];
+  __shared__ int s_cidx[SP_SAMPLE_CAND];
+  __shared__ unsigned s_ncand;
   __shared__ int s_tok, s_best;
   const int item = blockIdx.x, req = b.req[item];
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const float* L = logits + (size_t)item * b.V;
   const int V = b.V, K = min(b.top_k, V);
 
-  // row maximum
-  float mx = -INFINITY;
-  for (int i = tid; i < V; i += 1024) mx = fmaxf(mx, L[i]);
-  mx = wave_max(mx);
-  if (lane == 0) s_f[wave] = mx;
-  __syncthreads();
-  mx = s_f[0];
+  // first pass: thread maxima, from them the row maximum and the bound t0
+  float tm = -INFINITY;
+  for (int base = 0; base < V; base += 8 * 1024 * W) {
+    float v[8][W];
+    sample_load<W>(L, V, base, tid, v);
 #pragma unroll
-  for (int w = 1; w < 16; ++w) mx = fmaxf(mx, s_f[w]);
+    for (int u = 0; u < 8; ++u)
+      if (base + (u * 1024 + tid) * W < V) {
+#pragma unroll
+        for (int c = 0; c < W; ++c) tm = fmaxf(tm, v[u][c]);
+      }
+  }
+  {
+    const float wmx = wave_max(tm);
+    float cur = tm, kept = wmx;
+    const int rounds = (K + 15) >> 4;
+    for (int r = 0; r < rounds; ++r) {           // the wave's r-th largest thread maximum, one thread retired per round
+      kept = wave_max(cur);
+      const unsigned long long holders = __ballot(cur == kept);
+      if (holders == 0ull) { kept = -INFINITY; break; }          // only NaNs left
+      if (lane == (int)__builtin_ctzll(holders)) cur = -INFINITY;
+    }
+    if (lane == 0) { s_f[wave] = wmx; s_g[wave] = kept; }
+    if (tid == 0) s_ncand = 0u;
+  }
   __syncthreads();
-  // normaliser of softmax(l / T) over the whole vocabulary, added in a fixed order
+  float mx = s_f[0], t0 = s_g[0];
+#pragma unroll
+  for (int w = 1; w < 16; ++w) { mx = fmaxf(mx, s_f[w]); t0 = fminf(t0, s_g[w]); }
+  __syncthreads();
+
+  // second pass: the normaliser of softmax(l / T) over the whole vocabulary, added in a fixed order, and the candidates
   float z = 0.f;
-  for (int i = tid; i < V; i += 1024) z += expf((L[i] - mx) * b.inv_T);
+  for (int base = 0; base < V; base += 8 * 1024 * W) {
+    float v[8][W];
+    sample_load<W>(L, V, base, tid, v);
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const int i = base + (u * 1024 + tid) * W;
+      if (i < V) {
+#pragma unroll
+        for (int c = 0; c < W; ++c) {
+          z += expf((v[u][c] - mx) * b.inv_T);
+          if (v[u][c] >= t0) {
+            const unsigned p = atomicAdd(&s_ncand, 1u);
+            if (p < SP_SAMPLE_CAND) { s_ckey[p] = order_key(v[u][c]); s_cidx[p] = i + c; }
+          }
+        }
+      }
+    }
+  }
   z = wave_sum(z);
   if (lane == 0) s_f[wave] = z;
   __syncthreads();
   float Z = 0.f;
 #pragma unroll
   for (int w = 0; w < 16; ++w) Z += s_f[w];
+  const int n_cand = (int)s_ncand;
 
-  // the K-th largest key: fix its bytes from the top, counting the keys that share the bytes fixed so far
-  uint32_t prefix = 0u, mask = 0u;
-  unsigned need = (unsigned)K;
-  for (int shift = 24; shift >= 0; shift -= 8) {
-    for (int i = tid; i < 16 * 256; i += 1024) (&s_hist[0][0])[i] = 0u;
-    __syncthreads();
-    for (int i = tid; i < V; i += 1024) {
-      const uint32_t k = order_key(L[i]);
-      if ((k & mask) == prefix) atomicAdd(&s_hist[wave][(k >> shift) & 255u], 1u);
+  if (n_cand <= SP_SAMPLE_CAND) {
+    // descending probability, equal ones by ascending token id: a candidate's place is the number that beat it
+    for (int i = tid; i < n_cand; i += 1024) {
+      const uint32_t k = s_ckey[i];
+      const int ix = s_cidx[i];
+      int rank = 0;
+      for (int j = 0; j < n_cand; ++j) rank += (s_ckey[j] > k) || (s_ckey[j] == k && s_cidx[j] < ix);
+      if (rank < K) { s_skey[rank] = k; s_sidx[rank] = ix; }
     }
-    __syncthreads();
-    if (tid < 256) {
-      unsigned c = 0u;
+  } else {
+    // the K-th largest key: fix its bytes from the top, counting the keys that share the bytes fixed so far
+    uint32_t prefix = 0u, mask = 0u;
+    unsigned need = (unsigned)K;
+    for (int shift = 24; shift >= 0; shift -= 8) {
+      for (int i = tid; i < 16 * 256; i += 1024) (&s_hist[0][0])[i] = 0u;
+      __syncthreads();
+      for (int base = 0; base < V; base += 8 * 1024 * W) {
+        float v[8][W];
+        sample_load<W>(L, V, base, tid, v);
 #pragma unroll
-      for (int w = 0; w < 16; ++w) c += s_hist[w][tid];
-      s_hist[0][tid] = c;
-    }
-    __syncthreads();
-    if (tid == 0) {
-      unsigned above = 0u;
-      int bin = 255;
-      for (; bin > 0; --bin) {
-        if (above + s_hist[0][bin] >= need) break;
-        above += s_hist[0][bin];
+        for (int u = 0; u < 8; ++u) {
+          if (base + (u * 1024 + tid) * W < V) {
+#pragma unroll
+            for (int c = 0; c < W; ++c) {
+              const uint32_t k = order_key(v[u][c]);
+              if ((k & mask) == prefix) atomicAdd(&s_hist[wave][(k >> shift) & 255u], 1u);
+            }
+          }
+        }
       }
-      s_pick[0] = (unsigned)bin;
-      s_pick[1] = need - above;
+      __syncthreads();
+      if (tid < 256) {
+        unsigned c = 0u;
+#pragma unroll
+        for (int w = 0; w < 16; ++w) c += s_hist[w][tid];
+        s_hist[0][tid] = c;
+      }
+      __syncthreads();
+      if (tid == 0) {
+        unsigned above = 0u;
+        int bin = 255;
+        for (; bin > 0; --bin) {
+          if (above + s_hist[0][bin] >= need) break;
+          above += s_hist[0][bin];
+        }
+        s_pick[0] = (unsigned)bin;
+        s_pick[1] = need - above;
+      }
+      __syncthreads();
+      prefix |= s_pick[0] << shift;
+      mask |= 255u << shift;
+      need = s_pick[1];
+      __syncthreads();
+    }
+    const uint32_t kth = prefix;                    // `need` of the keys equal to it belong to the top K: those with the lowest index
+    const int n_gt = K - (int)need;
+
+    // gather in index order: wave w owns the indices [w * seg, (w + 1) * seg) and reads them 64 at a time, so a
+    // candidate's place is the count of the waves in front, of the rows in front and of the lower lanes of its row
+    const int seg = (((V + 15) >> 4) + 63) & ~63;
+    const int w0 = min(wave * seg, V), w1 = min(w0 + seg, V);
+    unsigned c_gt = 0u, c_eq = 0u;                  // wave-uniform
+    for (int r0 = w0; r0 < w1; r0 += 16 * 64) {
+      float v[16];
+#pragma unroll
+      for (int u = 0; u < 16; ++u) { const int i = r0 + u * 64 + lane; v[u] = i < w1 ? L[i] : 0.f; }
+#pragma unroll
+      for (int u = 0; u < 16; ++u) {
+        const bool in = r0 + u * 64 + lane < w1;
+        const uint32_t k = order_key(v[u]);
+        c_gt += (unsigned)__popcll(__ballot(in && k > kth));
+        c_eq += (unsigned)__popcll(__ballot(in && k == kth));
+      }
+    }
+    if (lane == 0) s_scan[wave] = (c_gt << 16) | min(c_eq, 0xffffu);   // more equal keys than that: only the first `need` matter
+    __syncthreads();
+    unsigned base = 0u;
+    for (int w = 0; w < wave; ++w) {                 // saturating in the low half: the sum is only compared with `need`
+      const unsigned sw = s_scan[w];
+      base = ((base >> 16) + (sw >> 16)) << 16 | min((base & 0xffffu) + (sw & 0xffffu), 0xffffu);
+    }
+    int p_gt = (int)(base >> 16), p_eq = (int)(base & 0xffffu);
+    const unsigned long long below = (1ull << lane) - 1ull;
+    for (int r0 = w0; r0 < w1; r0 += 16 * 64) {
+      float v[16];
+#pragma unroll
+      for (int u = 0; u < 16; ++u) { const int i = r0 + u * 64 + lane; v[u] = i < w1 ? L[i] : 0.f; }
+#pragma unroll
+      for (int u = 0; u < 16; ++u) {
+        const int i = r0 + u * 64 + lane;
+        const bool in = i < w1;
+        const uint32_t k = order_key(v[u]);
+        const unsigned long long m_gt = __ballot(in && k > kth), m_eq = __ballot(in && k == kth);
+        if (in && k > kth) { const int p = p_gt + __popcll(m_gt & below); s_key[p] = k; s_idx[p] = i; }
+        if (in && k == kth) {
+          const int p = p_eq + __popcll(m_eq & below);
+          if (p < (int)need) { s_key[n_gt + p] = k; s_idx[n_gt + p] = i; }
+        }
+        p_gt += __popcll(m_gt);
+        p_eq = min(p_eq + __popcll(m_eq), 0xffff);
+      }
     }
     __syncthreads();
-    prefix |= s_pick[0] << shift;
-    mask |= 255u << shift;
-    need = s_pick[1];
-    __syncthreads();
-  }
-  const uint32_t kth = prefix;                    // `need` of the keys equal to it belong to the top K: those with the lowest index
-  const int n_gt = K - (int)need;
-
-  // gather in index order: thread t owns the indices [t * chunk, (t + 1) * chunk)
-  const int chunk = (V + 1023) / 1024;
-  const int i0 = min(tid * chunk, V), i1 = min(i0 + chunk, V);
-  unsigned c_gt = 0u, c_eq = 0u;
-  for (int i = i0; i < i1; ++i) {
-    const uint32_t k = order_key(L[i]);
-    c_gt += k > kth;
-    c_eq += k == kth;
-  }
-  // exclusive prefix sums over the threads (both counts in one word: a chunk holds fewer than 65536 indices)
-  unsigned mine = (c_gt << 16) | c_eq, incl = mine;
-#pragma unroll
-  for (int o = 1; o < 64; o <<= 1) {
-    const unsigned v = __shfl_up(incl, o, 64);
-    if (lane >= o) incl += v;
-  }
-  if (lane == 63) s_scan[wave] = incl;
-  __syncthreads();
-  unsigned base = 0u;
-  for (int w = 0; w < wave; ++w) base += s_scan[w];
-  const unsigned excl = base + incl - mine;
-  int p_gt = (int)(excl >> 16), p_eq = (int)(excl & 0xffffu);
-  for (int i = i0; i < i1; ++i) {
-    const uint32_t k = order_key(L[i]);
-    if (k > kth) { s_key[p_gt] = k; s_idx[p_gt] = i; ++p_gt; }
-    else if (k == kth) { if (p_eq < (int)need) { s_key[n_gt + p_eq] = k; s_idx[n_gt + p_eq] = i; } ++p_eq; }
-  }
-  __syncthreads();
-  // descending probability, equal ones by ascending token id: a candidate's place is the number that beat it
-  if (tid < K) {
-    const uint32_t k = s_key[tid];
-    const int ix = s_idx[tid];
-    int rank = 0;
-    for (int j = 0; j < K; ++j) rank += (s_key[j] > k) || (s_key[j] == k && s_idx[j] < ix);
-    s_skey[rank] = k;
-    s_sidx[rank] = ix;
+    if (tid < K) {
+      const uint32_t k = s_key[tid];
+      const int ix = s_idx[tid];
+      int rank = 0;
+      for (int j = 0; j < K; ++j) rank += (s_key[j] > k) || (s_key[j] == k && s_idx[j] < ix);
+      s_skey[rank] = k;
+      s_sidx[rank] = ix;
+    }
   }
   if (tid == 0) s_best = 0x7fffffff;
+  __syncthreads();
+  float* cum = reinterpret_cast<float*>(&s_hist[1][0]);           // K floats, free by now
+  if (tid < K) cum[tid] = expf((key_value(s_skey[tid]) - mx) * b.inv_T) / Z;
   __syncthreads();
   if (tid == 0) {
     // running sums until top_p is reached (or the K candidates are used up); then the inverse CDF at u
     float run = 0.f;
     int m = 0;
-    float* cum = reinterpret_cast<float*>(&s_hist[1][0]);         // K floats, free by now
     for (; m < K;) {
-      run += expf((key_value(s_skey[m]) - mx) * b.inv_T) / Z;
+      run += cum[m];
       cum[m] = run;
       ++m;
       if (run >= b.top_p) break;
@@ -418,7 +526,10 @@ hipError_t sp_launch_verify_sample(ReqMeta* meta, const ReqTables* tables, const
   SampleBatch b;
   b.n = n; b.V = V; b.top_k = top_k; b.inv_T = 1.f / temperature; b.top_p = top_p;
   for (int i = 0; i < n; ++i) { b.req[i] = reqs[i]; b.u[i] = u[i]; }
-  hipLaunchKernelGGL(k_sample_decide, dim3(n), dim3(1024), 0, st, meta, tables, logits, b, out);
+  if (V % 4 == 0 && (reinterpret_cast<uintptr_t>(logits) & 15) == 0)
+    hipLaunchKernelGGL(k_sample_decide<4>, dim3(n), dim3(1024), 0, st, meta, tables, logits, b, out);
+  else
+    hipLaunchKernelGGL(k_sample_decide<1>, dim3(n), dim3(1024), 0, st, meta, tables, logits, b, out);
   return hipGetLastError();
 }
 

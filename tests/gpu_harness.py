@@ -53,7 +53,7 @@ class Pair:
 
     def __init__(self, shape: wl.ModelShape, seed: int, prefixes: Dict[int, int], *, tree_room: int = 256 + 64,
                  flags: int = 0, max_batch_nodes: int = 64, oracle: bool = True, vocab: int = 0,
-                 oracle_reqs: Optional[Sequence[int]] = None, page_slots: int = 0, head_gain: float = 1.0,
+                 oracle_reqs: Optional[Sequence[int]] = None, page_slots: int = 0, head_gain: float = 1.0, head_distinct: int = 0,
                  norm1_gain: float = 1.0, prefix_k_scale: float = 1.0, weights=None):
         """norm1_gain (a power of two: exact in bf16) multiplies the gain of every attention RMSNorm, which
         scales the nodes' queries, keys and values; prefix_k_scale (same) the keys of the committed
@@ -108,6 +108,9 @@ class Pair:
         if vocab:
             # output head of the last stage, same numbers on both sides
             self.head_np = wl.head_weights(shape, seed, vocab)
+            if head_distinct:
+                # vocabulary rows repeat with this period: logits tie exactly, on both sides
+                self.head_np["wvocab"] = np.ascontiguousarray(self.head_np["wvocab"][np.arange(vocab) % head_distinct])
             # a power of two keeps the gains exact in bf16; larger gains make the distribution peakier
             self.head_np["norm"] = self.head_np["norm"] * np.asarray(head_gain, self.head_np["norm"].dtype)
             td = torch.bfloat16 if shape.dtype == "bf16" else torch.float32
