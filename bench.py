@@ -29,6 +29,20 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16, published
 
 
+def profiled_traffic():
+    """Bytes per gate/up launch as the rocprofv3 counter runs measured them: the line
+    `bench.roofline.traffic_bytes = <number>` of profiles/pmc_hbm_traffic_stage_step_c2.txt, else None."""
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", "pmc_hbm_traffic_stage_step_c2.txt")
+    try:
+        with open(path) as f:
+            for line in f:
+                if line.startswith("bench.roofline.traffic_bytes"):
+                    return float(line.split("=", 1)[1])
+    except (OSError, ValueError):
+        pass
+    return None
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -161,8 +175,9 @@ def main() -> int:
     gu_us = gu_ms * 1e3 / max(n_launch, 1)
     achieved = gu_bytes / (gu_us * 1e-6) / 1e9
     # HBM bytes per launch from rocprofv3 PMC runs of this same command (FETCH_SIZE x 2.00 + WRITE_SIZE x 1.00,
-    # factors from a 1 GiB copy; profiles/pmc_hbm_traffic_stage_step_c2.txt).  Only valid for the profiled shape.
-    traffic = 242.63e6 if (args.workload == "C2" and n == 64) else None
+    # factors from a 1 GiB copy), read from the committed summary of those runs; it holds the profiled shape
+    # only (C2 at 64 rows), and without the file or its line the field stays null.
+    traffic = profiled_traffic() if (args.workload == "C2" and n == 64) else None
     roofline = {"bound": "hbm", "kernel": "gemm_gateup (k_gemm_bf16 GATEUP)", "achieved": round(achieved, 1),
                 "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
                 "traffic": traffic, "avg_launch_us": round(gu_us, 2), "launches": n_launch,

@@ -41,3 +41,16 @@ def test_config_shapes():
     c2, c3 = wl.CONFIGS["C2"].shape, wl.CONFIGS["C3"].shape
     assert c2.params_per_layer == 218103808 and c3.params_per_layer == 855638016
     assert c2.group == 4 and c3.group == 8
+
+
+def test_bench_traffic_comes_from_the_profile_summary():
+    """bench.py's roofline.traffic is the figure of the committed counter summary, not a constant in the
+    script: the summary's machine-readable line parses, and it is a plausible byte count for one gate/up
+    launch of the 8B shape at 64 rows (at least the algorithmic bytes, at most a few per cent more)."""
+    import bench
+    import workloads as wl
+    sh = wl.CONFIGS["C2"].shape
+    algorithmic = 2 * sh.d_ff * sh.d_model * 2 + 64 * sh.d_model * 2 + 64 * sh.d_ff * 2
+    t = bench.profiled_traffic()
+    assert t is not None
+    assert algorithmic <= t <= 1.1 * algorithmic
