@@ -39,11 +39,11 @@ template <int QT, bool PAGED>
 __global__ void __launch_bounds__(64 * AW) k_attn_bf16(AttnArgs a) {
   const AttnPlan& plan = *a.plan;
   // V tiles of the eight waves; the same bytes later carry the states being folded
-  // (four waves x QT x 8 d-tiles x 64 lanes x 16 B = QT * 32 KB <= 8 * VT_BYTES for QT <= 2).
-  __shared__ __attribute__((aligned(16))) char s_v[AW * VT_BYTES];
+  // (eight waves x QT x 8 d-tiles x 64 lanes x 16 B = QT * 64 KB).
+  constexpr int FOLD_BYTES = AW * QT * 8 * 64 * 16;
+  __shared__ __attribute__((aligned(16))) char s_v[AW * VT_BYTES > FOLD_BYTES ? AW * VT_BYTES : FOLD_BYTES];
   __shared__ float s_m[AW][QT * 16];
   __shared__ float s_l[AW][QT * 16];
-  static_assert(4 * QT * 8 * 64 * 16 <= AW * VT_BYTES, "fold buffer");
 
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   // KV head fastest: consecutive workgroup ids go round-robin over the 8 XCDs, so all query
@@ -108,13 +108,11 @@ __global__ void __launch_bounds__(64 * AW) k_attn_bf16(AttnArgs a) {
   // ---- query fragments and ancestor masks of this lane's query row per tile ------
   u32x4_t qf[QT][4];
   unsigned long long anc[QT][SP_W];
-  bool qrow_ok[QT];
   const ReqTables* tab = a.tables + plan.seg_req[seg];
 #pragma unroll
   for (int t = 0; t < QT; ++t) {
     const int qi = qb * (QT * 16) + t * 16 + l15;  // index inside (request, KV head): node_local * g + gq
     const bool ok = qi < nqrows;
-    qrow_ok[t] = ok;
     const int nl = ok ? (int)(((float)qi + 0.5f) * inv_g) : 0, gq = ok ? qi - nl * g : 0;
     const bf16_t* qp = a.q + ((size_t)(row0 + nl) * a.n_q + (size_t)kvh * g + gq) * DH + kg * 8;
 #pragma unroll
@@ -246,6 +244,9 @@ __global__ void __launch_bounds__(64 * AW) k_attn_bf16(AttnArgs a) {
 #undef SP_PHYS
 
   // ---- fold the eight wave states (fixed order, so results do not depend on timing) ----
+  // Every wave rescales its state to the common maximum and leaves it in LDS; after one barrier the block's
+  // 4 * QT pieces (query tile t, 32 output columns G) are each summed over the eight waves and written by a
+  // wave of their own.
 #pragma unroll
   for (int t = 0; t < QT; ++t) {
     lrun[t] = quad_rows_sum(lrun[t]);
@@ -253,6 +254,7 @@ __global__ void __launch_bounds__(64 * AW) k_attn_bf16(AttnArgs a) {
     if (kg == 0) s_m[wave][t * 16 + l15] = mrun[t];
   }
   __syncthreads();                       // every wave is done with its V tile; maxima are posted
+  f32x4_t* fold = reinterpret_cast<f32x4_t*>(s_v);
   float mall[QT];
 #pragma unroll
   for (int t = 0; t < QT; ++t) {
@@ -261,68 +263,49 @@ __global__ void __launch_bounds__(64 * AW) k_attn_bf16(AttnArgs a) {
     for (int w = 0; w < AW; ++w) m = fmaxf(m, s_m[w][t * 16 + l15]);
     mall[t] = m;
     const float f = (mrun[t] == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(mrun[t] - m);
-    lrun[t] *= f;
 #pragma unroll
-    for (int d = 0; d < 8; ++d) o[t][d] *= f;
+    for (int d = 0; d < 8; ++d) fold[((wave * QT + t) * 8 + d) * 64 + lane] = o[t][d] * f;
+    if (kg == 0) s_l[wave][t * 16 + l15] = lrun[t] * f;
   }
-  f32x4_t* fold = reinterpret_cast<f32x4_t*>(s_v);
+  __syncthreads();
+  if (wave >= 4 * QT) return;
+  const int t = wave >> 2, G = wave & 3;            // this wave's piece
+  f32x4_t e0 = {0.f, 0.f, 0.f, 0.f}, e1 = {0.f, 0.f, 0.f, 0.f};   // d-tiles 2G and 2G+1
+  float lsum = 0.f;
 #pragma unroll
-  for (int half = AW / 2; half >= 1; half >>= 1) {
-    if (wave >= half && wave < 2 * half) {
-#pragma unroll
-      for (int t = 0; t < QT; ++t) {
-#pragma unroll
-        for (int d = 0; d < 8; ++d) fold[(((wave - half) * QT + t) * 8 + d) * 64 + lane] = o[t][d];
-        if (kg == 0) s_l[wave - half][t * 16 + l15] = lrun[t];
-      }
-    }
-    __syncthreads();
-    if (wave < half) {
-#pragma unroll
-      for (int t = 0; t < QT; ++t) {
-#pragma unroll
-        for (int d = 0; d < 8; ++d) o[t][d] += fold[((wave * QT + t) * 8 + d) * 64 + lane];
-        lrun[t] += s_l[wave][t * 16 + l15];
-      }
-    }
-    __syncthreads();
+  for (int w = 0; w < AW; ++w) {
+    e0 += fold[((w * QT + t) * 8 + 2 * G) * 64 + lane];
+    e1 += fold[((w * QT + t) * 8 + 2 * G + 1) * 64 + lane];
+    lsum += s_l[w][t * 16 + l15];
   }
-  if (wave != 0) return;
 
-  // ---- wave 0 writes the block's result --------------------------------------------
-  // o[t][2G+h][i] is output column G*32 + 2*(4*kg+i) + h of query row t*16 + l15.
-  const size_t unit0 = (size_t)plan.seg_unit0[seg] + (size_t)ch * seg_rows * a.n_q;
-  float* part_ml = a.part_o + (size_t)plan.units_total * DH;
-#pragma unroll
-  for (int t = 0; t < QT; ++t) {
-    if (!qrow_ok[t]) continue;
-    const int qi = qb * (QT * 16) + t * 16 + l15;
-    const int nl = (int)(((float)qi + 0.5f) * inv_g), gq = qi - nl * g;
-    const int head = kvh * g + gq;
-    if (chunks == 1) {
-      const float inv = 1.f / lrun[t];
-      bf16_t* po = a.out + ((size_t)(row0 + nl) * a.n_q + head) * DH;
-#pragma unroll
-      for (int G = 0; G < 4; ++G) {
-        u32x4_t pk;
-        pk.x = pack_bf16x2(o[t][2 * G][0] * inv, o[t][2 * G + 1][0] * inv);
-        pk.y = pack_bf16x2(o[t][2 * G][1] * inv, o[t][2 * G + 1][1] * inv);
-        pk.z = pack_bf16x2(o[t][2 * G][2] * inv, o[t][2 * G + 1][2] * inv);
-        pk.w = pack_bf16x2(o[t][2 * G][3] * inv, o[t][2 * G + 1][3] * inv);
-        *reinterpret_cast<u32x4_t*>(po + G * 32 + 8 * kg) = pk;
-      }
-    } else {
-      const size_t unit = unit0 + (size_t)nl * a.n_q + head;
-      float* po = a.part_o + unit * DH;
-#pragma unroll
-      for (int G = 0; G < 4; ++G) {
-        f32x4_t lo, hi;
-        lo[0] = o[t][2 * G][0]; lo[1] = o[t][2 * G + 1][0]; lo[2] = o[t][2 * G][1]; lo[3] = o[t][2 * G + 1][1];
-        hi[0] = o[t][2 * G][2]; hi[1] = o[t][2 * G + 1][2]; hi[2] = o[t][2 * G][3]; hi[3] = o[t][2 * G + 1][3];
-        *reinterpret_cast<f32x4_t*>(po + G * 32 + 8 * kg) = lo;
-        *reinterpret_cast<f32x4_t*>(po + G * 32 + 8 * kg + 4) = hi;
-      }
-      if (kg == 0) { part_ml[unit * 2] = mall[t]; part_ml[unit * 2 + 1] = lrun[t]; }
+  // e0[i] / e1[i] are output columns G*32 + 2*(4*kg+i) and +1 of query row t*16 + l15.
+  const int qi = qb * (QT * 16) + t * 16 + l15;
+  if (qi >= nqrows) return;
+  const int nl = (int)(((float)qi + 0.5f) * inv_g), gq = qi - nl * g;
+  const int head = kvh * g + gq;
+  if (chunks == 1) {
+    const float inv = 1.f / lsum;
+    bf16_t* po = a.out + ((size_t)(row0 + nl) * a.n_q + head) * DH;
+    u32x4_t pk;
+    pk.x = pack_bf16x2(e0[0] * inv, e1[0] * inv);
+    pk.y = pack_bf16x2(e0[1] * inv, e1[1] * inv);
+    pk.z = pack_bf16x2(e0[2] * inv, e1[2] * inv);
+    pk.w = pack_bf16x2(e0[3] * inv, e1[3] * inv);
+    *reinterpret_cast<u32x4_t*>(po + G * 32 + 8 * kg) = pk;
+  } else {
+    const size_t unit = (size_t)plan.seg_unit0[seg] + (size_t)ch * seg_rows * a.n_q + (size_t)nl * a.n_q + head;
+    float* po = a.part_o + unit * DH;
+    f32x4_t lo, hi;
+    lo[0] = e0[0]; lo[1] = e1[0]; lo[2] = e0[1]; lo[3] = e1[1];
+    hi[0] = e0[2]; hi[1] = e1[2]; hi[2] = e0[3]; hi[3] = e1[3];
+    *reinterpret_cast<f32x4_t*>(po + G * 32 + 8 * kg) = lo;
+    *reinterpret_cast<f32x4_t*>(po + G * 32 + 8 * kg + 4) = hi;
+    if (G == 0 && kg == 0) {
+      float* part_ml = a.part_o + (size_t)plan.units_total * DH;
+      // the common maximum of query row t*16 + l15 (a wave-uniform choice between the two tiles' registers)
+      const float m_t = (t == 0) ? mall[0] : mall[QT - 1];
+      part_ml[unit * 2] = m_t; part_ml[unit * 2 + 1] = lsum;
     }
   }
 }
