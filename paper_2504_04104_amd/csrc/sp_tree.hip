@@ -365,27 +365,42 @@ __global__ void __launch_bounds__(1024) k_tree_expand(const ReqTables* tables, E
   __shared__ __attribute__((aligned(16))) unsigned long long s_key[SP_EXPAND_MAX];
   __shared__ unsigned char s_sel[SP_EXPAND_MAX];
   __shared__ int s_wave[16];
+  __shared__ float s_prob[SP_T], s_base[SP_T];
+  constexpr int EXPAND_CAND = 1024;                  // keys the short ranking can hold
+  __shared__ unsigned long long s_cand[EXPAND_CAND], s_bound[16];
+  __shared__ unsigned s_ncand;
   const ReqTables& t = tables[a.req];
   const int C = a.n_bottom * a.k;
-  const int C2 = (C + 1) & ~1;
+  const int C16 = (C + 15) & ~15;                    // the ranking sweep reads 16 keys at a time
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-  for (int c = tid; c < C2; c += 1024) {
-    unsigned long long key = 0ull;
-    if (c < C && cand_tok[c] >= 0) {
-      const int node = a.bottom[c / a.k];
-      float base = 1.f;
-      if (node >= 0) {
+  // the path product of every bottom token, once: the nodes' probabilities go to LDS first, so that the
+  // walk down a path is a chain of LDS reads, not of memory round trips
+  if (tid < SP_T) s_prob[tid] = t.prob[tid];
+  __syncthreads();
+  if (tid < a.n_bottom) {
+    const int node = a.bottom[tid];
+    float base = 1.f;
+    if (node >= 0) {
+      unsigned long long anc[SP_W];
 #pragma unroll
-        for (int w = 0; w < SP_W; ++w) {
-          unsigned long long bits = t.anc[node][w];
-          while (bits) {                              // ascending index = from the root downwards
-            const int j = w * 64 + __ffsll((long long)bits) - 1;
-            bits &= bits - 1;
-            base = base * t.prob[j];
-          }
+      for (int w = 0; w < SP_W; ++w) anc[w] = t.anc[node][w];
+#pragma unroll
+      for (int w = 0; w < SP_W; ++w) {
+        unsigned long long bits = anc[w];
+        while (bits) {                              // ascending index = from the root downwards
+          const int j = w * 64 + __ffsll((long long)bits) - 1;
+          bits &= bits - 1;
+          base = base * s_prob[j];
         }
       }
-      const float cum = base * cand_prob[c];
+    }
+    s_base[tid] = base;
+  }
+  __syncthreads();
+  for (int c = tid; c < C16; c += 1024) {
+    unsigned long long key = 0ull;
+    if (c < C && cand_tok[c] >= 0) {
+      const float cum = s_base[c / a.k] * cand_prob[c];
       // negative or NaN probabilities are outside the contract; they rank as absent
       key = cum >= 0.f ? ((unsigned long long)__float_as_uint(cum + 0.f) << 32) | (unsigned long long)(0xffffffffu - (unsigned)c)
                        : 0ull;
@@ -393,26 +408,78 @@ __global__ void __launch_bounds__(1024) k_tree_expand(const ReqTables* tables, E
     s_key[c] = key;
   }
   __syncthreads();
-  // rank of this thread's candidates (tid, tid + 1024, ...): one sweep over all keys, two per LDS read
+  // Which candidates are among the w largest.  A bound first: a wave takes the ceil(w / 16) largest of its
+  // threads' best keys; those are 16 * ceil(w / 16) >= w distinct candidates, so the smallest of them (t0) is
+  // at most the w-th largest key.  Only the keys >= t0 (a few more than w on spread-out probabilities) are
+  // then ranked against each other.  If they do not fit the list, every key is ranked against all keys.
   const int per_rank = (C + 1023) / 1024;            // uniform: slots this launch uses
   unsigned long long mykey[PER];
-  int rank[PER];
+  unsigned long long best = 0ull;
 #pragma unroll
   for (int i = 0; i < PER; ++i) {
     const int c = tid + i * 1024;
-    mykey[i] = c < C ? s_key[c] : ~0ull;
-    rank[i] = 0;
+    mykey[i] = c < C ? s_key[c] : 0ull;
+    best = mykey[i] > best ? mykey[i] : best;
+    if (c < C) s_sel[c] = 0;
   }
-  for (int o = 0; o < C2; o += 2) {
-    const unsigned long long k0 = s_key[o], k1 = s_key[o + 1];
+  {
+    unsigned long long cur = best, kept = 0ull;
+    const int rounds = (a.w + 15) >> 4;
+    for (int r = 0; r < rounds; ++r) {
+      kept = cur;
 #pragma unroll
-    for (int i = 0; i < PER; ++i)
-      if (i < per_rank) rank[i] += (k0 > mykey[i] ? 1 : 0) + (k1 > mykey[i] ? 1 : 0);
+      for (int o = 32; o > 0; o >>= 1) {
+        const unsigned long long other = __shfl_xor(kept, o, 64);
+        kept = other > kept ? other : kept;
+      }
+      if (kept == 0ull) break;                        // fewer present candidates than rounds: no bound from this wave
+      const unsigned long long holders = __ballot(cur == kept);     // keys are distinct: one lane
+      if (lane == (int)__builtin_ctzll(holders)) cur = 0ull;
+    }
+    if (lane == 0) s_bound[wave] = kept;
+    if (tid == 0) s_ncand = 0u;
   }
+  __syncthreads();
+  unsigned long long t0 = s_bound[0];
 #pragma unroll
-  for (int i = 0; i < PER; ++i) {
-    const int c = tid + i * 1024;
-    if (c < C) s_sel[c] = (mykey[i] != 0ull && rank[i] < a.w) ? 1 : 0;
+  for (int w = 1; w < 16; ++w) t0 = s_bound[w] < t0 ? s_bound[w] : t0;
+#pragma unroll
+  for (int i = 0; i < PER; ++i)
+    if (i < per_rank && mykey[i] != 0ull && mykey[i] >= t0) {
+      const unsigned p = atomicAdd(&s_ncand, 1u);
+      if (p < EXPAND_CAND) s_cand[p] = mykey[i];
+    }
+  __syncthreads();
+  const int n_cand = (int)s_ncand;
+  if (n_cand <= EXPAND_CAND) {
+    for (int i = tid; i < n_cand; i += 1024) {
+      const unsigned long long k = s_cand[i];
+      int rank = 0;
+      for (int j = 0; j < n_cand; ++j) rank += s_cand[j] > k ? 1 : 0;
+      if (rank < a.w) s_sel[0xffffffffu - (unsigned)(k & 0xffffffffull)] = 1;
+    }
+  } else {
+    // one sweep over all keys, sixteen per step so that eight LDS reads are in flight (absent keys are 0
+    // and beat nobody)
+    int rank[PER];
+#pragma unroll
+    for (int i = 0; i < PER; ++i) rank[i] = 0;
+    for (int o = 0; o < C16; o += 16) {
+      unsigned long long kk[16];
+#pragma unroll
+      for (int j = 0; j < 16; ++j) kk[j] = s_key[o + j];
+#pragma unroll
+      for (int i = 0; i < PER; ++i)
+        if (i < per_rank) {
+#pragma unroll
+          for (int j = 0; j < 16; ++j) rank[i] += kk[j] > mykey[i] ? 1 : 0;
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < PER; ++i) {
+      const int c = tid + i * 1024;
+      if (c < C) s_sel[c] = (mykey[i] != 0ull && rank[i] < a.w) ? 1 : 0;
+    }
   }
   __syncthreads();
   // ordered compaction: thread t owns candidates [t*per, (t+1)*per); exclusive scan of the counts
