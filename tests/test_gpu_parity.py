@@ -96,6 +96,27 @@ def test_row_counts_across_tile_edges(n):
     pair.close()
 
 
+@pytest.mark.parametrize("d_ff,n,packed", [(2048, 17, True), (6144, 33, False), (10240, 48, True), (14336, 64, True),
+                                           (14336, 50, False), (16384, 64, False), (14336, 16, True)])
+def test_ffn_widths_by_increment(d_ff, n, packed):
+    """The FFN at several widths up to the 8B shape's, both weight layouts, ragged row counts.  Small inputs
+    and the increment y - x element by element, so that a wrong strip of gate/up columns or a wrong split of
+    the down projection cannot hide behind the residual."""
+    from gpu_harness import elementwise_figure
+    shape = wl.ModelShape(n_layers=1, d_model=512, n_q_heads=4, n_kv_heads=2, d_head=128, d_ff=d_ff)
+    pair = Pair(shape, 61, {0: 40}, max_batch_nodes=64, flags=sp.SP_FLAG_PACKED_WEIGHTS if packed else 0)
+    par = wl.tree_uniform_parents(61, n, 9, name=("gu", n))
+    x = wl.hidden_rows(shape, 61, ("gu", n), n) * np.float32(2.0 ** -6)
+    pair.insert(0, par)
+    y, ref = pair.forward([0], [0], [n], x)
+    inc_gpu, inc_ref = y.astype(np.float64) - x, ref - x
+    e = float(np.max(np.abs(inc_gpu - inc_ref)) / np.max(np.abs(inc_ref)))
+    fig = elementwise_figure(inc_gpu, inc_ref, 2e-2, 5e-2)
+    say("d_ff", d_ff, "rows", n, ": increment rel err %.3e, element-wise figure %.2f" % (e, fig))
+    assert e <= TOL["bf16"] and fig <= 1.0
+    pair.close()
+
+
 def test_empty_and_degenerate_calls():
     """Calls that carry no work leave everything as it was and report success: an insert of no
     nodes, a forward / output head over no nodes (alone and as an empty request inside a batch), a
