@@ -93,10 +93,14 @@ k_gemm_bf16(const bf16_t* __restrict__ X, const bf16_t* __restrict__ W, float* _
 #define SP_STORE_X(BUF)                                                                                 \
   _Pragma("unroll") for (int p = 0; p < PASSES; ++p)                                                    \
       *reinterpret_cast<u32x4_t*>(&lds[BUF][(p * RPP + xr) * XS + xu * 16]) = xnxt[p];
+  // Every weight is read once per launch: the loads carry the non-temporal hint, so the stream does not
+  // push the activation panel (which every workgroup re-reads) out of L2 nor fill the Infinity Cache
+  // (gate/up at 8 rows: 43.4 -> 38.8 us, at 64 rows: 50.7 -> 49.5 us).
 #define SP_LOAD_W(B, C)                                                                                 \
   _Pragma("unroll") for (int s = 0; s < KSTEPS; ++s) {                                                  \
-    wb[B][0][s] = *reinterpret_cast<const u32x4_t*>(w0 + SP_WOFF(C, s));                                \
-    if (NW == 2) wb[B][NW - 1][s] = *reinterpret_cast<const u32x4_t*>(w1 + SP_WOFF(C, s));              \
+    wb[B][0][s] = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(w0 + SP_WOFF(C, s)));     \
+    if (NW == 2)                                                                                        \
+      wb[B][NW - 1][s] = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(w1 + SP_WOFF(C, s))); \
   }
   // One chunk C out of weight buffer B.  The activation panel of chunk C+1 was loaded to
   // registers one chunk earlier and goes to the other LDS buffer first; then the loads of
