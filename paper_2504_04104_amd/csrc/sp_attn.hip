@@ -35,7 +35,9 @@ struct AttnArgs {
   const AttnPlan* plan;     // device copy of the call's plan (written by the kernel that opens the forward)
 };
 
-template <int QT, bool PAGED>
+// STREAM: every request of the call has a single block of query rows, so each K/V row is read by one workgroup
+// only; the loads then carry the non-temporal hint and the rows pass through the caches without staying.
+template <int QT, bool PAGED, bool STREAM>
 __global__ void __launch_bounds__(64 * AW) k_attn_bf16(AttnArgs a) {
   const AttnPlan& plan = *a.plan;
   // V tiles of the eight waves; the same bytes later carry the states being folded
@@ -91,12 +93,14 @@ __global__ void __launch_bounds__(64 * AW) k_attn_bf16(AttnArgs a) {
       slot = SP_PHYS(slot, pg_);                                                                   \
       const char* kp = kplane + (size_t)slot * 256 + kg * 16;                                      \
       _Pragma("unroll") for (int s = 0; s < 4; ++s)                                                \
-          kreg[t2][s] = *reinterpret_cast<const u32x4_t*>(kp + s * 64);                            \
+          kreg[t2][s] = STREAM ? __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(kp + s * 64)) \
+                               : *reinterpret_cast<const u32x4_t*>(kp + s * 64);                   \
     }                                                                                              \
     _Pragma("unroll") for (int i = 0; i < 8; ++i) {                                                \
       int slot = (S0) + i * 4 + kg;                                                                \
       slot = SP_PHYS(slot, pg_);                                                                   \
-      vreg[i] = *reinterpret_cast<const u32x4_t*>(vplane + (size_t)slot * 256 + l15 * 16);         \
+      const u32x4_t* vp_ = reinterpret_cast<const u32x4_t*>(vplane + (size_t)slot * 256 + l15 * 16); \
+      vreg[i] = STREAM ? __builtin_nontemporal_load(vp_) : *vp_;                                   \
     }                                                                                              \
   }
 
@@ -391,17 +395,19 @@ hipError_t sp_launch_attn_bf16(const bf16_t* q, const ReqTables* tables, KvGeom 
   a.out = out;
   a.plan = plan_dev;
   dim3 grid(plan.total_items * n_kv);
+  bool stream = true;                     // one block of query rows per request: K/V rows are read once
+  for (int i = 0; i < plan.n_seg; ++i) stream = stream && plan.seg_qblocks[i] <= 1;
+#define SP_ATTN_GO(QTV, PG, STR) hipLaunchKernelGGL((k_attn_bf16<QTV, PG, STR>), grid, dim3(64 * AW), 0, st, a)
+#define SP_ATTN_QT(QTV)                                                              \
+  if (g.page_table) { if (stream) SP_ATTN_GO(QTV, true, true); else SP_ATTN_GO(QTV, true, false); }   \
+  else { if (stream) SP_ATTN_GO(QTV, false, true); else SP_ATTN_GO(QTV, false, false); }
   switch (plan.qt) {
-    case 1:
-      if (g.page_table) hipLaunchKernelGGL((k_attn_bf16<1, true>), grid, dim3(64 * AW), 0, st, a);
-      else hipLaunchKernelGGL((k_attn_bf16<1, false>), grid, dim3(64 * AW), 0, st, a);
-      break;
-    case 2:
-      if (g.page_table) hipLaunchKernelGGL((k_attn_bf16<2, true>), grid, dim3(64 * AW), 0, st, a);
-      else hipLaunchKernelGGL((k_attn_bf16<2, false>), grid, dim3(64 * AW), 0, st, a);
-      break;
+    case 1: SP_ATTN_QT(1) break;
+    case 2: SP_ATTN_QT(2) break;
     default: return hipErrorInvalidValue;
   }
+#undef SP_ATTN_QT
+#undef SP_ATTN_GO
   hipError_t e = hipGetLastError();
   if (e != hipSuccess || !plan.any_split) return e;
   hipLaunchKernelGGL(k_attn_merge, dim3((M * n_q + 3) / 4), dim3(256), 0, st, a, M);

@@ -215,8 +215,9 @@ __device__ __forceinline__ void gather_inplace(char* stream, size_t row_stride, 
   const int rows_per_pass = blockDim.x / U;
   const int u = threadIdx.x % U, rr = threadIdx.x / U;
   const bool active = rr < rows_per_pass;
+  // every moved row is read once and written once: both carry the non-temporal hint
   for (int b0 = first; b0 < n_keep; b0 += rows_per_pass * R) {
-    uint4 regs[R];
+    u32x4_t regs[R];
 #pragma unroll
     for (int i = 0; i < R; ++i) {
       const int dst = b0 + i * rows_per_pass + rr;
@@ -225,8 +226,9 @@ __device__ __forceinline__ void gather_inplace(char* stream, size_t row_stride, 
       const bool mv = in && s != dst;
       // rows that stay (or lanes without a row) read the stream's first bytes and drop them
       const size_t srow = phys ? (size_t)phys[mv ? s : 0] : (size_t)s;
-      const uint4 v = *reinterpret_cast<const uint4*>(stream + (mv ? srow * row_stride + (size_t)u * 16 : 0));
-      regs[i] = mv ? v : make_uint4(0u, 0u, 0u, 0u);
+      const u32x4_t v = __builtin_nontemporal_load(
+          reinterpret_cast<const u32x4_t*>(stream + (mv ? srow * row_stride + (size_t)u * 16 : 0)));
+      regs[i] = mv ? v : (u32x4_t){0u, 0u, 0u, 0u};
     }
     __syncthreads();
 #pragma unroll
@@ -235,7 +237,8 @@ __device__ __forceinline__ void gather_inplace(char* stream, size_t row_stride, 
       if (active && dst < n_keep) {
         const int s = src[dst];
         const size_t drow = phys ? (size_t)phys[dst] : (size_t)dst;
-        if (s != dst) *reinterpret_cast<uint4*>(stream + drow * row_stride + (size_t)u * 16) = regs[i];
+        if (s != dst)
+          __builtin_nontemporal_store(regs[i], reinterpret_cast<u32x4_t*>(stream + drow * row_stride + (size_t)u * 16));
       }
     }
     __syncthreads();
