@@ -687,7 +687,7 @@ int sp_stage_forward(sp_stage* s, int32_t n_req, const int32_t* req_ids, const i
       { ProfScope p(s, SP_K_GEMM_GATEUP, st);
         if (s->fast) {
           if (wide) SP_STEP(sp_launch_gemm_wide_gateup((const bf16_t*)w.xn, (const bf16_t*)L.wgu, s->packed, (bf16_t*)w.act, M, F, d, st));
-          else SP_STEP(sp_launch_gemm_gateup_bf16((const bf16_t*)w.xn, (const bf16_t*)L.wgu, s->packed, (bf16_t*)w.act, M, F, d, st));
+          else SP_STEP(sp_launch_gemm_gateup_bf16((const bf16_t*)w.xn, (const bf16_t*)L.wgu, s->packed, (bf16_t*)w.act, M, F, d, s->n_cu, st));
         } else {
           SP_STEP(sp_launch_gemm_simple(dt, w.xn, L.wgu, w.part, M, 2 * F, d, st));
           SP_STEP(sp_launch_silu_mul(dt, w.part, w.act, M, F, st));

@@ -21,6 +21,9 @@
 #ifndef SP_GEMM_PF
 #define SP_GEMM_PF 2              // weight chunks in flight ahead of the math
 #endif
+#ifndef SP_GEMM_EVEN_MIN_MT
+#define SP_GEMM_EVEN_MIN_MT 2     // row tiles from which gate/up takes one workgroup per CU where d_ff allows
+#endif
 #ifndef SP_GEMM_NCG_PLAIN
 #define SP_GEMM_NCG_PLAIN 4       // column groups (of 16 weight rows) per workgroup
 #endif
@@ -43,35 +46,54 @@
 // TWO (plain products only): a wave holds two strips of 16 weight rows, 64 rows apart, so that a workgroup
 // covers 32*NCG columns: with 128 activation rows the staged panel would otherwise be twice the size of the
 // weights it meets, and the reads of the panel out of L2, not HBM, would set the pace.
-template <int MT, int NCG, bool GATEUP, int KC, int PF, bool PACKED, bool ARGMAX = false, bool TWO = false>
-__global__ void __launch_bounds__(256)
+// EVEN (gate/up, eight waves: four column groups times two k-halves): one workgroup per CU covers cpw = d_ff / CUs
+// activation columns, 48 < cpw <= 64 and a multiple of 8 -- column groups of 16, 16, 16 and cpw - 48 columns (the
+// upper lanes of a short last group re-read its last row and their results are dropped; 8 rows of the fragment
+// layout are one 128-byte line, so nothing is fetched twice).  Every CU then streams the same bytes, which 16-row
+// strips in fixed 32-column workgroups cannot do when d_ff / 32 is not a multiple of the CU count (d_ff = 14336:
+// 1.75 workgroups per CU), and the panel is staged once per CU instead of once per four waves.
+template <int MT, int NCG, bool GATEUP, int KC, int PF, bool PACKED, bool ARGMAX = false, bool TWO = false,
+          int NWAVES = 4, bool EVEN = false>
+__global__ void __launch_bounds__(64 * NWAVES)
 k_gemm_bf16(const bf16_t* __restrict__ X, const bf16_t* __restrict__ W, float* __restrict__ out,
-            bf16_t* __restrict__ act, int M, int N, int K, int chunks_total, int S) {
+            bf16_t* __restrict__ act, int M, int N, int K, int chunks_total, int S, int cpw = 0) {
   static_assert(!(TWO && (GATEUP || ARGMAX)), "two strips per wave: plain products only");
-  constexpr int NKH = 4 / NCG;            // waves sharing a column group split each chunk's k-steps
+  static_assert(!EVEN || (GATEUP && NCG == 4), "even split: gate/up with four column groups");
+  constexpr int NTH = 64 * NWAVES;
+  constexpr int NKH = NWAVES / NCG;       // waves sharing a column group split each chunk's k-steps
   constexpr int KSTEPS = (KC / 32) / NKH;
   constexpr int NW = (GATEUP || TWO) ? 2 : 1;
   constexpr int ROWS = MT * 16;
   constexpr int XS = KC * 2 + 16;         // LDS row stride in bytes (conflict-free 16-byte reads)
   constexpr int UPR = KC / 8;             // 16-byte units per X row chunk
-  constexpr int RPP = 256 / UPR;          // rows per staging pass
+  constexpr int RPP = NTH / UPR;          // rows per staging pass
   constexpr int PASSES = ROWS / RPP;
+  static_assert(ROWS % RPP == 0, "staging passes");
   constexpr int NB = PF + 1;              // weight register buffers
   __shared__ __attribute__((aligned(16))) char lds[2][ROWS * XS];
 
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int cg = wave % NCG, kh = wave / NCG;
   const int r = lane & 15, kg = lane >> 4;
-  const int n0 = blockIdx.x * (16 * NCG * (TWO ? 2 : 1)) + cg * 16;
+  const int n0 = EVEN ? blockIdx.x * cpw + cg * 16 : blockIdx.x * (16 * NCG * (TWO ? 2 : 1)) + cg * 16;
+  const int vr = EVEN ? min(16, cpw - cg * 16) : 16;     // valid columns of this wave's group (8 or 16)
   const int pair_off = TWO ? 16 * NCG : N;   // rows between a wave's two strips (gate/up: the up rows follow the N gate rows)
   const int m_base = blockIdx.z * ROWS;
   const int c_begin = (int)(((long long)blockIdx.y * chunks_total) / S);
   const int c_end = (int)(((long long)(blockIdx.y + 1) * chunks_total) / S);
 
-  const bf16_t* w0 = PACKED ? W + ((size_t)(n0 / 16) * (K / 32) + kh * KSTEPS) * 512 + lane * 8
-                            : W + (size_t)(n0 + r) * K + kg * 8 + kh * (KSTEPS * 32);
-  const bf16_t* w1 = PACKED ? W + ((size_t)((pair_off + n0) / 16) * (K / 32) + kh * KSTEPS) * 512 + lane * 8
-                            : W + (size_t)(pair_off + n0 + r) * K + kg * 8 + kh * (KSTEPS * 32);   // second strip
+  // EVEN: a group starts at a multiple of 8, so its 16 rows may lie in two fragment blocks: per-lane row addresses
+  const int wr0 = n0 + min(r, vr - 1), wr1 = pair_off + wr0;
+  const bf16_t* w0 =
+      EVEN ? (PACKED ? W + ((size_t)(wr0 >> 4) * (K / 32) + kh * KSTEPS) * 512 + (kg * 16 + (wr0 & 15)) * 8
+                     : W + (size_t)wr0 * K + kg * 8 + kh * (KSTEPS * 32))
+           : (PACKED ? W + ((size_t)(n0 / 16) * (K / 32) + kh * KSTEPS) * 512 + lane * 8
+                     : W + (size_t)(n0 + r) * K + kg * 8 + kh * (KSTEPS * 32));
+  const bf16_t* w1 =                                                                                // second strip
+      EVEN ? (PACKED ? W + ((size_t)(wr1 >> 4) * (K / 32) + kh * KSTEPS) * 512 + (kg * 16 + (wr1 & 15)) * 8
+                     : W + (size_t)wr1 * K + kg * 8 + kh * (KSTEPS * 32))
+           : (PACKED ? W + ((size_t)((pair_off + n0) / 16) * (K / 32) + kh * KSTEPS) * 512 + lane * 8
+                     : W + (size_t)(pair_off + n0 + r) * K + kg * 8 + kh * (KSTEPS * 32));
 #define SP_WOFF(C, s) (PACKED ? ((size_t)(C) * (KC / 32) + (s)) * 512 : (size_t)(C)*KC + (s) * 32)
   const int xu = tid % UPR, xr = tid / UPR;
   // rows past M are read from the last valid row and multiply into output rows that are never stored
@@ -164,6 +186,7 @@ k_gemm_bf16(const bf16_t* __restrict__ X, const bf16_t* __restrict__ W, float* _
 
   // lane holds, for activation row m = mt*16 + l%16, output columns n0 + 4*(l/16) + 0..3
   const int ncol = n0 + 4 * kg;
+  if (EVEN && 4 * kg >= vr) return;       // columns past a short last group
   if (ARGMAX) {
     static_assert(!ARGMAX || (NKH == 1 && !GATEUP), "one wave per column group");
     float* s_val = reinterpret_cast<float*>(&lds[0][0]);          // [NCG][ROWS]; the panels are no longer read
@@ -295,11 +318,32 @@ hipError_t sp_launch_gemm_bf16(const bf16_t* X, const bf16_t* W, bool packed, fl
   return launch_mt<SP_GEMM_NCG_PLAIN, false, SP_GEMM_KC_PLAIN, false>(MT, grid, st, X, W, out, nullptr, M, N, K, S, two);
 }
 
+template <bool PACKED>
+static hipError_t launch_even(int MT, int n_wg, hipStream_t st, const bf16_t* X, const bf16_t* W, bf16_t* act, int M,
+                              int F, int K, int cpw) {
+#define SP_GO(MTV)                                                                                              \
+  hipLaunchKernelGGL((k_gemm_bf16<MTV, 4, true, SP_GEMM_KC_GATEUP, SP_GEMM_PF, PACKED, false, false, 8, true>),   \
+                     dim3(n_wg), dim3(512), 0, st, X, W, nullptr, act, M, F, K, K / SP_GEMM_KC_GATEUP, 1, cpw)
+  switch (MT) {
+    case 2: SP_GO(2); break;
+    case 3: SP_GO(3); break;
+    default: SP_GO(4); break;
+  }
+#undef SP_GO
+  return hipGetLastError();
+}
+
 hipError_t sp_launch_gemm_gateup_bf16(const bf16_t* X, const bf16_t* W, bool packed, bf16_t* act, int M, int F,
-                                      int K, hipStream_t st) {
+                                      int K, int n_cu, hipStream_t st) {
   int MT, mblocks;
   row_blocks(M, &MT, &mblocks);
   if (M < 1 || F % 64 || K % SP_GEMM_KC_GATEUP || K % 128) return hipErrorInvalidValue;
+  // 17-64 rows and a d_ff that gives every CU the same 56 or 64 columns: one eight-wave workgroup per CU
+  if (MT >= SP_GEMM_EVEN_MIN_MT && MT <= 4 && n_cu > 0 && F % n_cu == 0 && (F / n_cu) % 8 == 0 && F / n_cu > 48 &&
+      F / n_cu <= 64 && SP_GEMM_KC_GATEUP == 256) {
+    return packed ? launch_even<true>(MT, n_cu, st, X, W, act, M, F, K, F / n_cu)
+                  : launch_even<false>(MT, n_cu, st, X, W, act, M, F, K, F / n_cu);
+  }
   // From 49 rows on: 64 gate + 64 up columns per workgroup (four column groups, 128-k chunks) where that
   // still gives every CU a workgroup, so that the staged panel is at most as large as the weights it meets
   // (70B shape: gate/up 193.6 -> 179.3 us at 64 rows, 252 -> 212 us at 128 rows); else 32 + 32 columns.  With

@@ -117,7 +117,7 @@ hipError_t sp_launch_gemm_bf16(const bf16_t* X, const bf16_t* W, bool packed, fl
 hipError_t sp_launch_gemm_argmax_bf16(const bf16_t* X, const bf16_t* W, bool packed, float* pairs, int M, int V, int K,
                                       size_t pair_capacity_floats, int* tiles_out, hipStream_t st);
 hipError_t sp_launch_gemm_gateup_bf16(const bf16_t* X, const bf16_t* W, bool packed, bf16_t* act, int M, int F,
-                                      int K, hipStream_t st);
+                                      int K, int n_cu, hipStream_t st);
 // Many rows (M > 128): workgroups of 128 rows x 256 columns, weights kept in registers per wave.
 // Needs N % 256 == 0 (gate/up: F % 128 == 0) and K % 64 == 0.
 hipError_t sp_launch_gemm_wide(const bf16_t* X, const bf16_t* W, bool packed, float* out, int M, int N, int K,
