@@ -21,6 +21,15 @@
 #ifndef SP_GEMM_PF
 #define SP_GEMM_PF 2              // weight chunks in flight ahead of the math
 #endif
+#ifndef SP_GEMM_PLAIN8
+#define SP_GEMM_PLAIN8 1
+#endif
+#ifndef SP_GEMM_PLAIN8_MT8
+#define SP_GEMM_PLAIN8_MT8 1
+#endif
+#ifndef SP_GEMM_EVEN_MT8
+#define SP_GEMM_EVEN_MT8 1
+#endif
 #ifndef SP_GEMM_EVEN_MIN_MT
 #define SP_GEMM_EVEN_MIN_MT 2     // row tiles from which gate/up takes one workgroup per CU where d_ff allows
 #endif
@@ -67,8 +76,8 @@ k_gemm_bf16(const bf16_t* __restrict__ X, const bf16_t* __restrict__ W, float* _
   constexpr int XS = KC * 2 + 16;         // LDS row stride in bytes (conflict-free 16-byte reads)
   constexpr int UPR = KC / 8;             // 16-byte units per X row chunk
   constexpr int RPP = NTH / UPR;          // rows per staging pass
-  constexpr int PASSES = ROWS / RPP;
-  static_assert(ROWS % RPP == 0, "staging passes");
+  constexpr int PASSES = (ROWS + RPP - 1) / RPP;   // the last pass may cover fewer rows (48 rows, 32 per pass)
+  constexpr bool RAGGED_PASS = ROWS % RPP != 0;
   constexpr int NB = PF + 1;              // weight register buffers
   __shared__ __attribute__((aligned(16))) char lds[2][ROWS * XS];
 
@@ -114,7 +123,8 @@ k_gemm_bf16(const bf16_t* __restrict__ X, const bf16_t* __restrict__ W, float* _
   }
 #define SP_STORE_X(BUF)                                                                                 \
   _Pragma("unroll") for (int p = 0; p < PASSES; ++p)                                                    \
-      *reinterpret_cast<u32x4_t*>(&lds[BUF][(p * RPP + xr) * XS + xu * 16]) = xnxt[p];
+      if (!RAGGED_PASS || p * RPP + xr < ROWS)                                                          \
+        *reinterpret_cast<u32x4_t*>(&lds[BUF][(p * RPP + xr) * XS + xu * 16]) = xnxt[p];
   // Every weight is read once per launch: the loads carry the non-temporal hint, so the stream does not
   // push the activation panel (which every workgroup re-reads) out of L2 nor fill the Infinity Cache
   // (gate/up at 8 rows: 43.4 -> 38.8 us, at 64 rows: 50.7 -> 49.5 us).
@@ -295,7 +305,10 @@ hipError_t sp_launch_gemm_bf16(const bf16_t* X, const bf16_t* W, bool packed, fl
   // of L2 reads, the price 65536/N * M*N*4 bytes of memory traffic: worth it for the large matrices (70B
   // shape: 5.38 -> 4.78 ms per 128-node step), not for the 8B shape (65-128 rows: +3 to +6 %).
   const bool two = MT == 8 && N % 128 == 0 && (double)N * (double)K >= 64.0 * 1048576.0;
-  const int TILE = two ? 128 : 16 * SP_GEMM_NCG_PLAIN;
+  // 17-64 rows: workgroups of eight waves over 128 columns, one per CU -- the same waves per CU as two
+  // four-wave workgroups of 64 columns, but the panel slice is staged once for all eight
+  const bool eight = SP_GEMM_PLAIN8 && N % 128 == 0 && ((MT >= 2 && MT <= 4) || (SP_GEMM_PLAIN8_MT8 && MT == 8 && !two && mblocks == 1));
+  const int TILE = (two || eight) ? 128 : 16 * SP_GEMM_NCG_PLAIN;
   if (M < 1 || N % TILE || K % SP_GEMM_KC_PLAIN || K % 128) return hipErrorInvalidValue;
   const int chunks = K / (MT == 8 ? 128 : SP_GEMM_KC_PLAIN);
   const int tiles = N / TILE;
@@ -306,7 +319,7 @@ hipError_t sp_launch_gemm_bf16(const bf16_t* X, const bf16_t* W, bool packed, fl
   // 0.608 ms against 0.617 ms; a count between two and three per CU, which leaves the CUs unevenly
   // loaded, 0.638 ms; two waves per column group with half the slices again: 0.612 ms).
   int S = MT == 1 ? (SP_GEMM_TARGET_WGS + tiles * mblocks - 1) / (tiles * mblocks)
-                  : SP_GEMM_TARGET_WGS_ROWS / (tiles * mblocks);
+                  : (eight ? SP_GEMM_TARGET_WGS_ROWS / 2 : SP_GEMM_TARGET_WGS_ROWS) / (tiles * mblocks);
   if (S > max_split) S = max_split;
   if (S > chunks) S = chunks;
   while (S > 1 && (size_t)S * M * N > part_capacity_floats) --S;
@@ -314,6 +327,15 @@ hipError_t sp_launch_gemm_bf16(const bf16_t* X, const bf16_t* W, bool packed, fl
   if ((size_t)S * M * N > part_capacity_floats) return hipErrorInvalidValue;
   *S_out = S;
   const dim3 grid(tiles, S, mblocks);
+  if (eight) {
+#define SP_GO8(MTV, PK)                                                                                          \
+  hipLaunchKernelGGL((k_gemm_bf16<MTV, 8, false, SP_GEMM_KC_PLAIN, SP_GEMM_PF, PK, false, false, 8>), grid, dim3(512), 0, \
+                     st, X, W, out, nullptr, M, N, K, K / SP_GEMM_KC_PLAIN, S, 0)
+    if (packed) { if (MT == 2) SP_GO8(2, true); else if (MT == 3) SP_GO8(3, true); else if (MT == 4) SP_GO8(4, true); else SP_GO8(8, true); }
+    else { if (MT == 2) SP_GO8(2, false); else if (MT == 3) SP_GO8(3, false); else if (MT == 4) SP_GO8(4, false); else SP_GO8(8, false); }
+#undef SP_GO8
+    return hipGetLastError();
+  }
   if (packed) return launch_mt<SP_GEMM_NCG_PLAIN, false, SP_GEMM_KC_PLAIN, true>(MT, grid, st, X, W, out, nullptr, M, N, K, S, two);
   return launch_mt<SP_GEMM_NCG_PLAIN, false, SP_GEMM_KC_PLAIN, false>(MT, grid, st, X, W, out, nullptr, M, N, K, S, two);
 }
@@ -327,7 +349,11 @@ static hipError_t launch_even(int MT, int n_wg, hipStream_t st, const bf16_t* X,
   switch (MT) {
     case 2: SP_GO(2); break;
     case 3: SP_GO(3); break;
-    default: SP_GO(4); break;
+    case 4: SP_GO(4); break;
+    default:      // 65-128 rows: the 128-k chunk, so that the two 128-row panels fit
+      hipLaunchKernelGGL((k_gemm_bf16<8, 4, true, 128, SP_GEMM_PF, PACKED, false, false, 8, true>), dim3(n_wg), dim3(512), 0,
+                         st, X, W, nullptr, act, M, F, K, K / 128, 1, cpw);
+      break;
   }
 #undef SP_GO
   return hipGetLastError();
@@ -339,7 +365,7 @@ hipError_t sp_launch_gemm_gateup_bf16(const bf16_t* X, const bf16_t* W, bool pac
   row_blocks(M, &MT, &mblocks);
   if (M < 1 || F % 64 || K % SP_GEMM_KC_GATEUP || K % 128) return hipErrorInvalidValue;
   // 17-64 rows and a d_ff that gives every CU the same 56 or 64 columns: one eight-wave workgroup per CU
-  if (MT >= SP_GEMM_EVEN_MIN_MT && MT <= 4 && n_cu > 0 && F % n_cu == 0 && (F / n_cu) % 8 == 0 && F / n_cu > 48 &&
+  if (MT >= SP_GEMM_EVEN_MIN_MT && (MT <= 4 || (SP_GEMM_EVEN_MT8 && mblocks == 1)) && n_cu > 0 && F % n_cu == 0 && (F / n_cu) % 8 == 0 && F / n_cu > 48 &&
       F / n_cu <= 64 && SP_GEMM_KC_GATEUP == 256) {
     return packed ? launch_even<true>(MT, n_cu, st, X, W, act, M, F, K, F / n_cu)
                   : launch_even<false>(MT, n_cu, st, X, W, act, M, F, K, F / n_cu);
