@@ -27,6 +27,9 @@
 #ifndef SP_GEMM_PLAIN8_MT8
 #define SP_GEMM_PLAIN8_MT8 1
 #endif
+#ifndef SP_GEMM_EVEN7
+#define SP_GEMM_EVEN7 1
+#endif
 #ifndef SP_GEMM_EVEN_MT8
 #define SP_GEMM_EVEN_MT8 1
 #endif
@@ -55,10 +58,11 @@
 // TWO (plain products only): a wave holds two strips of 16 weight rows, 64 rows apart, so that a workgroup
 // covers 32*NCG columns: with 128 activation rows the staged panel would otherwise be twice the size of the
 // weights it meets, and the reads of the panel out of L2, not HBM, would set the pace.
-// EVEN (gate/up, eight waves: four column groups times two k-halves): one workgroup per CU covers cpw = d_ff / CUs
-// activation columns, 48 < cpw <= 64 and a multiple of 8 -- column groups of 16, 16, 16 and cpw - 48 columns (the
-// upper lanes of a short last group re-read its last row and their results are dropped; 8 rows of the fragment
-// layout are one 128-byte line, so nothing is fetched twice).  Every CU then streams the same bytes, which 16-row
+// EVEN (gate/up): one workgroup per CU covers cpw = d_ff / CUs activation columns, a multiple of 8, in NCG column
+// groups of 16 columns and a last one of cpw - 16 * (NCG - 1) -- eight waves as four groups times two k-halves for
+// 48 < cpw <= 64, seven waves as seven groups for 96 < cpw <= 112 (the upper lanes of a short last group re-read
+// its last row and their results are dropped; 8 rows of the fragment layout are one 128-byte line, so nothing is
+// fetched twice).  Every CU then streams the same bytes, which 16-row
 // strips in fixed 32-column workgroups cannot do when d_ff / 32 is not a multiple of the CU count (d_ff = 14336:
 // 1.75 workgroups per CU), and the panel is staged once per CU instead of once per four waves.
 template <int MT, int NCG, bool GATEUP, int KC, int PF, bool PACKED, bool ARGMAX = false, bool TWO = false,
@@ -67,7 +71,7 @@ __global__ void __launch_bounds__(64 * NWAVES)
 k_gemm_bf16(const bf16_t* __restrict__ X, const bf16_t* __restrict__ W, float* __restrict__ out,
             bf16_t* __restrict__ act, int M, int N, int K, int chunks_total, int S, int cpw = 0) {
   static_assert(!(TWO && (GATEUP || ARGMAX)), "two strips per wave: plain products only");
-  static_assert(!EVEN || (GATEUP && NCG == 4), "even split: gate/up with four column groups");
+  static_assert(!EVEN || GATEUP, "even split: gate/up only");
   constexpr int NTH = 64 * NWAVES;
   constexpr int NKH = NWAVES / NCG;       // waves sharing a column group split each chunk's k-steps
   constexpr int KSTEPS = (KC / 32) / NKH;
@@ -358,6 +362,22 @@ static hipError_t launch_even(int MT, int n_wg, hipStream_t st, const bf16_t* X,
 #undef SP_GO
   return hipGetLastError();
 }
+// the same for 96 < cpw <= 112 (the 70B shape's d_ff = 28672 on 256 CUs): seven column groups, one wave each
+template <bool PACKED>
+static hipError_t launch_even7(int MT, int n_wg, hipStream_t st, const bf16_t* X, const bf16_t* W, bf16_t* act, int M,
+                               int F, int K, int cpw) {
+#define SP_GO(MTV)                                                                                              \
+  hipLaunchKernelGGL((k_gemm_bf16<MTV, 7, true, 128, SP_GEMM_PF, PACKED, false, false, 7, true>), dim3(n_wg), dim3(448),  \
+                     0, st, X, W, nullptr, act, M, F, K, K / 128, 1, cpw)
+  switch (MT) {
+    case 2: SP_GO(2); break;
+    case 3: SP_GO(3); break;
+    case 4: SP_GO(4); break;
+    default: SP_GO(8); break;
+  }
+#undef SP_GO
+  return hipGetLastError();
+}
 
 hipError_t sp_launch_gemm_gateup_bf16(const bf16_t* X, const bf16_t* W, bool packed, bf16_t* act, int M, int F,
                                       int K, int n_cu, hipStream_t st) {
@@ -369,6 +389,11 @@ hipError_t sp_launch_gemm_gateup_bf16(const bf16_t* X, const bf16_t* W, bool pac
       F / n_cu <= 64 && SP_GEMM_KC_GATEUP == 256) {
     return packed ? launch_even<true>(MT, n_cu, st, X, W, act, M, F, K, F / n_cu)
                   : launch_even<false>(MT, n_cu, st, X, W, act, M, F, K, F / n_cu);
+  }
+  if (SP_GEMM_EVEN7 && MT >= 2 && mblocks == 1 && n_cu > 0 && F % n_cu == 0 && (F / n_cu) % 8 == 0 && F / n_cu > 96 &&
+      F / n_cu <= 112) {
+    return packed ? launch_even7<true>(MT, n_cu, st, X, W, act, M, F, K, F / n_cu)
+                  : launch_even7<false>(MT, n_cu, st, X, W, act, M, F, K, F / n_cu);
   }
   // From 49 rows on: 64 gate + 64 up columns per workgroup (four column groups, 128-k chunks) where that
   // still gives every CU a workgroup, so that the staged panel is at most as large as the weights it meets
