@@ -24,6 +24,9 @@
 #ifndef SP_GEMM_PLAIN8
 #define SP_GEMM_PLAIN8 1
 #endif
+#ifndef SP_GEMM_PLAIN6
+#define SP_GEMM_PLAIN6 1
+#endif
 #ifndef SP_GEMM_PLAIN8_MT8
 #define SP_GEMM_PLAIN8_MT8 1
 #endif
@@ -312,7 +315,11 @@ hipError_t sp_launch_gemm_bf16(const bf16_t* X, const bf16_t* W, bool packed, fl
   // 17-64 rows: workgroups of eight waves over 128 columns, one per CU -- the same waves per CU as two
   // four-wave workgroups of 64 columns, but the panel slice is staged once for all eight
   const bool eight = SP_GEMM_PLAIN8 && N % 128 == 0 && ((MT >= 2 && MT <= 4) || (SP_GEMM_PLAIN8_MT8 && MT == 8 && !two && mblocks == 1));
-  const int TILE = (two || eight) ? 128 : 16 * SP_GEMM_NCG_PLAIN;
+  // ... or six waves over 96 columns where that divides the CUs evenly and 128 columns do not (N = 6144 on 256 CUs:
+  // 64 tiles x 4 slices of equal length instead of 48 x 5 of 6 or 7 chunks)
+  const bool six = SP_GEMM_PLAIN6 && eight && MT <= 4 && N % 96 == 0 && (SP_GEMM_TARGET_WGS_ROWS / 2) % (N / 128) != 0 &&
+                   (SP_GEMM_TARGET_WGS_ROWS / 2) % (N / 96) == 0;
+  const int TILE = six ? 96 : (two || eight) ? 128 : 16 * SP_GEMM_NCG_PLAIN;
   if (M < 1 || N % TILE || K % SP_GEMM_KC_PLAIN || K % 128) return hipErrorInvalidValue;
   const int chunks = K / (MT == 8 ? 128 : SP_GEMM_KC_PLAIN);
   const int tiles = N / TILE;
@@ -331,6 +338,15 @@ hipError_t sp_launch_gemm_bf16(const bf16_t* X, const bf16_t* W, bool packed, fl
   if ((size_t)S * M * N > part_capacity_floats) return hipErrorInvalidValue;
   *S_out = S;
   const dim3 grid(tiles, S, mblocks);
+  if (six) {
+#define SP_GO6(MTV, PK)                                                                                          \
+  hipLaunchKernelGGL((k_gemm_bf16<MTV, 6, false, SP_GEMM_KC_PLAIN, SP_GEMM_PF, PK, false, false, 6>), grid, dim3(384), 0, \
+                     st, X, W, out, nullptr, M, N, K, K / SP_GEMM_KC_PLAIN, S, 0)
+    if (packed) { if (MT == 2) SP_GO6(2, true); else if (MT == 3) SP_GO6(3, true); else SP_GO6(4, true); }
+    else { if (MT == 2) SP_GO6(2, false); else if (MT == 3) SP_GO6(3, false); else SP_GO6(4, false); }
+#undef SP_GO6
+    return hipGetLastError();
+  }
   if (eight) {
 #define SP_GO8(MTV, PK)                                                                                          \
   hipLaunchKernelGGL((k_gemm_bf16<MTV, 8, false, SP_GEMM_KC_PLAIN, SP_GEMM_PF, PK, false, false, 8>), grid, dim3(512), 0, \
