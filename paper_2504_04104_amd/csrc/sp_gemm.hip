@@ -24,6 +24,9 @@
 #ifndef SP_GEMM_PLAIN8
 #define SP_GEMM_PLAIN8 1
 #endif
+#ifndef SP_GEMM_ARGMAX8
+#define SP_GEMM_ARGMAX8 1
+#endif
 #ifndef SP_GEMM_PLAIN6
 #define SP_GEMM_PLAIN6 1
 #endif
@@ -430,15 +433,26 @@ hipError_t sp_launch_gemm_gateup_bf16(const bf16_t* X, const bf16_t* W, bool pac
 // pairs[(m * tiles + tile) * 2]; *tiles_out = V / 64.  One pass over the vocabulary matrix.
 hipError_t sp_launch_gemm_argmax_bf16(const bf16_t* X, const bf16_t* W, bool packed, float* pairs, int M, int V, int K,
                                       size_t pair_capacity_floats, int* tiles_out, hipStream_t st) {
-  constexpr int TILE = 16 * SP_GEMM_NCG_PLAIN;
   static_assert(SP_GEMM_NCG_PLAIN == 4, "the top-column epilogue needs one wave per column group");
-  if (M < 1 || V % TILE || K % SP_GEMM_KC_PLAIN || K % 128) return hipErrorInvalidValue;
   int MT, mblocks;
   row_blocks(M, &MT, &mblocks);
+  // 17-64 rows: eight waves over 128 columns share one staged panel, as in the plain projections
+  const bool eight = SP_GEMM_ARGMAX8 && MT >= 2 && MT <= 4 && V % 128 == 0 && SP_GEMM_KC_PLAIN == 128;
+  const int TILE = eight ? 128 : 16 * SP_GEMM_NCG_PLAIN;
+  if (M < 1 || V % TILE || K % SP_GEMM_KC_PLAIN || K % 128) return hipErrorInvalidValue;
   const int tiles = V / TILE;
   if ((size_t)M * tiles * 2 > pair_capacity_floats) return hipErrorInvalidValue;
   *tiles_out = tiles;
   const dim3 grid(tiles, 1, mblocks);
+  if (eight) {
+#define SP_GOA(MTV, PK)                                                                                        \
+  hipLaunchKernelGGL((k_gemm_bf16<MTV, 8, false, 128, SP_GEMM_PF, PK, true, false, 8>), grid, dim3(512), 0, st, X, W, \
+                     pairs, nullptr, M, V, K, K / 128, 1, 0)
+    if (packed) { if (MT == 2) SP_GOA(2, true); else if (MT == 3) SP_GOA(3, true); else SP_GOA(4, true); }
+    else { if (MT == 2) SP_GOA(2, false); else if (MT == 3) SP_GOA(3, false); else SP_GOA(4, false); }
+#undef SP_GOA
+    return hipGetLastError();
+  }
   if (packed) return launch_mt<SP_GEMM_NCG_PLAIN, false, SP_GEMM_KC_PLAIN, true, true>(MT, grid, st, X, W, pairs, nullptr, M, V, K, 1);
   return launch_mt<SP_GEMM_NCG_PLAIN, false, SP_GEMM_KC_PLAIN, false, true>(MT, grid, st, X, W, pairs, nullptr, M, V, K, 1);
 }
