@@ -52,19 +52,32 @@ __global__ void __launch_bounds__(64 * AW) k_attn_bf16(AttnArgs a) {
   // blocks and chunks of one KV head share one XCD's L2 and its K/V rows are fetched from HBM once
   const int kvh = blockIdx.x % a.n_kv;
   const int item = blockIdx.x / a.n_kv;
+  // Segment 0's fields are asked for together with the segment count: a call with one request (the rule) then
+  // waits for one round trip to the plan, not for two in a row.
+  int sg_item0 = plan.seg_item0[0], sg_chunks = plan.seg_chunks[0], sg_rows = plan.seg_rows[0], sg_row0 = plan.seg_row0[0];
+  int sg_P = plan.seg_P[0], sg_T = plan.seg_T[0], sg_clen = plan.seg_clen[0], sg_req = plan.seg_req[0];
+  int sg_first = plan.seg_first[0], sg_unit0 = plan.seg_unit0[0];
+  long long sg_base = plan.seg_base[0];
+  const int n_seg = plan.n_seg, units_total = plan.units_total;
   int seg = 0;
-  while (seg + 1 < plan.n_seg && item >= plan.seg_item0[seg + 1]) ++seg;
-  const int local = item - plan.seg_item0[seg];
-  const int chunks = plan.seg_chunks[seg];
+  while (seg + 1 < n_seg && item >= plan.seg_item0[seg + 1]) ++seg;
+  if (seg != 0) {
+    sg_item0 = plan.seg_item0[seg]; sg_chunks = plan.seg_chunks[seg]; sg_rows = plan.seg_rows[seg];
+    sg_row0 = plan.seg_row0[seg]; sg_P = plan.seg_P[seg]; sg_T = plan.seg_T[seg]; sg_clen = plan.seg_clen[seg];
+    sg_req = plan.seg_req[seg]; sg_first = plan.seg_first[seg]; sg_unit0 = plan.seg_unit0[seg];
+    sg_base = plan.seg_base[seg];
+  }
+  const int local = item - sg_item0;
+  const int chunks = sg_chunks;
   const int qb = local / chunks, ch = local - qb * chunks;
   const int g = a.n_q / a.n_kv;
   const float inv_g = 1.f / (float)g;              // (qi + 0.5) * inv_g truncates to qi / g for these small integers
-  const int seg_rows = plan.seg_rows[seg], row0 = plan.seg_row0[seg];
+  const int seg_rows = sg_rows, row0 = sg_row0;
   const int nqrows = seg_rows * g;                 // query rows of this (request, KV head)
-  const int P = plan.seg_P[seg], T = plan.seg_T[seg];
+  const int P = sg_P, T = sg_T;
   const int span = P + T;
-  const int c0 = ch * plan.seg_clen[seg];
-  const int c1 = min(c0 + plan.seg_clen[seg], span);
+  const int c0 = ch * sg_clen;
+  const int c1 = min(c0 + sg_clen, span);
   // this wave's run of 32-slot tiles inside [c0, c1)
   const int ntiles = (c1 - c0 + 31) >> 5;
   const int w0 = c0 + 32 * ((wave * ntiles) / AW);
@@ -73,10 +86,10 @@ __global__ void __launch_bounds__(64 * AW) k_attn_bf16(AttnArgs a) {
 
   // contiguous cache: the request's range starts at its base slot; paged: logical slots go through
   // the request's page table, one lookup per 32-slot tile (a tile never straddles a page)
-  const size_t base_b = PAGED ? 0 : (size_t)plan.seg_base[seg] * 256;
+  const size_t base_b = PAGED ? 0 : (size_t)sg_base * 256;
   const char* kplane = a.g.kv + ((size_t)(a.layer * 2 + 0) * a.n_kv + kvh) * a.g.plane_bytes + base_b;
   const char* vplane = a.g.kv + ((size_t)(a.layer * 2 + 1) * a.n_kv + kvh) * a.g.plane_bytes + base_b;
-  const int* pt = PAGED ? a.g.page_table + (size_t)plan.seg_req[seg] * a.g.pt_stride : nullptr;
+  const int* pt = PAGED ? a.g.page_table + (size_t)sg_req * a.g.pt_stride : nullptr;
   const int pg_sh = PAGED ? a.g.pg_shift : 0, pg_mask = (1 << pg_sh) - 1;
   const int page0 = PAGED ? pt[0] : 0;
 #define SP_PHYS(slot, pg) (PAGED ? (((slot) < span ? (pg) : page0) << pg_sh | ((slot) < span ? ((slot) & pg_mask) : 0)) \
@@ -112,7 +125,7 @@ __global__ void __launch_bounds__(64 * AW) k_attn_bf16(AttnArgs a) {
   // ---- query fragments and ancestor masks of this lane's query row per tile ------
   u32x4_t qf[QT][4];
   unsigned long long anc[QT][SP_W];
-  const ReqTables* tab = a.tables + plan.seg_req[seg];
+  const ReqTables* tab = a.tables + sg_req;
 #pragma unroll
   for (int t = 0; t < QT; ++t) {
     const int qi = qb * (QT * 16) + t * 16 + l15;  // index inside (request, KV head): node_local * g + gq
@@ -124,7 +137,7 @@ __global__ void __launch_bounds__(64 * AW) k_attn_bf16(AttnArgs a) {
       const u32x4_t v = *reinterpret_cast<const u32x4_t*>(qp + s * 32);
       qf[t][s] = ok ? v : (u32x4_t){0u, 0u, 0u, 0u};
     }
-    const int node = plan.seg_first[seg] + nl;
+    const int node = sg_first + nl;
 #pragma unroll
     for (int w = 0; w < SP_W; ++w) {
       const unsigned long long v = tab->anc[node][w];
@@ -298,7 +311,7 @@ __global__ void __launch_bounds__(64 * AW) k_attn_bf16(AttnArgs a) {
     pk.w = pack_bf16x2(e0[3] * inv, e1[3] * inv);
     *reinterpret_cast<u32x4_t*>(po + G * 32 + 8 * kg) = pk;
   } else {
-    const size_t unit = (size_t)plan.seg_unit0[seg] + (size_t)ch * seg_rows * a.n_q + (size_t)nl * a.n_q + head;
+    const size_t unit = (size_t)sg_unit0 + (size_t)ch * seg_rows * a.n_q + (size_t)nl * a.n_q + head;
     float* po = a.part_o + unit * DH;
     f32x4_t lo, hi;
     lo[0] = e0[0]; lo[1] = e1[0]; lo[2] = e0[1]; lo[3] = e1[1];
@@ -306,7 +319,7 @@ __global__ void __launch_bounds__(64 * AW) k_attn_bf16(AttnArgs a) {
     *reinterpret_cast<f32x4_t*>(po + G * 32 + 8 * kg) = lo;
     *reinterpret_cast<f32x4_t*>(po + G * 32 + 8 * kg + 4) = hi;
     if (G == 0 && kg == 0) {
-      float* part_ml = a.part_o + (size_t)plan.units_total * DH;
+      float* part_ml = a.part_o + (size_t)units_total * DH;
       // the common maximum of query row t*16 + l15 (a wave-uniform choice between the two tiles' registers)
       const float m_t = (t == 0) ? mall[0] : mall[QT - 1];
       part_ml[unit * 2] = m_t; part_ml[unit * 2 + 1] = lsum;
@@ -319,17 +332,22 @@ __global__ void __launch_bounds__(64 * AW) k_attn_bf16(AttnArgs a) {
 // the chunk's weight; the outputs are then accumulated chunk by chunk, two columns per lane.
 __global__ void __launch_bounds__(256) k_attn_merge(AttnArgs a, int M) {
   const AttnPlan& plan = *a.plan;
+  int sg_chunks = plan.seg_chunks[0], sg_rows = plan.seg_rows[0], sg_unit0 = plan.seg_unit0[0], sg_row0 = plan.seg_row0[0];
+  const int n_seg = plan.n_seg;
   const float* part_ml = a.part_o + (size_t)plan.units_total * DH;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int item = blockIdx.x * 4 + wave;
   if (item >= M * a.n_q) return;
   const int row = item / a.n_q, head = item - row * a.n_q;
   int seg = 0;
-  while (seg + 1 < plan.n_seg && row >= plan.seg_row0[seg + 1]) ++seg;
-  const int chunks = plan.seg_chunks[seg], seg_rows = plan.seg_rows[seg];
+  while (seg + 1 < n_seg && row >= plan.seg_row0[seg + 1]) ++seg;
+  if (seg != 0) {
+    sg_chunks = plan.seg_chunks[seg]; sg_rows = plan.seg_rows[seg]; sg_unit0 = plan.seg_unit0[seg]; sg_row0 = plan.seg_row0[seg];
+  }
+  const int chunks = sg_chunks, seg_rows = sg_rows;
   if (chunks == 1) return;               // written directly by the attention kernel
   const size_t stride = (size_t)seg_rows * a.n_q;
-  const size_t u0 = (size_t)plan.seg_unit0[seg] + (size_t)(row - plan.seg_row0[seg]) * a.n_q + head;
+  const size_t u0 = (size_t)sg_unit0 + (size_t)(row - sg_row0) * a.n_q + head;
   float acc0 = 0.f, acc1 = 0.f, lsum = 0.f, mx = -INFINITY;
   for (int c0 = 0; c0 < chunks; c0 += 64) {        // blocks of 64 chunks (one is the rule)
     const int c = c0 + lane;
