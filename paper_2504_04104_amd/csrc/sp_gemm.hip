@@ -383,7 +383,7 @@ static hipError_t launch_even(int MT, int n_wg, hipStream_t st, const bf16_t* X,
     case 3: SP_GO(3); break;
     case 4: SP_GO(4); break;
     default:      // 65-128 rows: the 128-k chunk, so that the two 128-row panels fit
-      hipLaunchKernelGGL((k_gemm_bf16<8, 4, true, 128, SP_GEMM_PF, PACKED, false, false, 8, true>), dim3(n_wg), dim3(512), 0,
+      hipLaunchKernelGGL((k_gemm_bf16<8, 4, true, 128, SP_GEMM_PF_EVEN, PACKED, false, false, 8, true>), dim3(n_wg), dim3(512), 0,
                          st, X, W, nullptr, act, M, F, K, K / 128, 1, cpw);
       break;
   }
@@ -394,14 +394,15 @@ static hipError_t launch_even(int MT, int n_wg, hipStream_t st, const bf16_t* X,
 template <bool PACKED>
 static hipError_t launch_even7(int MT, int n_wg, hipStream_t st, const bf16_t* X, const bf16_t* W, bf16_t* act, int M,
                                int F, int K, int cpw) {
-#define SP_GO(MTV)                                                                                              \
-  hipLaunchKernelGGL((k_gemm_bf16<MTV, 7, true, 128, SP_GEMM_PF, PACKED, false, false, 7, true>), dim3(n_wg), dim3(448),  \
-                     0, st, X, W, nullptr, act, M, F, K, K / 128, 1, cpw)
+  // three weight chunks in flight up to 64 rows (148 -> 145 us per launch), two with 128 (three: 171 -> 179 us)
+#define SP_GO(MTV, PFV)                                                                                         \
+  hipLaunchKernelGGL((k_gemm_bf16<MTV, 7, true, 128, PFV, PACKED, false, false, 7, true>), dim3(n_wg), dim3(448), 0, st, X, \
+                     W, nullptr, act, M, F, K, K / 128, 1, cpw)
   switch (MT) {
-    case 2: SP_GO(2); break;
-    case 3: SP_GO(3); break;
-    case 4: SP_GO(4); break;
-    default: SP_GO(8); break;
+    case 2: SP_GO(2, 3); break;
+    case 3: SP_GO(3, 3); break;
+    case 4: SP_GO(4, 3); break;
+    default: SP_GO(8, 2); break;
   }
 #undef SP_GO
   return hipGetLastError();
