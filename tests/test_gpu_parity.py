@@ -97,14 +97,17 @@ def test_row_counts_across_tile_edges(n):
 
 
 @pytest.mark.parametrize("d_ff,n,packed", [(2048, 17, True), (6144, 33, False), (10240, 48, True), (14336, 64, True),
-                                           (14336, 50, False), (16384, 64, False), (14336, 16, True)])
+                                           (14336, 50, False), (16384, 64, False), (14336, 16, True), (14336, 20, False),
+                                           (14336, 40, True), (14336, 100, True), (16384, 128, False), (14336, 65, False)])
 def test_ffn_widths_by_increment(d_ff, n, packed):
-    """The FFN at several widths up to the 8B shape's, both weight layouts, ragged row counts.  Small inputs
-    and the increment y - x element by element, so that a wrong strip of gate/up columns or a wrong split of
-    the down projection cannot hide behind the residual."""
+    """The FFN at several widths up to the 8B shape's, both weight layouts, ragged row counts from two row
+    tiles to the 128-row block (d_ff = 14336 and 16384 give each of 256 CUs 56 and 64 gate/up columns: the
+    one-workgroup-per-CU kernel with a short and with a full last column group).  Small inputs and the
+    increment y - x element by element, so that a wrong strip of gate/up columns or a wrong split of the down
+    projection cannot hide behind the residual."""
     from gpu_harness import elementwise_figure
     shape = wl.ModelShape(n_layers=1, d_model=512, n_q_heads=4, n_kv_heads=2, d_head=128, d_ff=d_ff)
-    pair = Pair(shape, 61, {0: 40}, max_batch_nodes=64, flags=sp.SP_FLAG_PACKED_WEIGHTS if packed else 0)
+    pair = Pair(shape, 61, {0: 40}, max_batch_nodes=128, flags=sp.SP_FLAG_PACKED_WEIGHTS if packed else 0)
     par = wl.tree_uniform_parents(61, n, 9, name=("gu", n))
     x = wl.hidden_rows(shape, 61, ("gu", n), n) * np.float32(2.0 ** -6)
     pair.insert(0, par)
