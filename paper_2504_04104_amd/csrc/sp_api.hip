@@ -151,6 +151,9 @@ struct sp_stage {
   int* pin_nodes = nullptr;    // pinned host copy of the device-side verification results (sp_tree_prune_verified)
   hipEvent_t rec_ev = nullptr; // done when that copy has arrived
   int n_cu = 256;              // compute units of the device
+  // The O projections of all the stage's layers together fit in half of the 256 MB Infinity Cache: they are read with
+  // ordinary loads and so stay there from one step to the next, while every other weight streams past it.
+  bool o_resident = false;
   int device = 0;              // the device that was current at sp_stage_create
   int last_hip = 0;
   // profiling
@@ -350,6 +353,7 @@ int sp_stage_create(const sp_config* cfg, const sp_layer_weights* layers, const 
     s->device = dev;
     if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && cus > 0)
       s->n_cu = cus;
+    s->o_resident = (size_t)cfg->n_layers * cfg->d_model * cfg->n_q_heads * cfg->d_head * 2 <= ((size_t)128 << 20);
     if (!g_noalloc_scratch[dev]) {
       // this device's copy of the static scratch array (the device is current here)
       void* p = nullptr;
@@ -644,12 +648,12 @@ int sp_stage_forward(sp_stage* s, int32_t n_req, const int32_t* req_ids, const i
   const size_t strideD = (size_t)M * d, strideQ = (size_t)M * nqkv;
   // projections: few rows stream the weights (HBM-bound); many rows use the register-blocked kernel
   const bool wide = s->fast && M > 128 && nqkv % 256 == 0 && d % 256 == 0 && F % 128 == 0 && dq % 128 == 0;
-  auto gemm = [&](const void* X, const void* Wm, int N_, int K_, int* S_) -> hipError_t {
+  auto gemm = [&](const void* X, const void* Wm, int N_, int K_, int* S_, bool resident = false) -> hipError_t {
     if (wide)
       return sp_launch_gemm_wide((const bf16_t*)X, (const bf16_t*)Wm, s->packed, w.part, M, N_, K_, s->n_cu,
                                  w.part_floats, S_, st);
     return sp_launch_gemm_bf16((const bf16_t*)X, (const bf16_t*)Wm, s->packed, w.part, M, N_, K_, 16, w.part_floats,
-                               S_, st);
+                               S_, st, resident);
   };
   // Everything between the kernel that opens the call (rows enter, first RMSNorm, plan to device
   // memory) and the one that writes the result out.  No argument of these launches depends on the
@@ -680,7 +684,7 @@ int sp_stage_forward(sp_stage* s, int32_t n_req, const int32_t* req_ids, const i
       }
       { ProfScope p(s, SP_K_GEMM_O, st);
         S = 1;
-        if (s->fast) SP_STEP(gemm(w.attn, L.wo, d, dq, &S));
+        if (s->fast) SP_STEP(gemm(w.attn, L.wo, d, dq, &S, s->o_resident));
         else SP_STEP(sp_launch_gemm_simple(dt, w.attn, L.wo, w.part, M, d, dq, st)); }
       { ProfScope p(s, SP_K_NORM, st);
         SP_STEP(sp_launch_add_norm(dt, w.h, w.part, S, strideD, L.norm2, w.xn, M, d, c.rms_eps, st)); }

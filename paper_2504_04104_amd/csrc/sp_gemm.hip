@@ -78,7 +78,7 @@
 // strips in fixed 32-column workgroups cannot do when d_ff / 32 is not a multiple of the CU count (d_ff = 14336:
 // 1.75 workgroups per CU), and the panel is staged once per CU instead of once per four waves.
 template <int MT, int NCG, bool GATEUP, int KC, int PF, bool PACKED, bool ARGMAX = false, bool TWO = false,
-          int NWAVES = 4, bool EVEN = false>
+          int NWAVES = 4, bool EVEN = false, bool WNT = true>
 __global__ void __launch_bounds__(64 * NWAVES)
 k_gemm_bf16(const bf16_t* __restrict__ X, const bf16_t* __restrict__ W, float* __restrict__ out,
             bf16_t* __restrict__ act, int M, int N, int K, int chunks_total, int S, int cpw = 0) {
@@ -141,14 +141,17 @@ k_gemm_bf16(const bf16_t* __restrict__ X, const bf16_t* __restrict__ W, float* _
   _Pragma("unroll") for (int p = 0; p < PASSES; ++p)                                                    \
       if (!RAGGED_PASS || p * RPP + xr < ROWS)                                                          \
         *reinterpret_cast<u32x4_t*>(&lds[BUF][(p * RPP + xr) * XS + xu * 16]) = xnxt[p];
-  // Every weight is read once per launch: the loads carry the non-temporal hint, so the stream does not
+  // Every weight is read once per launch: the loads carry the non-temporal hint (WNT), so the stream does not
   // push the activation panel (which every workgroup re-reads) out of L2 nor fill the Infinity Cache
-  // (gate/up at 8 rows: 43.4 -> 38.8 us, at 64 rows: 50.7 -> 49.5 us).
+  // (gate/up at 8 rows: 43.4 -> 38.8 us, at 64 rows: 50.7 -> 49.5 us).  The exception is a matrix the caller
+  // wants to find in the Infinity Cache again at the next step: ordinary loads.
 #define SP_LOAD_W(B, C)                                                                                 \
   _Pragma("unroll") for (int s = 0; s < KSTEPS; ++s) {                                                  \
-    wb[B][0][s] = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(w0 + SP_WOFF(C, s)));     \
+    wb[B][0][s] = WNT ? __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(w0 + SP_WOFF(C, s)))   \
+                      : *reinterpret_cast<const u32x4_t*>(w0 + SP_WOFF(C, s));                           \
     if (NW == 2)                                                                                        \
-      wb[B][NW - 1][s] = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(w1 + SP_WOFF(C, s))); \
+      wb[B][NW - 1][s] = WNT ? __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(w1 + SP_WOFF(C, s))) \
+                             : *reinterpret_cast<const u32x4_t*>(w1 + SP_WOFF(C, s));                    \
   }
   // One chunk C out of weight buffer B.  The activation panel of chunk C+1 was loaded to
   // registers one chunk earlier and goes to the other LDS buffer first; then the loads of
@@ -315,7 +318,7 @@ static inline void row_blocks(int M, int* MT, int* mblocks) {
 }
 
 hipError_t sp_launch_gemm_bf16(const bf16_t* X, const bf16_t* W, bool packed, float* out, int M, int N, int K,
-                               int max_split, size_t part_capacity_floats, int* S_out, hipStream_t st) {
+                               int max_split, size_t part_capacity_floats, int* S_out, hipStream_t st, bool resident) {
   int MT, mblocks;
   row_blocks(M, &MT, &mblocks);
   // 128-row blocks: two strips per wave (128 columns per workgroup) halve the panel traffic out of L2 (the
@@ -361,6 +364,10 @@ hipError_t sp_launch_gemm_bf16(const bf16_t* X, const bf16_t* W, bool packed, fl
   }
   if (eight) {
 #define SP_GO8(MTV, PK)                                                                                          \
+  if (resident && MTV <= 4)                                                                                      \
+    hipLaunchKernelGGL((k_gemm_bf16<(MTV <= 4 ? MTV : 4), 8, false, SP_GEMM_KC_PLAIN, SP_GEMM_PF_EIGHT, PK, false, false, 8, false, false>), \
+                       grid, dim3(512), 0, st, X, W, out, nullptr, M, N, K, K / SP_GEMM_KC_PLAIN, S, 0);          \
+  else                                                                                                           \
   hipLaunchKernelGGL((k_gemm_bf16<MTV, 8, false, SP_GEMM_KC_PLAIN, SP_GEMM_PF_EIGHT, PK, false, false, 8>), grid, dim3(512), 0, \
                      st, X, W, out, nullptr, M, N, K, K / SP_GEMM_KC_PLAIN, S, 0)
     if (packed) { if (MT == 2) SP_GO8(2, true); else if (MT == 3) SP_GO8(3, true); else if (MT == 4) SP_GO8(4, true); else SP_GO8(8, true); }

@@ -112,7 +112,8 @@ hipError_t sp_launch_gemm_simple(int dtype, const void* X, const void* W, float*
 // bf16 MFMA kernels.  Returns the split count used in *S_out (partials [S][M][N]).  packed: the
 // weights are in MFMA fragment order (sp_launch_pack_weights).
 hipError_t sp_launch_gemm_bf16(const bf16_t* X, const bf16_t* W, bool packed, float* out, int M, int N, int K,
-                               int max_split, size_t part_capacity_floats, int* S_out, hipStream_t st);
+                               int max_split, size_t part_capacity_floats, int* S_out, hipStream_t st,
+                               bool resident = false);
 // act[m][f] = silu(X Wg^T) * (X Wu^T), W = [gate rows ; up rows]
 hipError_t sp_launch_gemm_argmax_bf16(const bf16_t* X, const bf16_t* W, bool packed, float* pairs, int M, int V, int K,
                                       size_t pair_capacity_floats, int* tiles_out, hipStream_t st);
