@@ -4,6 +4,10 @@
 // its 16 weight rows straight from HBM into registers in MFMA operand layout (one
 // 16-byte load per lane per k-step, PF chunks ahead of the math), while the M x K
 // activation panel -- shared by every wave -- is staged once per workgroup through LDS.
+// Up to 16 rows a workgroup is four waves over 64 columns (the panel is small, more workgroups
+// stream better); from 17 rows on it is eight waves over 128 columns, or over the CU's even share
+// of the gate/up columns, one workgroup per CU, because the panel's way from L2 into the CU is
+// then what the rows cost.  The weights carry the non-temporal hint.
 //
 //   out[y][m][n] = sum_{k in slice y} X[m][k] * W[n][k]        (f32 partial sums)
 //
@@ -21,29 +25,30 @@
 #ifndef SP_GEMM_PF
 #define SP_GEMM_PF 2              // weight chunks in flight ahead of the math
 #endif
+// Workgroup shapes from 17 rows on, each measured against the four-wave 64-column workgroup it replaces (1 = on):
 #ifndef SP_GEMM_PLAIN8
-#define SP_GEMM_PLAIN8 1
+#define SP_GEMM_PLAIN8 1          // plain products, 17-64 rows: eight waves over 128 columns, one workgroup per CU
+#endif
+#ifndef SP_GEMM_PLAIN8_MT8
+#define SP_GEMM_PLAIN8_MT8 1      // ... and at 65-128 rows (small matrices; the large ones take two strips per wave)
+#endif
+#ifndef SP_GEMM_PLAIN6
+#define SP_GEMM_PLAIN6 1          // ... six waves over 96 columns where that divides the CUs evenly and 128 do not
+#endif
+#ifndef SP_GEMM_ARGMAX8
+#define SP_GEMM_ARGMAX8 1         // the output head's top-column kernel in the eight-wave shape
+#endif
+#ifndef SP_GEMM_EVEN7
+#define SP_GEMM_EVEN7 1           // gate/up, one workgroup per CU over 96 < d_ff / CUs <= 112 columns (seven waves)
+#endif
+#ifndef SP_GEMM_EVEN_MT8
+#define SP_GEMM_EVEN_MT8 1        // gate/up, one workgroup per CU, also at 65-128 rows
 #endif
 #ifndef SP_GEMM_PF_EVEN
 #define SP_GEMM_PF_EVEN 3         // the eight-wave gate/up kernel has the registers for a third chunk (45.5 -> 44.9 us)
 #endif
 #ifndef SP_GEMM_PF_EIGHT
-#define SP_GEMM_PF_EIGHT SP_GEMM_PF
-#endif
-#ifndef SP_GEMM_ARGMAX8
-#define SP_GEMM_ARGMAX8 1
-#endif
-#ifndef SP_GEMM_PLAIN6
-#define SP_GEMM_PLAIN6 1
-#endif
-#ifndef SP_GEMM_PLAIN8_MT8
-#define SP_GEMM_PLAIN8_MT8 1
-#endif
-#ifndef SP_GEMM_EVEN7
-#define SP_GEMM_EVEN7 1
-#endif
-#ifndef SP_GEMM_EVEN_MT8
-#define SP_GEMM_EVEN_MT8 1
+#define SP_GEMM_PF_EIGHT SP_GEMM_PF   // the eight-wave plain kernels are faster with two
 #endif
 #ifndef SP_GEMM_EVEN_MIN_MT
 #define SP_GEMM_EVEN_MIN_MT 2     // row tiles from which gate/up takes one workgroup per CU where d_ff allows
