@@ -369,8 +369,8 @@ hipError_t sp_launch_gemm_bf16(const bf16_t* X, const bf16_t* W, bool packed, fl
   }
   if (eight) {
 #define SP_GO8(MTV, PK)                                                                                          \
-  if (resident && MTV <= 4)                                                                                      \
-    hipLaunchKernelGGL((k_gemm_bf16<(MTV <= 4 ? MTV : 4), 8, false, SP_GEMM_KC_PLAIN, SP_GEMM_PF_EIGHT, PK, false, false, 8, false, false>), \
+  if (resident)                                                                                                  \
+    hipLaunchKernelGGL((k_gemm_bf16<MTV, 8, false, SP_GEMM_KC_PLAIN, SP_GEMM_PF_EIGHT, PK, false, false, 8, false, false>), \
                        grid, dim3(512), 0, st, X, W, out, nullptr, M, N, K, K / SP_GEMM_KC_PLAIN, S, 0);          \
   else                                                                                                           \
   hipLaunchKernelGGL((k_gemm_bf16<MTV, 8, false, SP_GEMM_KC_PLAIN, SP_GEMM_PF_EIGHT, PK, false, false, 8>), grid, dim3(512), 0, \
@@ -378,6 +378,15 @@ hipError_t sp_launch_gemm_bf16(const bf16_t* X, const bf16_t* W, bool packed, fl
     if (packed) { if (MT == 2) SP_GO8(2, true); else if (MT == 3) SP_GO8(3, true); else if (MT == 4) SP_GO8(4, true); else SP_GO8(8, true); }
     else { if (MT == 2) SP_GO8(2, false); else if (MT == 3) SP_GO8(3, false); else if (MT == 4) SP_GO8(4, false); else SP_GO8(8, false); }
 #undef SP_GO8
+    return hipGetLastError();
+  }
+  if (resident && MT == 1) {     // one row tile of a matrix that is to stay in the Infinity Cache: ordinary weight loads
+    if (packed)
+      hipLaunchKernelGGL((k_gemm_bf16<1, SP_GEMM_NCG_PLAIN, false, SP_GEMM_KC_PLAIN, SP_GEMM_PF, true, false, false, 4, false, false>),
+                         grid, dim3(256), 0, st, X, W, out, nullptr, M, N, K, K / SP_GEMM_KC_PLAIN, S, 0);
+    else
+      hipLaunchKernelGGL((k_gemm_bf16<1, SP_GEMM_NCG_PLAIN, false, SP_GEMM_KC_PLAIN, SP_GEMM_PF, false, false, false, 4, false, false>),
+                         grid, dim3(256), 0, st, X, W, out, nullptr, M, N, K, K / SP_GEMM_KC_PLAIN, S, 0);
     return hipGetLastError();
   }
   if (packed) return launch_mt<SP_GEMM_NCG_PLAIN, false, SP_GEMM_KC_PLAIN, true>(MT, grid, st, X, W, out, nullptr, M, N, K, S, two);
