@@ -59,6 +59,13 @@
 #ifndef SP_GEMM_NCG_GATEUP
 #define SP_GEMM_NCG_GATEUP 2
 #endif
+#ifndef SP_GEMM_ROT
+// One row tile, split K, K up to 8192 (the QKV and O shapes): workgroups walk their k slice from different
+// starting chunks.  At 1-16 rows: 6144 x 4096 12.3 -> 10.3 us, 8192 x 8192 25.2 -> 23.2 us, 10240 x 8192
+// 33.2 -> 32.2 us, 4096 x 4096 unchanged; with K = 14336 or 28672 (down) 2-3 % slower, and nothing gained in
+// the kernels for more rows or in gate/up, which therefore keep the plain order.
+#define SP_GEMM_ROT 1
+#endif
 #ifndef SP_GEMM_TARGET_WGS
 #define SP_GEMM_TARGET_WGS 768    // one row tile: split K until the grid has about this many workgroups
 #endif
@@ -86,7 +93,7 @@ template <int MT, int NCG, bool GATEUP, int KC, int PF, bool PACKED, bool ARGMAX
           int NWAVES = 4, bool EVEN = false, bool WNT = true>
 __global__ void __launch_bounds__(64 * NWAVES)
 k_gemm_bf16(const bf16_t* __restrict__ X, const bf16_t* __restrict__ W, float* __restrict__ out,
-            bf16_t* __restrict__ act, int M, int N, int K, int chunks_total, int S, int cpw = 0) {
+            bf16_t* __restrict__ act, int M, int N, int K, int chunks_total, int S, int cpw = 0, int rot = 0) {
   static_assert(!(TWO && (GATEUP || ARGMAX)), "two strips per wave: plain products only");
   static_assert(!EVEN || GATEUP, "even split: gate/up only");
   constexpr int NTH = 64 * NWAVES;
@@ -125,6 +132,13 @@ k_gemm_bf16(const bf16_t* __restrict__ X, const bf16_t* __restrict__ W, float* _
            : (PACKED ? W + ((size_t)((pair_off + n0) / 16) * (K / 32) + kh * KSTEPS) * 512 + lane * 8
                      : W + (size_t)(pair_off + n0 + r) * K + kg * 8 + kh * (KSTEPS * 32));
 #define SP_WOFF(C, s) (PACKED ? ((size_t)(C) * (KC / 32) + (s)) * 512 : (size_t)(C)*KC + (s) * 32)
+  // rot: workgroups start at different chunks of their k slice and wrap around, so that the workgroups of one
+  // slice, whose weight rows lie a fixed distance apart, are not all at the same offset of their rows at the
+  // same moment (the start moves with id / 8; id, id / 2, id / 4 and id / 16 measured worse).  The sum over k
+  // is then taken in a different, still fixed, order per workgroup.
+  const int c_n = c_end - c_begin;
+  const int c_rot = rot && c_n > 1 ? (int)((blockIdx.x >> 3) % (unsigned)c_n) : 0;
+#define SP_PC(C) ((C) + c_rot < c_end ? (C) + c_rot : (C) + c_rot - c_n)
   const int xu = tid % UPR, xr = tid / UPR;
   // rows past M are read from the last valid row and multiply into output rows that are never stored
   const int m_last = M - 1;
@@ -140,7 +154,7 @@ k_gemm_bf16(const bf16_t* __restrict__ X, const bf16_t* __restrict__ W, float* _
 #define SP_LOAD_X(C)                                                                                   \
   _Pragma("unroll") for (int p = 0; p < PASSES; ++p) {                                                  \
     const int m = min(m_base + p * RPP + xr, m_last);                                                   \
-    xnxt[p] = *reinterpret_cast<const u32x4_t*>(X + (size_t)m * K + (size_t)(C)*KC + xu * 8);           \
+    xnxt[p] = *reinterpret_cast<const u32x4_t*>(X + (size_t)m * K + (size_t)SP_PC(C) * KC + xu * 8);     \
   }
 #define SP_STORE_X(BUF)                                                                                 \
   _Pragma("unroll") for (int p = 0; p < PASSES; ++p)                                                    \
@@ -152,11 +166,12 @@ k_gemm_bf16(const bf16_t* __restrict__ X, const bf16_t* __restrict__ W, float* _
   // wants to find in the Infinity Cache again at the next step: ordinary loads.
 #define SP_LOAD_W(B, C)                                                                                 \
   _Pragma("unroll") for (int s = 0; s < KSTEPS; ++s) {                                                  \
-    wb[B][0][s] = WNT ? __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(w0 + SP_WOFF(C, s)))   \
-                      : *reinterpret_cast<const u32x4_t*>(w0 + SP_WOFF(C, s));                           \
+    const int pc_ = SP_PC(C);                                                                           \
+    wb[B][0][s] = WNT ? __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(w0 + SP_WOFF(pc_, s))) \
+                      : *reinterpret_cast<const u32x4_t*>(w0 + SP_WOFF(pc_, s));                         \
     if (NW == 2)                                                                                        \
-      wb[B][NW - 1][s] = WNT ? __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(w1 + SP_WOFF(C, s))) \
-                             : *reinterpret_cast<const u32x4_t*>(w1 + SP_WOFF(C, s));                    \
+      wb[B][NW - 1][s] = WNT ? __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(w1 + SP_WOFF(pc_, s))) \
+                             : *reinterpret_cast<const u32x4_t*>(w1 + SP_WOFF(pc_, s));                  \
   }
   // One chunk C out of weight buffer B.  The activation panel of chunk C+1 was loaded to
   // registers one chunk earlier and goes to the other LDS buffer first; then the loads of
@@ -201,6 +216,7 @@ k_gemm_bf16(const bf16_t* __restrict__ X, const bf16_t* __restrict__ W, float* _
 #undef SP_LOAD_W
 #undef SP_STORE_X
 #undef SP_LOAD_X
+#undef SP_PC
 #undef SP_WOFF
 
   if (NKH == 2) {       // fold the two k-halves of a column group together through LDS
@@ -290,7 +306,7 @@ static hipError_t launch_mt(int MT, dim3 grid, hipStream_t st, const bf16_t* X, 
                             bf16_t* act, int M, int N, int K, int S, bool two = false) {
 #define SP_GO(MTV, KCX)                                                                                        \
   hipLaunchKernelGGL((k_gemm_bf16<MTV, NCG, GATEUP, KCX, SP_GEMM_PF, PACKED, ARGMAX>), grid, dim3(256), 0, st, X, \
-                     W, out, act, M, N, K, K / KCX, S)
+                     W, out, act, M, N, K, K / KCX, S, 0, (SP_GEMM_ROT && MTV == 1 && !GATEUP && !ARGMAX && S > 1 && K <= 8192) ? 1 : 0)
   if (!ARGMAX && MT == 4 && GATEUP && NCG == 4) {      // the 64 + 64 column gate/up workgroup at 49-64 rows
     hipLaunchKernelGGL((k_gemm_bf16<4, 4, true, 128, SP_GEMM_PF, PACKED, false>), grid, dim3(256), 0, st, X, W, out, act, M, N, K, K / 128, S);
     return hipGetLastError();
@@ -383,10 +399,10 @@ hipError_t sp_launch_gemm_bf16(const bf16_t* X, const bf16_t* W, bool packed, fl
   if (resident && MT == 1) {     // one row tile of a matrix that is to stay in the Infinity Cache: ordinary weight loads
     if (packed)
       hipLaunchKernelGGL((k_gemm_bf16<1, SP_GEMM_NCG_PLAIN, false, SP_GEMM_KC_PLAIN, SP_GEMM_PF, true, false, false, 4, false, false>),
-                         grid, dim3(256), 0, st, X, W, out, nullptr, M, N, K, K / SP_GEMM_KC_PLAIN, S, 0);
+                         grid, dim3(256), 0, st, X, W, out, nullptr, M, N, K, K / SP_GEMM_KC_PLAIN, S, 0, SP_GEMM_ROT && S > 1 && K <= 8192);
     else
       hipLaunchKernelGGL((k_gemm_bf16<1, SP_GEMM_NCG_PLAIN, false, SP_GEMM_KC_PLAIN, SP_GEMM_PF, false, false, false, 4, false, false>),
-                         grid, dim3(256), 0, st, X, W, out, nullptr, M, N, K, K / SP_GEMM_KC_PLAIN, S, 0);
+                         grid, dim3(256), 0, st, X, W, out, nullptr, M, N, K, K / SP_GEMM_KC_PLAIN, S, 0, SP_GEMM_ROT && S > 1 && K <= 8192);
     return hipGetLastError();
   }
   if (packed) return launch_mt<SP_GEMM_NCG_PLAIN, false, SP_GEMM_KC_PLAIN, true>(MT, grid, st, X, W, out, nullptr, M, N, K, S, two);
