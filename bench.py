@@ -59,8 +59,9 @@ def main() -> int:
     ap.add_argument("--graph", action="store_true",
                     help="capture one step into a HIP graph and time replays (the step's device work is the "
                          "same every step; the host-side argument checks then run once, at capture)")
-    ap.add_argument("--roofline-sample", type=int, default=5,
-                    help="bracket one gate/up launch in this many with HIP events (default 5)")
+    ap.add_argument("--roofline-sample", type=int, default=20,
+                    help="bracket the gate/up launches of one forward call in this many with HIP events (default 20); "
+                         "a bracketed call is launched kernel by kernel instead of replaying its graph")
     ap.add_argument("--calib-copy", action="store_true",
                     help="first run three plain 1 GiB device copies (a known-size kernel that scales rocprofv3's "
                          "FETCH_SIZE / WRITE_SIZE counters)")
