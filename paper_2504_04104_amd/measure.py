@@ -8,6 +8,7 @@
     python -m paper_2504_04104_amd.measure --run compact      # batched prune + KV compaction, scaled
     python -m paper_2504_04104_amd.measure --run verify       # last stage: output head (vocab 128256) + match
     python -m paper_2504_04104_amd.measure --run wide         # many-row projections at 512 / 574 / 1024 rows
+    python -m paper_2504_04104_amd.measure --run wide_context # the vendor library's GEMM on the same shapes (yardstick)
 
 Each run prints one JSON line.  These runs only time the HIP path (parity is the tests' job), so
 weights are drawn on the GPU (seeded N(0, 0.02)) instead of through the host generators; trees,
@@ -343,6 +344,37 @@ def run_wide(args):
     print(json.dumps({"run": "wide", "workload": "8B-shaped layer, many-row projections (k_gemm_wide)", "by_rows": out}))
 
 
+def run_wide_context(args):
+    """A yardstick for `--run wide`, not a part of the path: the vendor library's bf16 GEMM (torch.matmul) on the
+    same four shapes and row counts, random operands, timed with events.  It says what this chip sustains on
+    these shapes with somebody else's kernel; the gate/up figure is for the two products alone (no SiLU)."""
+    sh = wl.CONFIGS["C5"].shape
+    g = torch.Generator(device=DEV).manual_seed(7)
+    out = {}
+    for M in (512, 574, 1024):
+        row = {}
+        for name, N, K in (("qkv", sh.d_q + 2 * sh.d_kv, sh.d_model), ("o", sh.d_model, sh.d_q),
+                           ("gateup", 2 * sh.d_ff, sh.d_model), ("down", sh.d_model, sh.d_ff)):
+            x = torch.randn(M, K, generator=g, device=DEV, dtype=torch.float32).to(torch.bfloat16)
+            wt = (torch.randn(N, K, generator=g, device=DEV, dtype=torch.float32) * 0.02).to(torch.bfloat16)
+            for _ in range(5):
+                torch.matmul(x, wt.t())
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            torch.cuda.synchronize()
+            e0.record()
+            for _ in range(40):
+                torch.matmul(x, wt.t())
+            e1.record()
+            torch.cuda.synchronize()
+            us = e0.elapsed_time(e1) * 1e3 / 40
+            row[name] = {"us": round(us, 1), "TFLOPs": round(2.0 * M * N * K / us / 1e6, 1),
+                         "mfma_frac": round(2.0 * M * N * K / us / 1e6 / MFMA_PEAK, 4)}
+            del x, wt
+        out[M] = row
+    print(json.dumps({"run": "wide_context", "workload": "vendor library bf16 GEMM (torch.matmul) on the shapes of --run wide",
+                      "by_rows": out}))
+
+
 def run_verify(args):
     """Last-stage step on the 8B-shaped stage: forward of 64 nodes, output head over a vocabulary of
     128256 with the top-1 token per node, match of the root's successor, accept, compaction."""
@@ -423,12 +455,12 @@ def run_verify(args):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--page-slots", type=int, default=0, help="c5: keep the cache in pages of this many slots")
-    ap.add_argument("--run", required=True, choices=["sweep", "c3", "c4", "c5", "compact", "verify", "wide"])
+    ap.add_argument("--run", required=True, choices=["sweep", "c3", "c4", "c5", "compact", "verify", "wide", "wide_context"])
     ap.add_argument("--steps", type=int, default=0)
     args = ap.parse_args()
     # a stream of our own: the forward call replays HIP graphs of its launches only on a stream that can be captured
     torch.cuda.set_stream(torch.cuda.Stream(device=DEV))
-    {"sweep": run_sweep, "c3": run_c3, "c4": run_c4, "c5": run_c5, "compact": run_compact, "verify": run_verify, "wide": run_wide}[args.run](args)
+    {"sweep": run_sweep, "c3": run_c3, "c4": run_c4, "c5": run_c5, "compact": run_compact, "verify": run_verify, "wide": run_wide, "wide_context": run_wide_context}[args.run](args)
 
 
 if __name__ == "__main__":
