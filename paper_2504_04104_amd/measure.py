@@ -148,7 +148,7 @@ def run_c3(args):
 def run_c4(args):
     """Streaming: per step insert 1-8 nodes, forward them, prune, compact; prefix 32768."""
     w = wl.CONFIGS["C4"]
-    sh, P = w.shape, w.prefix_len
+    sh, P = w.shape, args.prefix or w.prefix_len
     layers = gpu_layers(sh, w.seed)
     steps = wl.streaming_schedule(w.seed, args.steps or 512, max_new=8, cap=256, p_accept=0.7)
     cap = P + 256 + sum(1 for s in steps if s.prune and s.prune.mode == wl.ACCEPT) * 9 + 64
@@ -186,7 +186,7 @@ def run_c4(args):
     P_end = stage.request_info(0)[0]
     kv_bytes = ((P + P_end) / 2 + 128) * sh.kv_bytes_per_token_per_layer     # per launch, average context
     att_us = ms * 1e3 / cnt
-    res = {"run": "c4", "workload": "streaming, 8B-shaped 4-layer stage, prefix 32768, %d steps" % len(steps),
+    res = {"run": "c4", "workload": "streaming, 8B-shaped 4-layer stage, prefix %d, %d steps" % (P, len(steps)),
            "ms_per_step": round(t / len(steps) * 1e3, 4), "tree_tokens_per_s": round(tokens / t, 1),
            "tokens": tokens, "attention_us_per_launch": round(att_us, 1),
            "attention_GBps": round(kv_bytes / (att_us * 1e-6) / 1e9, 1),
@@ -457,6 +457,7 @@ def main():
     ap.add_argument("--page-slots", type=int, default=0, help="c5: keep the cache in pages of this many slots")
     ap.add_argument("--run", required=True, choices=["sweep", "c3", "c4", "c5", "compact", "verify", "wide", "wide_context"])
     ap.add_argument("--steps", type=int, default=0)
+    ap.add_argument("--prefix", type=int, default=0, help="c4: committed context length (default: the workload's 32768)")
     args = ap.parse_args()
     # a stream of our own: the forward call replays HIP graphs of its launches only on a stream that can be captured
     torch.cuda.set_stream(torch.cuda.Stream(device=DEV))
