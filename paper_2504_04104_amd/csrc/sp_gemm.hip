@@ -60,10 +60,11 @@
 #define SP_GEMM_NCG_GATEUP 2
 #endif
 #ifndef SP_GEMM_ROT
-// One row tile, split K, K up to 8192 (the QKV and O shapes): workgroups walk their k slice from different
-// starting chunks.  At 1-16 rows: 6144 x 4096 12.3 -> 10.3 us, 8192 x 8192 25.2 -> 23.2 us, 10240 x 8192
-// 33.2 -> 32.2 us, 4096 x 4096 unchanged; with K = 14336 or 28672 (down) 2-3 % slower, and nothing gained in
-// the kernels for more rows or in gate/up, which therefore keep the plain order.
+// Plain products split over k, K up to 8192 (the QKV and O shapes): workgroups walk their k slice from
+// different starting chunks.  At 1-16 rows: 6144 x 4096 12.3 -> 10.3 us, 8192 x 8192 25.2 -> 23.2 us,
+// 10240 x 8192 33.2 -> 32.2 us, 4096 x 4096 unchanged; at 32 and 64 rows 8192 x 8192 29.2 -> 24.8 and
+// 31.0 -> 27.9 us, the other shapes within 1 %; with K = 14336 or 28672 (down) 2-3 % slower at 1-16 rows,
+// and nothing gained in gate/up: those keep the plain order.
 #define SP_GEMM_ROT 1
 #endif
 #ifndef SP_GEMM_TARGET_WGS
@@ -301,12 +302,15 @@ k_gemm_bf16(const bf16_t* __restrict__ X, const bf16_t* __restrict__ W, float* _
 // always with the 128-wide chunk so that the two LDS panels fit), each block streaming the weights once.
 // More than 64 rows (MT = 8): workgroups of twice the columns -- two strips per wave for the plain products,
 // four column groups instead of two for gate/up -- so that panel and weights stay one to one.
+// staggered starting chunks: plain products that are split over k, K up to 8192 (see SP_GEMM_ROT)
+static inline int rot_for(int S, int K) { return (SP_GEMM_ROT && S > 1 && K <= 8192) ? 1 : 0; }
+
 template <int NCG, bool GATEUP, int KCV, bool PACKED, bool ARGMAX = false>
 static hipError_t launch_mt(int MT, dim3 grid, hipStream_t st, const bf16_t* X, const bf16_t* W, float* out,
                             bf16_t* act, int M, int N, int K, int S, bool two = false) {
 #define SP_GO(MTV, KCX)                                                                                        \
   hipLaunchKernelGGL((k_gemm_bf16<MTV, NCG, GATEUP, KCX, SP_GEMM_PF, PACKED, ARGMAX>), grid, dim3(256), 0, st, X, \
-                     W, out, act, M, N, K, K / KCX, S, 0, (SP_GEMM_ROT && MTV == 1 && !GATEUP && !ARGMAX && S > 1 && K <= 8192) ? 1 : 0)
+                     W, out, act, M, N, K, K / KCX, S, 0, (!GATEUP && !ARGMAX) ? rot_for(S, K) : 0)
   if (!ARGMAX && MT == 4 && GATEUP && NCG == 4) {      // the 64 + 64 column gate/up workgroup at 49-64 rows
     hipLaunchKernelGGL((k_gemm_bf16<4, 4, true, 128, SP_GEMM_PF, PACKED, false>), grid, dim3(256), 0, st, X, W, out, act, M, N, K, K / 128, S);
     return hipGetLastError();
@@ -324,7 +328,7 @@ static hipError_t launch_mt(int MT, dim3 grid, hipStream_t st, const bf16_t* X, 
       else if (GATEUP || !two) SP_GO(8, 128);
       else
         hipLaunchKernelGGL((k_gemm_bf16<8, 4, false, 128, SP_GEMM_PF, PACKED, false, true>), grid, dim3(256), 0, st, X, W,
-                           out, act, M, N, K, K / 128, S);
+                           out, act, M, N, K, K / 128, S, 0, rot_for(S, K));
       break;
   }
 #undef SP_GO
@@ -377,7 +381,7 @@ hipError_t sp_launch_gemm_bf16(const bf16_t* X, const bf16_t* W, bool packed, fl
   if (six) {
 #define SP_GO6(MTV, PK)                                                                                          \
   hipLaunchKernelGGL((k_gemm_bf16<MTV, 6, false, SP_GEMM_KC_PLAIN, SP_GEMM_PF, PK, false, false, 6>), grid, dim3(384), 0, \
-                     st, X, W, out, nullptr, M, N, K, K / SP_GEMM_KC_PLAIN, S, 0)
+                     st, X, W, out, nullptr, M, N, K, K / SP_GEMM_KC_PLAIN, S, 0, rot_for(S, K))
     if (packed) { if (MT == 2) SP_GO6(2, true); else if (MT == 3) SP_GO6(3, true); else SP_GO6(4, true); }
     else { if (MT == 2) SP_GO6(2, false); else if (MT == 3) SP_GO6(3, false); else SP_GO6(4, false); }
 #undef SP_GO6
@@ -387,10 +391,10 @@ hipError_t sp_launch_gemm_bf16(const bf16_t* X, const bf16_t* W, bool packed, fl
 #define SP_GO8(MTV, PK)                                                                                          \
   if (resident)                                                                                                  \
     hipLaunchKernelGGL((k_gemm_bf16<MTV, 8, false, SP_GEMM_KC_PLAIN, SP_GEMM_PF_EIGHT, PK, false, false, 8, false, false>), \
-                       grid, dim3(512), 0, st, X, W, out, nullptr, M, N, K, K / SP_GEMM_KC_PLAIN, S, 0);          \
+                       grid, dim3(512), 0, st, X, W, out, nullptr, M, N, K, K / SP_GEMM_KC_PLAIN, S, 0, rot_for(S, K)); \
   else                                                                                                           \
   hipLaunchKernelGGL((k_gemm_bf16<MTV, 8, false, SP_GEMM_KC_PLAIN, SP_GEMM_PF_EIGHT, PK, false, false, 8>), grid, dim3(512), 0, \
-                     st, X, W, out, nullptr, M, N, K, K / SP_GEMM_KC_PLAIN, S, 0)
+                     st, X, W, out, nullptr, M, N, K, K / SP_GEMM_KC_PLAIN, S, 0, rot_for(S, K))
     if (packed) { if (MT == 2) SP_GO8(2, true); else if (MT == 3) SP_GO8(3, true); else if (MT == 4) SP_GO8(4, true); else SP_GO8(8, true); }
     else { if (MT == 2) SP_GO8(2, false); else if (MT == 3) SP_GO8(3, false); else if (MT == 4) SP_GO8(4, false); else SP_GO8(8, false); }
 #undef SP_GO8
@@ -399,10 +403,10 @@ hipError_t sp_launch_gemm_bf16(const bf16_t* X, const bf16_t* W, bool packed, fl
   if (resident && MT == 1) {     // one row tile of a matrix that is to stay in the Infinity Cache: ordinary weight loads
     if (packed)
       hipLaunchKernelGGL((k_gemm_bf16<1, SP_GEMM_NCG_PLAIN, false, SP_GEMM_KC_PLAIN, SP_GEMM_PF, true, false, false, 4, false, false>),
-                         grid, dim3(256), 0, st, X, W, out, nullptr, M, N, K, K / SP_GEMM_KC_PLAIN, S, 0, SP_GEMM_ROT && S > 1 && K <= 8192);
+                         grid, dim3(256), 0, st, X, W, out, nullptr, M, N, K, K / SP_GEMM_KC_PLAIN, S, 0, rot_for(S, K));
     else
       hipLaunchKernelGGL((k_gemm_bf16<1, SP_GEMM_NCG_PLAIN, false, SP_GEMM_KC_PLAIN, SP_GEMM_PF, false, false, false, 4, false, false>),
-                         grid, dim3(256), 0, st, X, W, out, nullptr, M, N, K, K / SP_GEMM_KC_PLAIN, S, 0, SP_GEMM_ROT && S > 1 && K <= 8192);
+                         grid, dim3(256), 0, st, X, W, out, nullptr, M, N, K, K / SP_GEMM_KC_PLAIN, S, 0, rot_for(S, K));
     return hipGetLastError();
   }
   if (packed) return launch_mt<SP_GEMM_NCG_PLAIN, false, SP_GEMM_KC_PLAIN, true>(MT, grid, st, X, W, out, nullptr, M, N, K, S, two);
