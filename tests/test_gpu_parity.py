@@ -876,13 +876,16 @@ def test_c2_full_size_in_bench_configuration():
     pair.close()
 
 
-@pytest.mark.parametrize("n_nodes,flags", [(128, sp.SP_FLAG_PACKED_WEIGHTS), (60, 0), (100, 0)],
-                         ids=["128_packed", "60_rowmajor", "100_rowmajor"])
+@pytest.mark.parametrize("n_nodes,flags", [(128, sp.SP_FLAG_PACKED_WEIGHTS), (60, 0), (100, 0),
+                                           (8, sp.SP_FLAG_PACKED_WEIGHTS), (40, sp.SP_FLAG_PACKED_WEIGHTS), (12, 0)],
+                         ids=["128_packed", "60_rowmajor", "100_rowmajor", "8_packed", "40_packed", "12_rowmajor"])
 def test_c3_dimensions_one_layer(n_nodes, flags):
     """One layer at the 70B shape (d=8192, 64/8 heads, FFN 28672) with config 3's 128-node tree and
     prefix 4096: a 128-row block per projection (two strips of 16 weight rows per wave, 64 + 64 gate/up
     columns per workgroup), 8 query heads per KV head; and with 60 nodes, where the gate/up projection
     takes the same wide workgroups with four row tiles, the last one ragged; both weight layouts.
+    With 8, 12 and 40 nodes the QKV and O products (K = 8192) run as one or three row tiles whose
+    workgroups walk their k slices from staggered starting chunks (slices of 10-11 and 16 chunks).
     (All ten layers: the full-depth test.)"""
     w = wl.CONFIGS["C3"]
     shape = wl.scaled(w.shape, n_layers=1)
