@@ -384,6 +384,49 @@ def test_ragged_batch_mini(page_slots):
     pair.close()
 
 
+@pytest.mark.parametrize("page_slots", [0, 32], ids=["contiguous", "pages32"])
+def test_ragged_batch_of_64_requests(page_slots):
+    """The largest batch one call takes (64 requests): contexts of 1-120 tokens, trees of 1-3 nodes, one forward
+    call, a batched prune and compaction of every request, a batched insert and a second forward call; one
+    request more than the maximum is refused before anything is launched."""
+    shape = MINI_GQA4
+    reqs = wl.batch_requests(23, n_req=64, p_lo=1, p_hi=120, t_lo=1, t_hi=3, max_levels=3, name=("batch64",))
+    pair = Pair(shape, 23, {r.req: r.prefix_len for r in reqs}, max_batch_nodes=256, page_slots=page_slots)
+    for r in reqs:
+        pair.insert(r.req, r.parents)
+    ids = [r.req for r in reqs]
+    counts = [len(r.parents) for r in reqs]
+    x = wl.hidden_rows(shape, 23, ("b64",), sum(counts))
+    y, ref = pair.forward(ids, [0] * 64, counts, x)
+    e = rel_err(y, ref)
+    say("64 requests, first call rel err", e, "rows", sum(counts))
+    assert e <= TOL["bf16"]
+    one_more = torch.zeros(sum(counts) + 1, shape.d_model, dtype=pair.gpu.tdtype, device="cuda")
+    with pytest.raises(sp.SpError):                 # the library's own check: 65 requests in one call
+        pair.gpu.stage_forward(ids + [0], [0] * 65, counts + [1], one_more)
+    # every request accepts a child of its root (node 0 is one: parents start with -1) or drops it
+    modes = [sp.SP_ACCEPT if r.req % 3 else sp.SP_DROP for r in reqs]
+    nodes = [0] * 64
+    live, commit = pair.gpu.tree_prune_batch(ids, modes, nodes)
+    pair.gpu.kv_compact_batch(ids)
+    for i, r in enumerate(reqs):
+        pr = pair.ora.accept(r.req, 0) if modes[i] == sp.SP_ACCEPT else pair.ora.drop(r.req, 0)
+        assert commit[i] == pr.n_commit and live[i] == pair.ora.req[r.req].tree.n - 1
+        pair.check_tables(r.req)
+    new = [[-1, -1] if r.req % 2 else [-1] for r in reqs]
+    firsts = pair.insert_batch(ids, new, [[7 * r.req + k for k in range(len(p))] for r, p in zip(reqs, new)],
+                               [[0.5] * len(p) for p in new])
+    counts = [len(p) for p in new]
+    x = wl.hidden_rows(shape, 23, ("b64", 1), sum(counts))
+    y, ref = pair.forward(ids, firsts, counts, x)
+    e = rel_err(y, ref)
+    say("64 requests, second call rel err", e)
+    assert e <= TOL["bf16"]
+    for r in reqs:
+        pair.check_kv(r.req, TOL["bf16"])
+    pair.close()
+
+
 WIDE_BATCHES = {
     # rows 387: one block of 256 and a ragged block of 131
     "387": {0: (150, 333), 1: (97, 64), 2: (140, 200)},          # request: (nodes, prefix)
