@@ -12,7 +12,7 @@
 // bit is set in the node's ancestor mask.
 //
 // MFMA use (v_mfma_f32_16x16x32_bf16, D[4*(l/16)+i][l%16]):
-//   S^T = K Q^T : A = 16 slots x 32 d (straight from global, 16 B per lane),
+//   S^T = K Q^T : A = 16 slots x 32 d (16 B per lane, read from an LDS copy of the K tile),
 //                 B = 32 d x 16 query rows (registers, loaded once).
 //   O^T = V^T P^T: B = P^T is exactly the S^T registers of two 16-slot tiles (the
 //                 contraction order over the 32 slots is free, so no shuffle is
@@ -37,13 +37,19 @@ struct AttnArgs {
 
 // STREAM: every request of the call has a single block of query rows, so each K/V row is read by one workgroup
 // only; the loads then carry the non-temporal hint and the rows pass through the caches without staying.
+// The K rows take the same way as the V rows: loaded as whole 256-byte rows (a load instruction covers four rows)
+// into an LDS tile of the wave, from which the MFMA A fragments are read.  Loaded straight from global memory in
+// A-fragment order an instruction would cover 64 bytes of each of 16 rows and every 128-byte line would be asked
+// for twice: a workgroup alone on its CU streams 8 KB tiles at 48 (non-temporal) or 84 GB/s (ordinary loads) in
+// whole rows against 26 or 34 GB/s in quarter rows, and the ragged batch's attention went from 78 to 68 us.
 template <int QT, bool PAGED, bool STREAM>
 __global__ void __launch_bounds__(64 * AW) k_attn_bf16(AttnArgs a) {
   const AttnPlan& plan = *a.plan;
-  // V tiles of the eight waves; the same bytes later carry the states being folded
+  // V (and K) tiles of the eight waves; the same bytes later carry the states being folded
   // (eight waves x QT x 8 d-tiles x 64 lanes x 16 B = QT * 64 KB).
   constexpr int FOLD_BYTES = AW * QT * 8 * 64 * 16;
-  __shared__ __attribute__((aligned(16))) char s_v[AW * VT_BYTES > FOLD_BYTES ? AW * VT_BYTES : FOLD_BYTES];
+  constexpr int TILE_BYTES = 2 * AW * VT_BYTES;
+  __shared__ __attribute__((aligned(16))) char s_v[TILE_BYTES > FOLD_BYTES ? TILE_BYTES : FOLD_BYTES];
   __shared__ float s_m[AW][QT * 16];
   __shared__ float s_l[AW][QT * 16];
 
@@ -95,31 +101,25 @@ __global__ void __launch_bounds__(64 * AW) k_attn_bf16(AttnArgs a) {
 #define SP_PHYS(slot, pg) (PAGED ? (((slot) < span ? (pg) : page0) << pg_sh | ((slot) < span ? ((slot) & pg_mask) : 0)) \
                                  : ((slot) < span ? (slot) : 0))
 
-  // Loads of one 32-slot tile: K as MFMA A fragments (row l15 of each 16-slot half, 16 B at
-  // d = s*32 + kg*8), V as plain 16-byte pieces (row i*4+kg, piece l15).  Slots past the
-  // request's data are read from slot 0 (always valid) and masked later.
+  // Loads of one 32-slot tile: K and V as plain 16-byte pieces (row i*4+kg, piece l15).  Slots past
+  // the request's data are read from slot 0 (always valid) and masked later.
 #define SP_LOAD_TILE(S0)                                                                           \
   {                                                                                                \
     const int pg_ = PAGED ? pt[((S0) < span ? (S0) : 0) >> pg_sh] : 0;                             \
-    _Pragma("unroll") for (int t2 = 0; t2 < 2; ++t2) {                                             \
-      int slot = (S0) + t2 * 16 + l15;                                                             \
-      slot = SP_PHYS(slot, pg_);                                                                   \
-      const char* kp = kplane + (size_t)slot * 256 + kg * 16;                                      \
-      _Pragma("unroll") for (int s = 0; s < 4; ++s)                                                \
-          kreg[t2][s] = STREAM ? __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(kp + s * 64)) \
-                               : *reinterpret_cast<const u32x4_t*>(kp + s * 64);                   \
-    }                                                                                              \
     _Pragma("unroll") for (int i = 0; i < 8; ++i) {                                                \
       int slot = (S0) + i * 4 + kg;                                                                \
       slot = SP_PHYS(slot, pg_);                                                                   \
       const u32x4_t* vp_ = reinterpret_cast<const u32x4_t*>(vplane + (size_t)slot * 256 + l15 * 16); \
       vreg[i] = STREAM ? __builtin_nontemporal_load(vp_) : *vp_;                                   \
+      const u32x4_t* kp_ = reinterpret_cast<const u32x4_t*>(kplane + (size_t)slot * 256 + l15 * 16); \
+      kreg[i >> 2][i & 3] = STREAM ? __builtin_nontemporal_load(kp_) : *kp_;                       \
     }                                                                                              \
   }
 
   // the first tile's loads go out before anything else that has to wait
   u32x4_t kreg[2][4], vreg[8];
   char* vt = s_v + wave * VT_BYTES;
+  char* kt = s_v + (AW + wave) * VT_BYTES;         // this wave's K tile, rows as in the V tile
   SP_LOAD_TILE(w0 < w1 ? w0 : span)
 
   // ---- query fragments and ancestor masks of this lane's query row per tile ------
@@ -167,6 +167,15 @@ __global__ void __launch_bounds__(64 * AW) k_attn_bf16(AttnArgs a) {
     __builtin_amdgcn_wave_barrier();
 #pragma unroll
     for (int i = 0; i < 8; ++i) *reinterpret_cast<u32x4_t*>(vt + (i * 4 + kg) * VS + l15 * 16) = vreg[i];
+    // K rows to the wave's K tile and back as A fragments: row l15 of each 16-slot half, 16 B at d = s*32 + kg*8
+#pragma unroll
+    for (int i = 0; i < 8; ++i) *reinterpret_cast<u32x4_t*>(kt + (i * 4 + kg) * VS + l15 * 16) = kreg[i >> 2][i & 3];
+    __builtin_amdgcn_wave_barrier();
+#pragma unroll
+    for (int t2 = 0; t2 < 2; ++t2)
+#pragma unroll
+      for (int s = 0; s < 4; ++s)
+        kreg[t2][s] = *reinterpret_cast<const u32x4_t*>(kt + (t2 * 16 + l15) * VS + s * 64 + kg * 16);
     // scores of every query tile first, so that the K registers are free for the next loads
     f32x4_t sacc[QT][2];
 #pragma unroll
