@@ -171,28 +171,27 @@ __global__ void __launch_bounds__(64 * AW) k_attn_bf16(AttnArgs a) {
 #pragma unroll
     for (int i = 0; i < 8; ++i) *reinterpret_cast<u32x4_t*>(kt + (i * 4 + kg) * VS + l15 * 16) = kreg[i >> 2][i & 3];
     __builtin_amdgcn_wave_barrier();
-#pragma unroll
-    for (int t2 = 0; t2 < 2; ++t2)
-#pragma unroll
-      for (int s = 0; s < 4; ++s)
-        kreg[t2][s] = *reinterpret_cast<const u32x4_t*>(kt + (t2 * 16 + l15) * VS + s * 64 + kg * 16);
-    // scores of every query tile first, so that the K registers are free for the next loads
-    f32x4_t sacc[QT][2];
-#pragma unroll
-    for (int t = 0; t < QT; ++t)
-#pragma unroll
-      for (int t2 = 0; t2 < 2; ++t2) {
-        sacc[t][t2] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int s = 0; s < 4; ++s)
-          sacc[t][t2] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(*reinterpret_cast<const bf16x8_t*>(&kreg[t2][s]),
-                                                                *reinterpret_cast<const bf16x8_t*>(&qf[t][s]),
-                                                                sacc[t][t2], 0, 0, 0);
-      }
+    // the tile is in LDS: the next tile's loads go out now and fly during everything below
     {
       const int nxt = (s0 + 32 < w1) ? s0 + 32 : span;     // span: every slot clamps to 0
       SP_LOAD_TILE(nxt)
     }
+    f32x4_t sacc[QT][2];
+#pragma unroll
+    for (int t = 0; t < QT; ++t)
+#pragma unroll
+      for (int t2 = 0; t2 < 2; ++t2) sacc[t][t2] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int t2 = 0; t2 < 2; ++t2)
+#pragma unroll
+      for (int s = 0; s < 4; ++s) {
+        const u32x4_t kf = *reinterpret_cast<const u32x4_t*>(kt + (t2 * 16 + l15) * VS + s * 64 + kg * 16);
+#pragma unroll
+        for (int t = 0; t < QT; ++t)
+          sacc[t][t2] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(*reinterpret_cast<const bf16x8_t*>(&kf),
+                                                                *reinterpret_cast<const bf16x8_t*>(&qf[t][s]),
+                                                                sacc[t][t2], 0, 0, 0);
+      }
 
     const bool tail = s0 + 32 > P || s0 + 32 > w1;   // tile touches the tree region or the run's end
     uint32_t pb[QT][4];
