@@ -161,9 +161,9 @@ __global__ void __launch_bounds__(64 * AW) k_attn_bf16(AttnArgs a) {
   for (int t = 0; t < QT; ++t) negm[t] = 0.f;
 
   for (int s0 = w0; s0 < w1; s0 += 32) {
-    // V tile -> LDS and the K fragments into the score MFMAs; then the next tile's loads
-    // are issued so that they fly during the softmax and the PV product (the tile after
-    // the last one re-reads slot 0 and is discarded).
+    // K and V tiles -> LDS; then the next tile's loads are issued, so that they fly during
+    // the score products, the softmax and the PV product (the tile after the last one
+    // re-reads slot 0 and is discarded).
     __builtin_amdgcn_wave_barrier();
 #pragma unroll
     for (int i = 0; i < 8; ++i) *reinterpret_cast<u32x4_t*>(vt + (i * 4 + kg) * VS + l15 * 16) = vreg[i];
