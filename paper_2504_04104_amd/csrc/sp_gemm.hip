@@ -59,6 +59,12 @@
 #ifndef SP_GEMM_NCG_GATEUP
 #define SP_GEMM_NCG_GATEUP 2
 #endif
+#ifndef SP_GEMM_ROWSTORE
+#define SP_GEMM_ROWSTORE 1        // split-K partial sums written in whole rows through LDS ...
+#endif
+#ifndef SP_GEMM_ROWSTORE_MIN_MT
+#define SP_GEMM_ROWSTORE_MIN_MT 8 // ... from this many row tiles
+#endif
 #ifndef SP_GEMM_ROT
 // Plain products split over k, K up to 8192 (the QKV and O shapes): workgroups walk their k slice from
 // different starting chunks.  At 1-16 rows: 6144 x 4096 12.3 -> 10.3 us, 8192 x 8192 25.2 -> 23.2 us,
@@ -271,6 +277,32 @@ k_gemm_bf16(const bf16_t* __restrict__ X, const bf16_t* __restrict__ W, float* _
       float* o = out + ((size_t)m * gridDim.x + blockIdx.x) * 2;
       o[0] = bv;
       reinterpret_cast<int*>(o)[1] = bi;
+    }
+    return;
+  }
+  if (SP_GEMM_ROWSTORE && !GATEUP && MT >= SP_GEMM_ROWSTORE_MIN_MT) {
+    // Partial sums leave in whole rows of the workgroup's columns: the waves' 16-column pieces are put together in
+    // LDS (the panels are no longer read: every wave has passed the barrier that ends its last chunk), and a store
+    // instruction then writes 1 KB of consecutive addresses instead of 64 bytes in each of 16 rows.
+    static_assert(NKH == 1 || GATEUP, "plain products: one wave per column group");
+    constexpr int WCOLS = 16 * NCG * (TWO ? 2 : 1);
+    constexpr int LSF = WCOLS + 4;                        // floats per LDS row
+    static_assert(ROWS * LSF * 4 <= (int)sizeof(lds), "the row tile fits the panels' LDS");
+    float* tile = reinterpret_cast<float*>(&lds[0][0]);
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+      for (int a = 0; a < NW; ++a)
+        *reinterpret_cast<f32x4_t*>(tile + (mt * 16 + r) * LSF + a * (16 * NCG) + cg * 16 + 4 * kg) = acc[a][mt];
+    __syncthreads();
+    constexpr int UPRW = WCOLS / 4;                       // 16-byte units per row
+    const int col0 = blockIdx.x * WCOLS;
+    for (int idx = tid; idx < ROWS * UPRW; idx += NTH) {
+      const int row = idx / UPRW, u = idx - row * UPRW;
+      const int m = m_base + row;
+      if (m < M)
+        *reinterpret_cast<f32x4_t*>(out + ((size_t)blockIdx.y * M + m) * N + col0 + u * 4) =
+            *reinterpret_cast<const f32x4_t*>(tile + row * LSF + u * 4);
     }
     return;
   }
